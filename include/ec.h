@@ -1,0 +1,192 @@
+/*
+ * ec.h - C ABI of the EntropyCache denoising step for AMD MI355X (gfx950).
+ *
+ * One context = one model (borrowed device weights) + one generation in flight: prompt, masked
+ * generation slots, per-layer KV cache, decode history.  A denoising step is either FULL (every
+ * position recomputes Q/K/V and overwrites the cache) or PARTIAL (only the masked positions of
+ * the current block plus the recently decoded tokens recompute Q/K/V, scatter their K/V into the
+ * cache and attend bidirectionally against the whole cached context).  After the forward pass
+ * the step decodes tokens from the block's logits, evaluates the maximum entropy of the newly
+ * decoded tokens and sets the flag that chooses the next step's mode.
+ *
+ * Paper passages: Method section ("Entropy-based skipping", Eq. 1; "Recent token
+ * recomputation", Eq. 2, Eq. 3, tau_R, R), Algorithm 1, and the appendix "Full EntropyCache
+ * algorithm".
+ *
+ * Conventions
+ *  - Every call returns EC_OK or a negative error code; it never throws or aborts.  Outputs are
+ *    written only on success.  ec_last_error() gives a message for the last failure of a context
+ *    (or of ec_init when passed NULL).
+ *  - Pointers marked DEVICE are device addresses on the current HIP device; HOST are host
+ *    addresses.  Weights and workspace are BORROWED: the caller allocates them (e.g. through
+ *    PyTorch), keeps them alive and unchanged while the context lives, and frees them afterwards.
+ *    The context owns only small host-side state and one pinned host buffer.
+ *  - All device work is enqueued on the HIP stream given to ec_init.  ec_step synchronises that
+ *    stream once, for the read-back of its small result.
+ *  - A context is not thread-safe.  batch must be 1.
+ *  - All matrices are row-major [out_features, in_features] in the model's storage type
+ *    (float32 or bfloat16).  Norm gains are vectors of the same type.
+ */
+#ifndef EC_H
+#define EC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define EC_MAX_N 32        /* most tokens one step may unmask (tokens_per_step <= EC_MAX_N)   */
+#define EC_MAX_BLOCK 128   /* largest block (window) size                                     */
+
+typedef struct ec_ctx ec_ctx; /* opaque */
+
+enum { EC_F32 = 0, EC_BF16 = 1 };
+/* EC_AUTO: follow the flag set by the previous step; the first step is always FULL. */
+enum { EC_FULL = 0, EC_PARTIAL = 1, EC_AUTO = 2 };
+enum {
+  EC_OK = 0,
+  EC_ERR_ARG = -1,       /* null pointer, bad enum value, bad size                              */
+  EC_ERR_CONFIG = -2,    /* model / decode configuration outside what the kernels support       */
+  EC_ERR_WORKSPACE = -3, /* workspace missing, misaligned or smaller than ec_workspace_bytes()  */
+  EC_ERR_STATE = -4,     /* PARTIAL before any FULL step; step after the generation is done     */
+  EC_ERR_HIP = -5        /* a HIP runtime call failed                                           */
+};
+
+/* Model shape.  "Bidirectional Llama-style": pre-norm blocks, RMSNorm, rotate-half RoPE on
+ * absolute positions, grouped-query attention without mask, SwiGLU MLP, no biases, untied
+ * embedding and LM head.  logit_scale multiplies the LM-head output (1.0 = the model as is). */
+typedef struct {
+  int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab, mask_id;
+  float rms_eps, rope_base, logit_scale;
+  int32_t dtype; /* EC_F32 | EC_BF16: storage type of weights, activations fed to GEMMs, KV cache */
+} ec_model_cfg;
+
+/* DEVICE pointers, BORROWED.  Per-layer entries are HOST arrays of n_layers DEVICE pointers. */
+typedef struct {
+  const void *tok_emb;          /* [vocab, d_model]                 */
+  const void *lm_head;          /* [vocab, d_model]                 */
+  const void *final_norm;       /* [d_model]                        */
+  const void *const *attn_norm; /* [L] of [d_model]                 */
+  const void *const *wq;        /* [L] of [n_heads*head_dim, d_model]    */
+  const void *const *wk;        /* [L] of [n_kv_heads*head_dim, d_model] */
+  const void *const *wv;        /* [L] of [n_kv_heads*head_dim, d_model] */
+  const void *const *wo;        /* [L] of [d_model, n_heads*head_dim]    */
+  const void *const *mlp_norm;  /* [L] of [d_model]                 */
+  const void *const *w_gate;    /* [L] of [d_ffn, d_model]          */
+  const void *const *w_up;      /* [L] of [d_ffn, d_model]          */
+  const void *const *w_down;    /* [L] of [d_model, d_ffn]          */
+} ec_weights;
+
+/* Decoding parameters: generation length N, block (window) size w, recent-token budget k,
+ * tokens unmasked per step n, entropy threshold tau in nats (Algorithm 1 inputs). */
+typedef struct {
+  int32_t batch, gen_len, block, k_recent, tokens_per_step;
+  float tau;
+} ec_decode_cfg;
+
+/* What one step did.  positions/tokens/entropy/confidence list the step's OWN decode() choice
+ * (n_unmasked entries, most confident first); max_entropy is E of that choice (Eq. 1);
+ * next_mode is EC_PARTIAL iff max_entropy <= tau.  Under ec_step_forced the caller's tokens are
+ * committed instead, but these fields still report the step's own choice. */
+typedef struct {
+  int32_t n_unmasked;
+  int32_t done;         /* 1 when no masked position is left after this step                   */
+  int32_t mode_run;     /* EC_FULL | EC_PARTIAL: what this step executed                        */
+  int32_t next_mode;    /* what EC_AUTO will execute next                                       */
+  int32_t n_query_rows; /* |S|: rows that recomputed Q/K/V in this step                         */
+  int32_t step_index;   /* t of this step, starting at 1                                        */
+  int32_t n_block_rows; /* |M^t|: masked rows of the current block = rows that got logits       */
+  int32_t n_recent_next;/* |R^{t+1}|                                                            */
+  float max_entropy;
+  int32_t positions[EC_MAX_N];
+  int32_t tokens[EC_MAX_N];
+  float entropy[EC_MAX_N];
+  float confidence[EC_MAX_N];
+} ec_step_result;
+
+typedef struct {
+  int32_t steps, full_steps, partial_steps, tokens;
+  int64_t rows_recomputed; /* sum of |S| over steps; recompute ratio = rows / (steps * T)       */
+  double ms_total;         /* host wall-clock of the whole generation                           */
+} ec_gen_stats;
+
+/* Kernel classes for ec_profile_*: names follow the paper's wall-clock breakdown (attention
+ * with rotary embeddings, feed-forward, KV-cache update, decision, remaining operations). */
+enum {
+  EC_K_EMBED = 0, EC_K_NORM, EC_K_QKV, EC_K_ROPE_KV, EC_K_ATTN, EC_K_OPROJ, EC_K_GATEUP,
+  EC_K_SWIGLU, EC_K_DOWN, EC_K_LMHEAD, EC_K_VOCAB_REDUCE, EC_K_DECIDE, EC_K_COUNT
+};
+typedef struct {
+  double ms[EC_K_COUNT];        /* accumulated device time per kernel class, from HIP events    */
+  int64_t launches[EC_K_COUNT]; /* accumulated launch count per class                           */
+  int64_t steps;
+} ec_profile;
+
+/* What ec_debug_read copies to the host. */
+enum {
+  EC_DBG_LOGITS = 0, /* float32 [n_block_rows, vocab] of the last step (already scaled)        */
+  EC_DBG_KCACHE,     /* layer's keys, post-RoPE, storage type, [T, n_kv_heads, head_dim]       */
+  EC_DBG_VCACHE,     /* layer's values, same layout                                            */
+  EC_DBG_X,          /* int32 [T] current token ids                                            */
+  EC_DBG_MASKED,     /* uint8 [T] 1 = still masked                                             */
+  EC_DBG_HIST,       /* int32 [gen_len] decode step per slot, INT32_MIN = never                */
+  EC_DBG_ROWS,       /* int32 [n]: row set the NEXT partial step would use (M u R), ascending  */
+  EC_DBG_ROW_STATS   /* float32 [n_block_rows, 4]: token id (as float), confidence, entropy, max logit of the last step's rows */
+};
+
+/* Bytes of DEVICE workspace ec_init needs for this model, decode setup and prompt length
+ * (KV cache, activations, state, and for bfloat16 a re-tiled copy of the matrices).
+ * Returns 0 on invalid arguments. */
+size_t ec_workspace_bytes(const ec_model_cfg *model, const ec_decode_cfg *decode,
+                          const int32_t *prompt_lens /*HOST [batch]*/);
+
+/* Creates a context: validates the configuration, carves the workspace, uploads the prompt,
+ * fills the generation slots with mask_id, clears the history (t = 1, flag = recompute).
+ * No forward pass runs here; the first step is FULL (appendix algorithm, t == 1 branch).
+ *  prompt_ids  HOST, concatenated prompts, prompt_lens[b] ids each, none equal to ... any id in
+ *              [0, vocab) is accepted
+ *  workspace   DEVICE, 256-byte aligned, >= ec_workspace_bytes(); BORROWED
+ *  hip_stream  hipStream_t to enqueue on (NULL = the default stream)                          */
+int ec_init(ec_ctx **out, const ec_model_cfg *model, const ec_weights *weights,
+            const ec_decode_cfg *decode, const int32_t *prompt_ids, const int32_t *prompt_lens,
+            void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Restarts the generation of an existing context with a new prompt of the SAME length. */
+int ec_reset(ec_ctx *ctx, const int32_t *prompt_ids /*HOST*/);
+
+/* One denoising step (Algorithm 1 loop body).  mode = EC_AUTO follows the entropy flag;
+ * EC_FULL / EC_PARTIAL override it.  out: HOST, one ec_step_result. */
+int ec_step(ec_ctx *ctx, int mode, ec_step_result *out);
+
+/* Teacher forcing: runs the forward pass and the vocabulary reduction in `mode`, reports the
+ * step's own choice in `out`, but commits the caller's n (position, token) pairs (HOST arrays;
+ * n may be 0) to x, the mask set and the history. */
+int ec_step_forced(ec_ctx *ctx, int mode, int32_t n, const int32_t *positions,
+                   const int32_t *tokens, ec_step_result *out);
+
+/* Runs EC_AUTO steps until no masked position is left (Algorithm 1).  out_tokens: HOST
+ * [gen_len] final ids of the generation slots.  stats may be NULL. */
+int ec_generate(ec_ctx *ctx, int32_t *out_tokens, ec_gen_stats *stats);
+
+/* Per-kernel-class device timing with HIP events on the context's stream.  While enabled every
+ * launch is bracketed by two events (this slows the step slightly; keep it off when timing
+ * whole steps).  ec_profile_read accumulates since the last enable. */
+int ec_profile_enable(ec_ctx *ctx, int on);
+int ec_profile_read(ec_ctx *ctx, ec_profile *out);
+
+/* Copies internal state to the host (synchronises the stream).  bytes must not exceed the
+ * size of the item; the copy is truncated to bytes. */
+int ec_debug_read(ec_ctx *ctx, int what, int layer, void *host_dst, size_t bytes);
+
+/* Frees host-side state only; never frees weights or workspace.  NULL is allowed. */
+void ec_destroy(ec_ctx *ctx);
+
+const char *ec_strerror(int code);
+const char *ec_last_error(const ec_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EC_H */

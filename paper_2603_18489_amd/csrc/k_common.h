@@ -1,0 +1,84 @@
+// Device helpers shared by the HIP kernels: bfloat16 conversion, wave / block reductions,
+// and the index maps of the two re-tiled ("packed") bf16 layouts.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ec {
+
+typedef uint16_t bf16_t;  // raw bfloat16 bit pattern
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) {
+  return __uint_as_float(((uint32_t)b) << 16);
+}
+// round to nearest, ties to even; NaN stays NaN
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+template <typename T> __device__ __forceinline__ float load_f32(const T* p);
+template <> __device__ __forceinline__ float load_f32<float>(const float* p) { return *p; }
+template <> __device__ __forceinline__ float load_f32<bf16_t>(const bf16_t* p) { return bf16_to_f32(*p); }
+template <typename T> __device__ __forceinline__ void store_f32(T* p, float v);
+template <> __device__ __forceinline__ void store_f32<float>(float* p, float v) { *p = v; }
+template <> __device__ __forceinline__ void store_f32<bf16_t>(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+
+// ---- packed bf16 operand layouts -------------------------------------------------------------
+// A 16 x 32 bf16 fragment is stored as 64 lanes x 8 elements = 1 KiB, lane = g*16 + r holding
+// row r, columns g*8 .. g*8+7: exactly what lane `lane` feeds to v_mfma_f32_16x16x32_bf16.
+//
+// Activations  A[M, K]:  fragment (kb, mt) at ((kb * MT + mt) * 512) elements, MT = ceil(M/16).
+// Weights      W[N, K]:  fragment (nt, kb) at ((nt * KB + kb) * 512) elements, KB = K/32.
+__device__ __forceinline__ size_t packed_act_index(int m, int k, int MT) {
+  int kb = k >> 5, g = (k >> 3) & 3, e = k & 7, mt = m >> 4, r = m & 15;
+  return ((size_t)(kb * MT + mt) * 64 + g * 16 + r) * 8 + e;
+}
+__device__ __forceinline__ size_t packed_w_index(int n, int k, int KB) {
+  int kb = k >> 5, g = (k >> 3) & 3, e = k & 7, nt = n >> 4, r = n & 15;
+  return (((size_t)nt * KB + kb) * 64 + g * 16 + r) * 8 + e;
+}
+
+// ---- reductions (fixed order => deterministic) -----------------------------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+// Sum over a block of NW waves; every thread gets the result.  `scratch` holds NW floats.
+template <int NW> __device__ __forceinline__ float block_sum(float v, float* scratch) {
+  v = wave_sum(v);
+  int w = threadIdx.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) scratch[w] = v;
+  __syncthreads();
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < NW; ++i) s += scratch[i];
+  return s;
+}
+template <int NW> __device__ __forceinline__ float block_max(float v, float* scratch) {
+  v = wave_max(v);
+  int w = threadIdx.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) scratch[w] = v;
+  __syncthreads();
+  float s = scratch[0];
+#pragma unroll
+  for (int i = 1; i < NW; ++i) s = fmaxf(s, scratch[i]);
+  return s;
+}
+
+}  // namespace ec

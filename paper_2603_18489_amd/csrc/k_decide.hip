@@ -1,0 +1,323 @@
+// The O(V) decision of EntropyCache and the bookkeeping around it:
+//   vocab_reduce : per logit row, partial (max, argmax, sum e^{z-max}, sum e^{z-max}(z-max))
+//                  over chunks of the vocabulary, in one pass.
+//   decide       : merges the partials (confidence = 1/S, entropy H = ln S - T/S; Eq. 1), picks
+//                  the tokens to unmask (decode()), records the decode history (Eq. 2), selects
+//                  the recent tokens (Eq. 3, tau_R, R), sets the skip flag (E <= tau) and builds
+//                  the row set M u R of the next partial step.
+// Every reduction runs in a fixed order, so results are bit-reproducible.
+#include <limits.h>
+
+#include "ec_internal.h"
+
+namespace ec {
+
+// ---- (max, argmax, S, T) tuples ---------------------------------------------------------------
+struct VTuple {
+  float m;   // running maximum
+  int idx;   // its index (lowest index among equal maxima)
+  float s;   // sum exp(z - m)
+  float t;   // sum exp(z - m) * (z - m)
+};
+
+__device__ __forceinline__ VTuple vt_identity() { return {-INFINITY, INT_MAX, 0.f, 0.f}; }
+
+// Associative merge: re-base both sides to the common maximum.
+__device__ __forceinline__ VTuple vt_merge(const VTuple& a, const VTuple& b) {
+  if (b.s == 0.f) return a;
+  if (a.s == 0.f) return b;
+  VTuple r;
+  bool a_wins = (a.m > b.m) || (a.m == b.m && a.idx < b.idx);
+  r.m = fmaxf(a.m, b.m);
+  r.idx = a_wins ? a.idx : b.idx;
+  float da = a.m - r.m, db = b.m - r.m;  // <= 0
+  float ea = expf(da), eb = expf(db);
+  r.s = a.s * ea + b.s * eb;
+  r.t = ea * (a.t + da * a.s) + eb * (b.t + db * b.s);
+  return r;
+}
+
+__device__ __forceinline__ void vt_push(VTuple& v, float z, int idx) {
+  if (z == -INFINITY) return;  // probability 0 contributes 0 (0 ln 0 := 0)
+  if (z > v.m) {  // new maximum: re-base what was accumulated so far
+    if (v.s != 0.f) {
+      float d = v.m - z, e = expf(d);
+      v.t = e * (v.t + d * v.s);
+      v.s = v.s * e;
+    }
+    v.m = z;
+    v.idx = idx;
+    v.s += 1.f;
+  } else {
+    float d = z - v.m, e = expf(d);
+    v.s += e;
+    v.t += e * d;
+  }
+}
+
+__device__ __forceinline__ VTuple vt_shfl_down(const VTuple& v, int o) {
+  VTuple r;
+  r.m = __shfl_down(v.m, o, 64);
+  r.idx = __shfl_down(v.idx, o, 64);
+  r.s = __shfl_down(v.s, o, 64);
+  r.t = __shfl_down(v.t, o, 64);
+  return r;
+}
+
+constexpr int VR_CHUNK = 2048;  // logits per block
+
+int vocab_reduce_parts(int V) { return (V + VR_CHUNK - 1) / VR_CHUNK; }
+
+__global__ __launch_bounds__(256) void vocab_reduce_kernel(const float* __restrict__ logits, int V,
+                                                           int nparts,
+                                                           float4* __restrict__ partials) {
+  __shared__ VTuple wt[4];
+  const int part = blockIdx.x, row = blockIdx.y, tid = threadIdx.x;
+  const float* z = logits + (size_t)row * V;
+  int lo = part * VR_CHUNK, hi = min(V, lo + VR_CHUNK);
+  VTuple v = vt_identity();
+  for (int i = lo + tid; i < hi; i += 256) vt_push(v, z[i], i);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    VTuple other = vt_shfl_down(v, o);
+    v = vt_merge(v, other);  // lane l merges lane l+o; lane 0 ends with the wave's result
+  }
+  if ((tid & 63) == 0) wt[tid >> 6] = v;
+  __syncthreads();
+  if (tid == 0) {
+    VTuple r = wt[0];
+    for (int w = 1; w < 4; ++w) r = vt_merge(r, wt[w]);
+    partials[(size_t)row * nparts + part] = make_float4(r.m, __int_as_float(r.idx), r.s, r.t);
+  }
+}
+
+void launch_vocab_reduce(const float* logits, int n_rows, int V, float4* partials, hipStream_t s) {
+  if (n_rows <= 0) return;
+  int nparts = vocab_reduce_parts(V);
+  vocab_reduce_kernel<<<dim3(nparts, n_rows), 256, 0, s>>>(logits, V, nparts, partials);
+}
+
+// ---- block-wide integer helpers (256 threads) -------------------------------------------------
+__device__ __forceinline__ int block_sum_int(int v, int* scratch) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return scratch[0] + scratch[1] + scratch[2] + scratch[3];
+}
+
+// Exclusive prefix of a 0/1 flag over the block; returns the prefix, *total gets the block sum.
+__device__ __forceinline__ int block_excl_scan_flag(int flag, int* scratch, int* total) {
+  unsigned long long ball = __ballot(flag);
+  int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  int pre = __popcll(ball & ((1ull << lane) - 1ull));
+  __syncthreads();
+  if (lane == 0) scratch[w] = __popcll(ball);
+  __syncthreads();
+  int off = 0;
+  for (int i = 0; i < w; ++i) off += scratch[i];
+  *total = scratch[0] + scratch[1] + scratch[2] + scratch[3];
+  return off + pre;
+}
+
+// ---------------------------------------------------------------------------------------------
+// decide: one block of 256 threads per sequence.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void decide_kernel(DecideArgs a) {
+  __shared__ int s_tok[EC_MAX_BLOCK];
+  __shared__ float s_conf[EC_MAX_BLOCK], s_H[EC_MAX_BLOCK];
+  __shared__ int s_taken[EC_MAX_BLOCK];
+  __shared__ int scratch[4];
+  __shared__ float sh_f[2];
+  const int tid = threadIdx.x;
+  DevState st = *a.st;  // every thread holds a private copy; thread 0 writes it back
+  const int t = st.t;
+  const int P = a.P, N = a.N, T = a.T;
+  const int nblocks = (N + a.block - 1) / a.block;
+
+  if (!a.init_only) {
+    // ---- merge the vocabulary partials of each block row (fixed order) ----------------------
+    if (tid < a.n_mb) {
+      VTuple v = vt_identity();
+      for (int p = 0; p < a.nparts; ++p) {
+        float4 q = a.partials[(size_t)tid * a.nparts + p];
+        VTuple o = {q.x, __float_as_int(q.y), q.z, q.w};
+        v = vt_merge(v, o);
+      }
+      float conf = 1.0f / v.s;                 // max probability = e^0 / S
+      float H = logf(v.s) - v.t / v.s;         // -sum p ln p
+      H = fmaxf(H, 0.f);
+      s_tok[tid] = v.idx;
+      s_conf[tid] = conf;
+      s_H[tid] = H;
+      s_taken[tid] = 0;
+      a.row_stats[tid * 4 + 0] = (float)v.idx;
+      a.row_stats[tid * 4 + 1] = conf;
+      a.row_stats[tid * 4 + 2] = H;
+      a.row_stats[tid * 4 + 3] = v.m;
+    }
+    __syncthreads();
+    // ---- decode(): most confident rows first; ties -> lowest position (= lowest row) --------
+    if (tid == 0) {
+      ec_step_result& R = a.out->r;
+      int n = min(a.n_tok, a.n_mb);
+      float E_own = -INFINITY;
+      for (int i = 0; i < n; ++i) {
+        int best = -1;
+        for (int r = 0; r < a.n_mb; ++r)
+          if (!s_taken[r] && (best < 0 || s_conf[r] > s_conf[best])) best = r;
+        s_taken[best] = 1;
+        R.positions[i] = a.mb_pos[best];
+        R.tokens[i] = s_tok[best];
+        R.entropy[i] = s_H[best];
+        R.confidence[i] = s_conf[best];
+        E_own = fmaxf(E_own, s_H[best]);
+      }
+      for (int i = n; i < EC_MAX_N; ++i) {
+        R.positions[i] = -1; R.tokens[i] = -1; R.entropy[i] = 0.f; R.confidence[i] = 0.f;
+      }
+      R.n_unmasked = n;
+      R.max_entropy = E_own;
+      // ---- commit: own choice, or the caller's under teacher forcing -----------------------
+      float E = E_own;
+      if (a.forced_n >= 0) {
+        bool all_in_block = true;
+        float Ef = -INFINITY;
+        for (int i = 0; i < a.forced_n; ++i) {
+          int p = a.forced_pos[i], row = -1;
+          for (int r = 0; r < a.n_mb; ++r)
+            if (a.mb_pos[r] == p) row = r;
+          if (row < 0) all_in_block = false; else Ef = fmaxf(Ef, s_H[row]);
+          a.x[p] = a.forced_tok[i];
+          a.masked[p] = 0;
+          a.hist[p - P] = t;                              // Eq. 2
+        }
+        if (all_in_block) E = Ef;                         // max over an empty set = -inf
+      } else {
+        for (int i = 0; i < n; ++i) {
+          int p = R.positions[i];
+          a.x[p] = R.tokens[i];
+          a.masked[p] = 0;
+          a.hist[p - P] = t;                              // Eq. 2
+        }
+      }
+      sh_f[0] = E;
+      sh_f[1] = E_own;
+    }
+    __syncthreads();
+    __threadfence_block();
+  }
+
+  // ---- recency threshold: tau_R = max(k-th largest history value, t - dt) --------------------
+  // History values are step indices in [1, t] or "never": the k-th largest is the largest v with
+  // count(hist >= v) >= k, found by bisection; fewer than k decoded -> -inf.
+  int t_lastfull = st.t_lastfull;
+  int tauR = INT_MAX;
+  if (!a.init_only) {
+    if (a.mode_run == EC_FULL) t_lastfull = t;
+    int kth = INT_MIN;
+    if (a.k_recent > 0) {
+      int lo = 1, hi = t, found = INT_MIN;
+      while (lo <= hi) {  // uniform across the block
+        int mid = (lo + hi) >> 1, c = 0;
+        for (int i = tid; i < N; i += 256) c += (a.hist[i] >= mid);
+        c = block_sum_int(c, scratch);
+        if (c >= a.k_recent) { found = mid; lo = mid + 1; } else { hi = mid - 1; }
+      }
+      kth = found;
+    } else {
+      kth = INT_MAX;  // empty selection: nothing qualifies by rank
+    }
+    tauR = max(kth, t_lastfull);  // t - dt == index of the last FULL step
+  }
+
+  // ---- flag for the next step, counters, block advance ---------------------------------------
+  if (!a.init_only) {
+    float E = sh_f[0];
+    if (E <= a.tau) { st.skip = 1; st.dt += 1; } else { st.skip = 0; st.dt = 0; }
+    st.t_lastfull = t_lastfull;
+    st.t = t + 1;
+  }
+  int blk = st.blk;
+  while (blk < nblocks) {  // uniform: every thread evaluates the same counts
+    int lo = P + blk * a.block, hi = min(T, lo + a.block), c = 0;
+    for (int i = lo + tid; i < hi; i += 256) c += a.masked[i];
+    c = block_sum_int(c, scratch);
+    if (c > 0) break;
+    ++blk;
+  }
+  st.blk = blk;
+  st.done = (blk >= nblocks);
+
+  // ---- row lists of the next step: M (block's masked rows) and M u R, ascending -------------
+  int blo = P + blk * a.block, bhi = min(T, blo + a.block);
+  int n_rows = 0, n_mb = 0, n_recent = 0;
+  for (int base = 0; base < N; base += 256) {
+    int i = base + tid, pos = P + i;
+    int inM = 0, inR = 0;
+    if (i < N) {
+      inM = (!st.done && pos >= blo && pos < bhi && a.masked[pos]) ? 1 : 0;
+      inR = (!a.init_only && a.hist[i] != INT_MIN && a.hist[i] >= tauR) ? 1 : 0;
+    }
+    int tot_any, tot_m, tot_r;
+    int pre_any = block_excl_scan_flag(inM | inR, scratch, &tot_any);
+    int pre_m = block_excl_scan_flag(inM, scratch, &tot_m);
+    (void)block_excl_scan_flag(inR, scratch, &tot_r);
+    if (inM | inR) a.rows_partial[n_rows + pre_any] = pos;
+    if (inM) {
+      a.mb_pos[n_mb + pre_m] = pos;
+      a.mb_idx[n_mb + pre_m] = n_rows + pre_any;
+    }
+    n_rows += tot_any;
+    n_mb += tot_m;
+    n_recent += tot_r;
+  }
+  if (tid == 0) {
+    st.n_mb = n_mb;
+    st.n_rows_partial = n_rows;
+    st.n_recent = n_recent;
+    *a.st = st;
+    StepOut& o = *a.out;
+    o.next_n_mb = n_mb;
+    o.next_n_rows_partial = n_rows;
+    if (!a.init_only) {
+      o.r.done = st.done;
+      o.r.mode_run = a.mode_run;
+      o.r.next_mode = (sh_f[1] <= a.tau) ? EC_PARTIAL : EC_FULL;
+      o.r.n_query_rows = a.n_rows_run;
+      o.r.step_index = t;
+      o.r.n_block_rows = a.n_mb;
+      o.r.n_recent_next = n_recent;
+    }
+  }
+}
+
+void launch_decide(const DecideArgs& a, hipStream_t s) { decide_kernel<<<1, 256, 0, s>>>(a); }
+
+// ---------------------------------------------------------------------------------------------
+// init_state: x = [prompt ; mask_id ...], mask set = generation slots, history = never,
+// t = 1, flag = recompute, Delta t = 0 (initialisation lines of both algorithms).
+// ---------------------------------------------------------------------------------------------
+__global__ void init_state_kernel(int* x, uint8_t* masked, int* hist, DevState* st,
+                                  const int* prompt, int P, int N, int mask_id) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < P + N) {
+    x[i] = i < P ? prompt[i] : mask_id;
+    masked[i] = i < P ? 0 : 1;
+    if (i >= P) hist[i - P] = INT_MIN;
+  }
+  if (i == 0) {
+    DevState z = {};
+    z.t = 1;
+    *st = z;
+  }
+}
+
+void launch_init_state(int* x, uint8_t* masked, int* hist, DevState* st, const int* prompt_dev,
+                       int P, int N, int mask_id, hipStream_t s) {
+  int n = P + N;
+  init_state_kernel<<<(n + 255) / 256, 256, 0, s>>>(x, masked, hist, st, prompt_dev, P, N, mask_id);
+}
+
+}  // namespace ec
