@@ -19,7 +19,7 @@ from typing import Dict, List, Tuple
 
 import numpy as np
 
-_CHUNK = 1 << 24  # elements drawn per Philox key
+_CHUNK = 1 << 20  # elements drawn per Philox key
 
 
 @dataclasses.dataclass(frozen=True)

@@ -65,7 +65,7 @@ def run_teacher_forced(cfg, w, dec, prompt, tol, max_steps=None, check_cache_eve
             worst["conf"] = max(worst["conf"], eC)
             # entropy / confidence inherit the logits' error, amplified by the logit range
             zrange = float(np.ptp(r["logits"]))
-            stat_tol = max(tol, 4 * tol * max(zrange, 1.0)) if cfg.dtype == "bf16" else 20 * tol
+            stat_tol = max(tol, 4 * tol * max(zrange, 1.0)) if cfg.dtype == "bf16" else 2 * tol
             assert eH <= stat_tol, f"step {r['t']}: entropy err {eH:.3e} > {stat_tol:.3e}"
             assert eC <= stat_tol, f"step {r['t']}: confidence err {eC:.3e}"
             # decisions: bit-exact wherever the oracle's margins exceed the tolerance

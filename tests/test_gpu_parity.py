@@ -37,7 +37,7 @@ def test_tiny_f32_whole_generation():
 @pytest.mark.parametrize("dtype,hq,hkv,hd,P,N,block,k,n,tau", [
     ("f32", 4, 2, 64, 37, 45, 16, 3, 2, 2.5),       # GQA, ragged last block, T not / 16
     ("f32", 2, 1, 128, 5, 9, 32, 0, 1, 1e9),        # gen shorter than block, k = 0, head_dim 128
-    ("bf16", 4, 4, 64, 64, 64, 32, 2, 1, 2.0),
+    ("bf16", 4, 4, 64, 64, 64, 32, 2, 1, 3.0),
     ("bf16", 4, 2, 128, 50, 70, 32, 4, 2, 2.5),     # GQA, head_dim 128, 70 = 2 blocks + 6
     ("bf16", 8, 2, 64, 100, 33, 32, 2, 3, 1e9),     # T = 133 > 128 rows: tiled GEMM in FULL
 ])
