@@ -49,6 +49,8 @@ struct Buffers {
 };
 
 size_t esize(int dtype) { return dtype == EC_BF16 ? 2 : 4; }
+// keys held per cache slab: the packed bf16 cache is padded to whole 32-key blocks
+int kv_keys(int dtype, int T) { return dtype == EC_BF16 ? (T + 31) / 32 * 32 : T; }
 
 void carve(Carver& c, const ec_model_cfg& m, const ec_decode_cfg& d, int P, Buffers& b) {
   const int T = P + d.gen_len, N = d.gen_len;
@@ -61,7 +63,7 @@ void carve(Carver& c, const ec_model_cfg& m, const ec_decode_cfg& d, int P, Buff
   b.out = c.take<StepOut>(1); b.forced_pos = c.take<int>(EC_MAX_N);
   b.forced_tok = c.take<int>(EC_MAX_N); b.prompt = c.take<int>(P);
   b.rope_cs = c.take<float2>((size_t)T * (m.head_dim / 2));
-  b.kv = c.take<char>((size_t)m.n_layers * 2 * T * nkv * es);
+  b.kv = c.take<char>((size_t)m.n_layers * 2 * kv_keys(m.dtype, T) * nkv * es);
   b.h = c.take<float>((size_t)T * m.d_model);
   b.u = c.take<char>(T16 * m.d_model * es);
   b.qkv = c.take<float>((size_t)T * (nq + 2 * nkv));
@@ -189,7 +191,7 @@ void prof_collect(ec_ctx* c) {  // stream must be idle
 
 char* kv_ptr(ec_ctx* c, int layer, int which) {
   size_t row = (size_t)c->m.n_kv_heads * c->m.head_dim * esize(c->m.dtype);
-  return c->b.kv + ((size_t)layer * 2 + which) * c->T * row;
+  return c->b.kv + ((size_t)layer * 2 + which) * kv_keys(c->m.dtype, c->T) * row;
 }
 
 int upload_and_init_state(ec_ctx* c, const int32_t* prompt_ids) {
@@ -245,10 +247,10 @@ int forward(ec_ctx* c, int mode, int M, int n_mb) {
       } }
     { Scope p(c, EC_K_ROPE_KV);
       launch_rope_scatter(dt, b.qkv, rows, M, m.n_heads, m.n_kv_heads, hd, b.rope_cs, b.q,
-                          kv_ptr(c, l, 0), kv_ptr(c, l, 1), s); }
+                          kv_ptr(c, l, 0), kv_ptr(c, l, 1), kv_keys(dt, c->T), s); }
     { Scope p(c, EC_K_ATTN);
-      launch_attention(dt, b.q, kv_ptr(c, l, 0), kv_ptr(c, l, 1), M, c->T, m.n_heads,
-                       m.n_kv_heads, hd, b.attn, s); }
+      launch_attention(dt, b.q, kv_ptr(c, l, 0), kv_ptr(c, l, 1), M, c->T, kv_keys(dt, c->T),
+                       m.n_heads, m.n_kv_heads, hd, b.attn, s); }
     { Scope p(c, EC_K_OPROJ);
       if (dt == EC_F32) {
         launch_gemm_f32((const float*)b.attn, (const float*)c->wo[l], b.h, d, M, d, nq, 1, 1.f, s);
@@ -443,9 +445,12 @@ int ec_init(ec_ctx** out, const ec_model_cfg* model, const ec_weights* weights,
   e = hipHostMalloc((void**)&c->host_stage, stage, hipHostMallocDefault);
   if (e != hipSuccess) return bail(EC_ERR_HIP, std::string("hipHostMalloc: ") + hipGetErrorString(e));
 
-  // one-time device set-up: RoPE table, re-tiled bf16 matrices
+  // one-time device set-up: RoPE table, re-tiled bf16 matrices, finite padding keys
   launch_rope_table(c->b.rope_cs, c->T, c->m.head_dim, c->m.rope_base, c->stream);
   if (c->m.dtype == EC_BF16) {
+    size_t kvbytes = (size_t)L * 2 * kv_keys(EC_BF16, c->T) * c->m.n_kv_heads * c->m.head_dim * 2;
+    e = hipMemsetAsync(c->b.kv, 0, kvbytes, c->stream);
+    if (e != hipSuccess) return bail(EC_ERR_HIP, std::string("hipMemsetAsync: ") + hipGetErrorString(e));
     const int d = c->m.d_model, F = c->m.d_ffn;
     const int nq = c->m.n_heads * c->m.head_dim, nkv = c->m.n_kv_heads * c->m.head_dim;
     for (int l = 0; l < L; ++l) {
@@ -534,7 +539,15 @@ int ec_debug_read(ec_ctx* ctx, int what, int layer, void* host_dst, size_t bytes
     case EC_DBG_KCACHE:
     case EC_DBG_VCACHE:
       if (layer < 0 || layer >= ctx->m.n_layers) return fail(ctx, EC_ERR_ARG, "layer out of range");
-      src = kv_ptr(ctx, layer, what == EC_DBG_VCACHE); avail = (size_t)ctx->T * kvrow; break;
+      src = kv_ptr(ctx, layer, what == EC_DBG_VCACHE); avail = (size_t)ctx->T * kvrow;
+      if (ctx->m.dtype == EC_BF16) {
+        // the packed cache is put back into [T, Hkv, hd] order in a scratch activation buffer
+        launch_unpack_cache((const bf16_t*)src, what == EC_DBG_VCACHE, ctx->T,
+                            kv_keys(EC_BF16, ctx->T), ctx->m.n_kv_heads, ctx->m.head_dim,
+                            (bf16_t*)ctx->b.qkv, ctx->stream);
+        src = ctx->b.qkv;
+      }
+      break;
     case EC_DBG_X: src = ctx->b.x; avail = (size_t)ctx->T * 4; break;
     case EC_DBG_MASKED: src = ctx->b.masked; avail = (size_t)ctx->T; break;
     case EC_DBG_HIST: src = ctx->b.hist; avail = (size_t)ctx->N * 4; break;

@@ -64,9 +64,13 @@ void launch_embed(int dtype, const void* emb, const int* x, const int* rows, int
 void launch_rmsnorm(int dtype, const float* h, const int* sel, int M, int d, const void* gain,
                     float eps, void* out, hipStream_t s);
 void launch_rope_table(float2* cs, int T, int hd, float base, hipStream_t s);
+// f32: caches are row-major [T, Hkv*hd].  bf16: packed per kv head (k_common.h), Tpad keys.
 void launch_rope_scatter(int dtype, const float* qkv, const int* rows, int M, int Hq, int Hkv,
                          int hd, const float2* cs, void* q_out, void* kcache, void* vcache,
-                         hipStream_t s);
+                         int Tpad, hipStream_t s);
+// bf16 only: packed cache of one layer -> row-major [T, Hkv*hd] (debug read-back).
+void launch_unpack_cache(const bf16_t* packed, int is_v, int T, int Tpad, int Hkv, int hd,
+                         bf16_t* out, hipStream_t s);
 void launch_swiglu(int dtype, const float* gu, int M, int F, void* act, hipStream_t s);
 void launch_repack_weight(const bf16_t* W, int N, int K, bf16_t* Wp, hipStream_t s);
 
@@ -85,7 +89,7 @@ void launch_gemm_bf16(const bf16_t* Ap, int M, const GemmSegs& segs, int K, floa
 // Non-causal attention of M query rows against all T cached positions.
 // q row-major [M, Hq*hd]; caches [T, Hkv*hd]; out row-major float (f32) or packed bf16.
 void launch_attention(int dtype, const void* q, const void* kc, const void* vc, int M, int T,
-                      int Hq, int Hkv, int hd, void* out, hipStream_t s);
+                      int Tpad, int Hq, int Hkv, int hd, void* out, hipStream_t s);
 
 int vocab_reduce_parts(int V);
 void launch_vocab_reduce(const float* logits, int n_rows, int V, float4* partials, hipStream_t s);

@@ -2,8 +2,9 @@
 // ("TransformerBlock(Q_[M u R], K_[I], V_[I])" of the appendix algorithm): every query row
 // attends all T cached positions, no mask.
 //
-// Generic kernel (any storage type): one block per (query row, head).  Scores for all T keys
-// are kept in LDS, softmax statistics in fp32, then P.V with the block split over hd columns.
+// Generic kernel for the float32 path (row-major cache): one block per (query row, head).
+// Scores for all T keys are kept in LDS, softmax statistics in fp32, then P.V with the block
+// split over hd columns.  The bf16 path uses the MFMA kernel of k_attn_mfma.hip.
 #include "ec_internal.h"
 
 namespace ec {
@@ -83,13 +84,17 @@ static void launch_attn_t(const void* q, const void* kc, const void* vc, int M, 
         (const TA*)q, (const TA*)kc, (const TA*)vc, M, T, Hq, Hkv, scale, out, MT);
 }
 
+void launch_attention_mfma(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int M, int T,
+                           int Tpad, int Hq, int Hkv, int hd, bf16_t* out, hipStream_t s);
+
 void launch_attention(int dtype, const void* q, const void* kc, const void* vc, int M, int T,
-                      int Hq, int Hkv, int hd, void* out, hipStream_t s) {
+                      int Tpad, int Hq, int Hkv, int hd, void* out, hipStream_t s) {
   if (M <= 0) return;
   if (dtype == EC_F32)
     launch_attn_t<float, false>(q, kc, vc, M, T, Hq, Hkv, hd, out, s);
   else
-    launch_attn_t<bf16_t, true>(q, kc, vc, M, T, Hq, Hkv, hd, out, s);
+    launch_attention_mfma((const bf16_t*)q, (const bf16_t*)kc, (const bf16_t*)vc, M, T, Tpad, Hq,
+                          Hkv, hd, (bf16_t*)out, s);
 }
 
 }  // namespace ec

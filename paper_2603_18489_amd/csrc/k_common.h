@@ -46,6 +46,23 @@ __device__ __forceinline__ size_t packed_w_index(int n, int k, int KB) {
   return (((size_t)nt * KB + kb) * 64 + g * 16 + r) * 8 + e;
 }
 
+// ---- packed bf16 KV cache (one kv head = one contiguous slab of Tpad * HD elements) -----------
+// K: fragments are MFMA "A" operands of S^T = K Q^T.  A 32-key block holds two 16-row tiles;
+//    tile t, row i is key (i/4)*8 + t*4 + (i%4) of the block, so that after the two tiles'
+//    MFMAs a lane owns 8 CONSECUTIVE keys - the order in which P feeds the P.V MFMA.
+//    fragment ((kb32*2 + t) * HD/32 + hb), lane g*16+i holds hd columns hb*32 + g*8 .. +7.
+// V: stored transposed; fragments are "A" operands of O^T = V^T P^T.
+//    fragment (ht * Tpad/32 + kb32), lane g*16+j holds hd row ht*16+j, keys kb32*32 + g*8 .. +7.
+__device__ __forceinline__ size_t kcache_index(int key, int c, int HD) {
+  int kb = key >> 5, w = key & 31, i = (w >> 3) * 4 + (w & 3), t = (w >> 2) & 1;
+  int hb = c >> 5, g = (c >> 3) & 3, e = c & 7;
+  return (((size_t)(kb * 2 + t) * (HD >> 5) + hb) * 64 + g * 16 + i) * 8 + e;
+}
+__device__ __forceinline__ size_t vcache_index(int key, int c, int Tpad) {
+  int kb = key >> 5, g = (key >> 3) & 3, e = key & 7, ht = c >> 4, j = c & 15;
+  return (((size_t)ht * (Tpad >> 5) + kb) * 64 + g * 16 + j) * 8 + e;
+}
+
 // ---- reductions (fixed order => deterministic) -----------------------------------------------
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

@@ -106,14 +106,14 @@ void launch_rope_table(float2* cs, int T, int hd, float base, hipStream_t s) {
 // absolute position, write q to the query buffer and k, v into the layer's cache row `pos`.
 // The cache holds post-RoPE keys.  One block per row; one full cache row per (row, K/V).
 // ---------------------------------------------------------------------------------------------
-template <typename TA>
+template <typename TA, bool PACKED>
 __global__ __launch_bounds__(256) void rope_scatter_kernel(const float* __restrict__ qkv,
                                                            const int* __restrict__ rows, int Hq,
                                                            int Hkv, int hd,
                                                            const float2* __restrict__ cs,
                                                            TA* __restrict__ q_out,
                                                            TA* __restrict__ kcache,
-                                                           TA* __restrict__ vcache) {
+                                                           TA* __restrict__ vcache, int Tpad) {
   int r = blockIdx.x;
   int pos = rows ? rows[r] : r;
   int half = hd / 2;
@@ -129,6 +129,10 @@ __global__ __launch_bounds__(256) void rope_scatter_kernel(const float* __restri
       TA* dst = q_out + (size_t)r * nq + head * hd + j;
       store_f32<TA>(dst, ra);
       store_f32<TA>(dst + half, rb);
+    } else if constexpr (PACKED) {
+      TA* slab = kcache + (size_t)(head - Hq) * Tpad * hd;
+      store_f32<TA>(slab + kcache_index(pos, j, hd), ra);
+      store_f32<TA>(slab + kcache_index(pos, j + half, hd), rb);
     } else {
       TA* dst = kcache + (size_t)pos * nkv + (head - Hq) * hd + j;
       store_f32<TA>(dst, ra);
@@ -136,20 +140,44 @@ __global__ __launch_bounds__(256) void rope_scatter_kernel(const float* __restri
     }
   }
   const float* vrow = row + nq + nkv;
-  TA* vdst = vcache + (size_t)pos * nkv;
-  for (int c = threadIdx.x; c < nkv; c += 256) store_f32<TA>(vdst + c, vrow[c]);
+  if constexpr (PACKED) {
+    for (int c = threadIdx.x; c < nkv; c += 256) {
+      int kvh = c / hd, cc = c - kvh * hd;
+      store_f32<TA>(vcache + (size_t)kvh * Tpad * hd + vcache_index(pos, cc, Tpad), vrow[c]);
+    }
+  } else {
+    TA* vdst = vcache + (size_t)pos * nkv;
+    for (int c = threadIdx.x; c < nkv; c += 256) store_f32<TA>(vdst + c, vrow[c]);
+  }
+}
+
+__global__ __launch_bounds__(256) void unpack_cache_kernel(const bf16_t* __restrict__ packed,
+                                                           int is_v, int T, int Tpad, int Hkv,
+                                                           int hd, bf16_t* __restrict__ out) {
+  int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= T * Hkv * hd) return;
+  int key = i / (Hkv * hd), c = i - key * (Hkv * hd), kvh = c / hd, cc = c - kvh * hd;
+  const bf16_t* slab = packed + (size_t)kvh * Tpad * hd;
+  out[i] = is_v ? slab[vcache_index(key, cc, Tpad)] : slab[kcache_index(key, cc, hd)];
+}
+
+void launch_unpack_cache(const bf16_t* packed, int is_v, int T, int Tpad, int Hkv, int hd,
+                         bf16_t* out, hipStream_t s) {
+  int n = T * Hkv * hd;
+  unpack_cache_kernel<<<(n + 255) / 256, 256, 0, s>>>(packed, is_v, T, Tpad, Hkv, hd, out);
 }
 
 void launch_rope_scatter(int dtype, const float* qkv, const int* rows, int M, int Hq, int Hkv,
                          int hd, const float2* cs, void* q_out, void* kcache, void* vcache,
-                         hipStream_t s) {
+                         int Tpad, hipStream_t s) {
   if (M <= 0) return;
   if (dtype == EC_F32)
-    rope_scatter_kernel<float><<<M, 256, 0, s>>>(qkv, rows, Hq, Hkv, hd, cs, (float*)q_out,
-                                                 (float*)kcache, (float*)vcache);
+    rope_scatter_kernel<float, false><<<M, 256, 0, s>>>(qkv, rows, Hq, Hkv, hd, cs, (float*)q_out,
+                                                        (float*)kcache, (float*)vcache, Tpad);
   else
-    rope_scatter_kernel<bf16_t><<<M, 256, 0, s>>>(qkv, rows, Hq, Hkv, hd, cs, (bf16_t*)q_out,
-                                                  (bf16_t*)kcache, (bf16_t*)vcache);
+    rope_scatter_kernel<bf16_t, true><<<M, 256, 0, s>>>(qkv, rows, Hq, Hkv, hd, cs,
+                                                        (bf16_t*)q_out, (bf16_t*)kcache,
+                                                        (bf16_t*)vcache, Tpad);
 }
 
 // ---------------------------------------------------------------------------------------------
