@@ -9,12 +9,19 @@
 //    splits K across its waves; each wave streams its slice of the weights exactly once from
 //    HBM while the small activation fragments come from L2.  The KS partial tiles are summed
 //    in LDS in a fixed order (deterministic).
-//  * tiled kernel (M > 64): 128x128 block tile, K step 32, LDS double buffering, 4 waves each
-//    computing 64x64 with 16 MFMA accumulators.
+//  * tiled kernel (M > 64): 2x2 waves, block tile chosen per shape (up to 192x192) so that the
+//    grid fills the 256 CUs, K step 32, LDS double buffering with register prefetch two steps
+//    ahead.
 #include "ec_internal.h"
 
 namespace ec {
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ bf16x8 v4_as_bf16x8(u32x4 v) {
+  union { u32x4 u; bf16x8 b; } c;
+  c.u = v;
+  return c.b;
+}
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) {
   union { uint4 u; bf16x8 b; } c;
   c.u = v;
@@ -132,89 +139,140 @@ static void launch_skinny_mt(const bf16_t* Ap, int M, const GemmSegs& sg, int to
 }
 
 // ---------------------------------------------------------------------------------------------
-// tiled: grid = (ceil(n-tiles/8), ceil(m-tiles/8)), 256 threads
+// tiled: 2x2 waves, wave tile = WTM x WTN fragments of 16 rows (activations x weights), K step 32.
+// Operands are double-buffered in LDS; global loads run R k-steps ahead through R register sets
+// so that L2/HBM latency is covered by R iterations of MFMA work.
+// grid = (ceil(n-tiles / (2*WTN)), ceil(m-tiles / (2*WTM)))
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void gemm_bf16_tiled_kernel(const uint4* __restrict__ Ap,
+#define EC_TILED_GLOAD(REGS, KBV)                                                   \
+  {                                                                                 \
+    int kbc_ = min((KBV), KB - 1);                                                  \
+    _Pragma("unroll") for (int i = 0; i < LF; ++i) REGS[i] = src[i][(size_t)kbc_ * stride[i]]; \
+  }
+#define EC_TILED_LSTORE(REGS, STAGE)                                                \
+  {                                                                                 \
+    _Pragma("unroll") for (int i = 0; i < LF; ++i) {                                \
+      if (4 * i + 3 < NF || wave + 4 * i < NF) lds[STAGE][wave + 4 * i][lane] = REGS[i]; \
+    }                                                                               \
+  }
+#define EC_TILED_COMPUTE(STAGE)                                                     \
+  {                                                                                 \
+    bf16x8 af_[WTM], wf_[WTN];                                                      \
+    _Pragma("unroll") for (int j = 0; j < WTM; ++j)                                 \
+        af_[j] = v4_as_bf16x8(lds[STAGE][wm * WTM + j][lane]);                         \
+    _Pragma("unroll") for (int i = 0; i < WTN; ++i)                                 \
+        wf_[i] = v4_as_bf16x8(lds[STAGE][BMT + wn * WTN + i][lane]);                   \
+    _Pragma("unroll") for (int i = 0; i < WTN; ++i)                                 \
+      _Pragma("unroll") for (int j = 0; j < WTM; ++j)                               \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf_[i], af_[j], acc[i][j], 0, 0, 0); \
+  }
+
+template <int WTM, int WTN>
+__global__ __launch_bounds__(256) void gemm_bf16_tiled_kernel(const u32x4* __restrict__ Ap,
                                                               GemmSegs sg, int total_nt, int KB,
                                                               int MT, float* __restrict__ C,
                                                               int ldc, int M, int accumulate,
                                                               float scale) {
-  __shared__ uint4 lds[2][16][64];  // [stage][frag: 0..7 activations, 8..15 weights][lane]
+  constexpr int BMT = 2 * WTM, BNT = 2 * WTN, NF = BMT + BNT;  // fragments per k-step
+  constexpr int LF = (NF + 3) / 4;                             // fragments loaded per wave
+  __shared__ u32x4 lds[2][NF][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int mt0 = blockIdx.y * 8, nt0 = blockIdx.x * 8;
+  const int mt0 = blockIdx.y * BMT, nt0 = blockIdx.x * BNT;
   const int wm = wave >> 1, wn = wave & 1;
 
-  // global loads of this wave: activation tiles mt0+2w, +1 and weight tiles nt0+2w, +1
-  const uint4* a_src[2];
-  const uint4* w_src[2];
+  // Fragment f of the block (0..BMT-1 activations, BMT.. weights) is loaded by wave f % 4.
+  // A fragment outside the matrix streams fragment 0 instead (valid memory); what it produces
+  // lands in rows / columns that are never stored.
+  const u32x4* src[LF];
+  size_t stride[LF];  // uint4 per k-step
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    int mt = mt0 + wave * 2 + i, nt = nt0 + wave * 2 + i;
-    a_src[i] = (mt < MT) ? Ap + (size_t)mt * 64 + lane : nullptr;  // + kb*MT*64 per step
-    const uint4* p = seg_tile_ptr(sg, nt, KB);
-    w_src[i] = p ? p + lane : nullptr;                              // + kb*64 per step
+  for (int i = 0; i < LF; ++i) {
+    int f = wave + 4 * i;
+    src[i] = Ap + lane;
+    stride[i] = (size_t)MT * 64;
+    if (f < BMT) {
+      int mt = mt0 + f;
+      if (mt < MT) src[i] = Ap + (size_t)mt * 64 + lane;
+    } else {
+      const u32x4* p = (const u32x4*)seg_tile_ptr(sg, nt0 + (f - BMT), KB);
+      if (f < NF && p) { src[i] = p + lane; stride[i] = 64; }
+    }
   }
-  const uint4 zero = make_uint4(0, 0, 0, 0);
-  uint4 a_reg[2], w_reg[2];
-  auto gload = [&](int kb) {
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      a_reg[i] = a_src[i] ? a_src[i][(size_t)kb * MT * 64] : zero;
-      w_reg[i] = w_src[i] ? w_src[i][(size_t)kb * 64] : zero;
-    }
-  };
-  auto lstore = [&](int stage) {
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      lds[stage][wave * 2 + i][lane] = a_reg[i];
-      lds[stage][8 + wave * 2 + i][lane] = w_reg[i];
-    }
-  };
 
-  f32x4 acc[4][4];  // [n-tile][m-tile]
+  f32x4 acc[WTN][WTM];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < WTN; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < WTM; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  gload(0);
-  lstore(0);
+  // prologue: k-step 0 into LDS stage 0, k-steps 1 and 2 in flight in the two register sets
+  u32x4 r0[LF], r1[LF];
+  EC_TILED_GLOAD(r0, 0)
+  EC_TILED_LSTORE(r0, 0)
+  EC_TILED_GLOAD(r0, 1)
+  EC_TILED_GLOAD(r1, 2)
   __syncthreads();
-  for (int kb = 0; kb < KB; ++kb) {
-    int cur = kb & 1;
-    if (kb + 1 < KB) gload(kb + 1);
-    bf16x8 af[4], wf[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) af[j] = as_bf16x8(lds[cur][wm * 4 + j][lane]);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) wf[i] = as_bf16x8(lds[cur][8 + wn * 4 + i][lane]);
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[i], af[j], acc[i][j], 0, 0, 0);
-    if (kb + 1 < KB) lstore(cur ^ 1);
+  // iteration kb: compute stage kb&1; the register set holding k-step kb+1 goes to stage
+  // (kb+1)&1 and is reloaded with k-step kb+3
+  for (int kb = 0; kb < KB; kb += 2) {
+    EC_TILED_COMPUTE(0)
+    EC_TILED_LSTORE(r0, 1)
+    EC_TILED_GLOAD(r0, kb + 3)
+    __syncthreads();
+    if (kb + 1 < KB) {
+      EC_TILED_COMPUTE(1)
+      EC_TILED_LSTORE(r1, 0)
+      EC_TILED_GLOAD(r1, kb + 4)
+    }
     __syncthreads();
   }
 
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    int nt = nt0 + wn * 4 + i;
+  for (int i = 0; i < WTN; ++i) {
+    int nt = nt0 + wn * WTN + i;
     if (nt >= total_nt) continue;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      int m = (mt0 + wm * 4 + j) * 16 + (lane & 15);
+    for (int j = 0; j < WTM; ++j) {
+      int m = (mt0 + wm * WTM + j) * 16 + (lane & 15);
       if (m >= M) continue;
       float4* c = (float4*)(C + (size_t)m * ldc + nt * 16 + (lane >> 4) * 4);
       f32x4 v = acc[i][j];
-      float4 s = make_float4(v[0] * scale, v[1] * scale, v[2] * scale, v[3] * scale);
+      float4 o = make_float4(v[0] * scale, v[1] * scale, v[2] * scale, v[3] * scale);
       if (accumulate) {
         float4 old = *c;
-        s.x += old.x; s.y += old.y; s.z += old.z; s.w += old.w;
+        o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w;
       }
-      *c = s;
+      *c = o;
     }
   }
+}
+#undef EC_TILED_GLOAD
+#undef EC_TILED_LSTORE
+#undef EC_TILED_COMPUTE
+
+template <int WTM, int WTN>
+static void launch_tiled_t(const bf16_t* Ap, int M, int MT, const GemmSegs& sg, int total_nt,
+                           int KB, float* C, int ldc, int accumulate, float scale, hipStream_t s) {
+  dim3 grid((total_nt + 2 * WTN - 1) / (2 * WTN), (MT + 2 * WTM - 1) / (2 * WTM));
+  gemm_bf16_tiled_kernel<WTM, WTN><<<grid, 256, 0, s>>>((const u32x4*)Ap, sg, total_nt, KB, MT, C,
+                                                        ldc, M, accumulate, scale);
+}
+
+// Picks the block tile whose grid wastes the least of the 256 CUs: the score is the useful
+// fraction of the rounds the grid needs, weighted by how well the tile shape feeds the MFMAs.
+static int pick_tile(int MT, int total_nt) {
+  static const int wtm[4] = {6, 6, 4, 3}, wtn[4] = {6, 4, 4, 4};
+  static const float shape_eff[4] = {1.00f, 0.90f, 0.80f, 0.62f};
+  int best = 0;
+  float best_score = -1.f;
+  for (int i = 0; i < 4; ++i) {
+    long gm = (MT + 2 * wtm[i] - 1) / (2 * wtm[i]), gn = (total_nt + 2 * wtn[i] - 1) / (2 * wtn[i]);
+    long blocks = gm * gn, rounds = (blocks + 255) / 256;
+    float useful = (float)((double)MT * total_nt / ((double)rounds * 256 * 4 * wtm[i] * wtn[i]));
+    float score = useful * shape_eff[i];
+    if (score > best_score) { best_score = score; best = i; }
+  }
+  return best;
 }
 
 void launch_gemm_bf16(const bf16_t* Ap, int M, const GemmSegs& sg, int K, float* C, int ldc,
@@ -231,9 +289,12 @@ void launch_gemm_bf16(const bf16_t* Ap, int M, const GemmSegs& sg, int K, float*
       default: launch_skinny_mt<4>(Ap, M, sg, total_nt, KB, C, ldc, accumulate, scale, s); break;
     }
   } else {
-    dim3 grid((total_nt + 7) / 8, (MT + 7) / 8);
-    gemm_bf16_tiled_kernel<<<grid, 256, 0, s>>>((const uint4*)Ap, sg, total_nt, KB, MT, C, ldc, M,
-                                                accumulate, scale);
+    switch (pick_tile(MT, total_nt)) {
+      case 0: launch_tiled_t<6, 6>(Ap, M, MT, sg, total_nt, KB, C, ldc, accumulate, scale, s); break;
+      case 1: launch_tiled_t<6, 4>(Ap, M, MT, sg, total_nt, KB, C, ldc, accumulate, scale, s); break;
+      case 2: launch_tiled_t<4, 4>(Ap, M, MT, sg, total_nt, KB, C, ldc, accumulate, scale, s); break;
+      default: launch_tiled_t<3, 4>(Ap, M, MT, sg, total_nt, KB, C, ldc, accumulate, scale, s); break;
+    }
   }
 }
 
