@@ -31,8 +31,10 @@ struct Carver {
   }
 };
 
+// Re-tiled matrices of one layer: [q | k | v] as one matrix (rotary pairs adjacent), o, gate
+// and up interleaved tile by tile, down.
 struct PackedLayer {
-  bf16_t *wq, *wk, *wv, *wo, *wg, *wu, *wd;
+  bf16_t *wqkv, *wo, *wgu, *wd;
 };
 
 struct Buffers {
@@ -44,7 +46,8 @@ struct Buffers {
   // activations
   float* h; void* u; float* qkv; void* q; void* attn; float* gu; void* act; void* u_lm;
   float* logits; float4* partials;
-  // packed matrices (bf16 only)
+  // bf16 only: row sums of squares [2L+1][sumsq_stride] (32.32 fixed point), packed matrices
+  unsigned long long* sumsq; int sumsq_stride;
   std::vector<PackedLayer> pl; bf16_t* lm_head_p;
 };
 
@@ -76,16 +79,16 @@ void carve(Carver& c, const ec_model_cfg& m, const ec_decode_cfg& d, int P, Buff
   b.partials = c.take<float4>((size_t)d.block * vocab_reduce_parts(m.vocab));
   b.pl.clear();
   b.lm_head_p = nullptr;
+  b.sumsq = nullptr;
+  b.sumsq_stride = (int)T16;
   if (m.dtype == EC_BF16) {
+    b.sumsq = c.take<unsigned long long>((size_t)(2 * m.n_layers + 1) * T16);
     b.pl.resize(m.n_layers);
     for (int l = 0; l < m.n_layers; ++l) {
       PackedLayer& p = b.pl[l];
-      p.wq = c.take<bf16_t>(nq * m.d_model);
-      p.wk = c.take<bf16_t>(nkv * m.d_model);
-      p.wv = c.take<bf16_t>(nkv * m.d_model);
+      p.wqkv = c.take<bf16_t>((nq + 2 * nkv) * m.d_model);
       p.wo = c.take<bf16_t>((size_t)m.d_model * nq);
-      p.wg = c.take<bf16_t>((size_t)m.d_ffn * m.d_model);
-      p.wu = c.take<bf16_t>((size_t)m.d_ffn * m.d_model);
+      p.wgu = c.take<bf16_t>((size_t)2 * m.d_ffn * m.d_model);
       p.wd = c.take<bf16_t>((size_t)m.d_model * m.d_ffn);
     }
     b.lm_head_p = c.take<bf16_t>((size_t)m.vocab * m.d_model);
@@ -223,73 +226,103 @@ int upload_and_init_state(ec_ctx* c, const int32_t* prompt_ids) {
 }
 
 // ---- the forward pass of one step over M rows -------------------------------------------------
-int forward(ec_ctx* c, int mode, int M, int n_mb) {
+int forward_f32(ec_ctx* c, int mode, int M, int n_mb) {
   const ec_model_cfg& m = c->m;
   Buffers& b = c->b;
   hipStream_t s = c->stream;
-  const int dt = m.dtype, d = m.d_model, F = m.d_ffn, hd = m.head_dim;
+  const int d = m.d_model, F = m.d_ffn, hd = m.head_dim;
   const int nq = m.n_heads * hd, nkv = m.n_kv_heads * hd, nqkv = nq + 2 * nkv;
   const int* rows = (mode == EC_FULL) ? nullptr : b.rows_partial;
   const int* lm_sel = (mode == EC_FULL) ? b.mb_pos : b.mb_idx;
+  float* u = (float*)b.u; float* q = (float*)b.q; float* attn = (float*)b.attn;
+  float* act = (float*)b.act; float* u_lm = (float*)b.u_lm;
+  auto W = [](const void* p) { return (const float*)p; };
 
-  { Scope p(c, EC_K_EMBED); launch_embed(dt, c->w.tok_emb, b.x, rows, M, d, b.h, s); }
+  { Scope p(c, EC_K_EMBED); launch_embed_f32(W(c->w.tok_emb), b.x, rows, M, d, b.h, s); }
   for (int l = 0; l < m.n_layers; ++l) {
+    float* kc = (float*)kv_ptr(c, l, 0); float* vc = (float*)kv_ptr(c, l, 1);
     { Scope p(c, EC_K_NORM);
-      launch_rmsnorm(dt, b.h, nullptr, M, d, c->attn_norm[l], m.rms_eps, b.u, s); }
+      launch_rmsnorm_f32(b.h, nullptr, M, d, W(c->attn_norm[l]), m.rms_eps, u, s); }
     { Scope p(c, EC_K_QKV);
-      if (dt == EC_F32) {
-        launch_gemm_f32((const float*)b.u, (const float*)c->wq[l], b.qkv, nqkv, M, nq, d, 0, 1.f, s);
-        launch_gemm_f32((const float*)b.u, (const float*)c->wk[l], b.qkv + nq, nqkv, M, nkv, d, 0, 1.f, s);
-        launch_gemm_f32((const float*)b.u, (const float*)c->wv[l], b.qkv + nq + nkv, nqkv, M, nkv, d, 0, 1.f, s);
-      } else {
-        GemmSegs sg{{b.pl[l].wq, b.pl[l].wk, b.pl[l].wv}, {nq / 16, nkv / 16, nkv / 16}, 3};
-        launch_gemm_bf16((const bf16_t*)b.u, M, sg, d, b.qkv, nqkv, 0, 1.f, s);
-      } }
+      launch_gemm_f32(u, W(c->wq[l]), b.qkv, nqkv, M, nq, d, 0, 1.f, s);
+      launch_gemm_f32(u, W(c->wk[l]), b.qkv + nq, nqkv, M, nkv, d, 0, 1.f, s);
+      launch_gemm_f32(u, W(c->wv[l]), b.qkv + nq + nkv, nqkv, M, nkv, d, 0, 1.f, s); }
     { Scope p(c, EC_K_ROPE_KV);
-      launch_rope_scatter(dt, b.qkv, rows, M, m.n_heads, m.n_kv_heads, hd, b.rope_cs, b.q,
-                          kv_ptr(c, l, 0), kv_ptr(c, l, 1), kv_keys(dt, c->T), s); }
+      launch_rope_scatter_f32(b.qkv, rows, M, m.n_heads, m.n_kv_heads, hd, b.rope_cs, q, kc, vc, s); }
     { Scope p(c, EC_K_ATTN);
-      launch_attention(dt, b.q, kv_ptr(c, l, 0), kv_ptr(c, l, 1), M, c->T, kv_keys(dt, c->T),
-                       m.n_heads, m.n_kv_heads, hd, b.attn, s); }
-    { Scope p(c, EC_K_OPROJ);
-      if (dt == EC_F32) {
-        launch_gemm_f32((const float*)b.attn, (const float*)c->wo[l], b.h, d, M, d, nq, 1, 1.f, s);
-      } else {
-        GemmSegs sg{{b.pl[l].wo, nullptr, nullptr}, {d / 16, 0, 0}, 1};
-        launch_gemm_bf16((const bf16_t*)b.attn, M, sg, nq, b.h, d, 1, 1.f, s);
-      } }
+      launch_attention_f32(q, kc, vc, M, c->T, m.n_heads, m.n_kv_heads, hd, attn, s); }
+    { Scope p(c, EC_K_OPROJ); launch_gemm_f32(attn, W(c->wo[l]), b.h, d, M, d, nq, 1, 1.f, s); }
     { Scope p(c, EC_K_NORM);
-      launch_rmsnorm(dt, b.h, nullptr, M, d, c->mlp_norm[l], m.rms_eps, b.u, s); }
+      launch_rmsnorm_f32(b.h, nullptr, M, d, W(c->mlp_norm[l]), m.rms_eps, u, s); }
     { Scope p(c, EC_K_GATEUP);
-      if (dt == EC_F32) {
-        launch_gemm_f32((const float*)b.u, (const float*)c->w_gate[l], b.gu, 2 * F, M, F, d, 0, 1.f, s);
-        launch_gemm_f32((const float*)b.u, (const float*)c->w_up[l], b.gu + F, 2 * F, M, F, d, 0, 1.f, s);
-      } else {
-        GemmSegs sg{{b.pl[l].wg, b.pl[l].wu, nullptr}, {F / 16, F / 16, 0}, 2};
-        launch_gemm_bf16((const bf16_t*)b.u, M, sg, d, b.gu, 2 * F, 0, 1.f, s);
-      } }
-    { Scope p(c, EC_K_SWIGLU); launch_swiglu(dt, b.gu, M, F, b.act, s); }
-    { Scope p(c, EC_K_DOWN);
-      if (dt == EC_F32) {
-        launch_gemm_f32((const float*)b.act, (const float*)c->w_down[l], b.h, d, M, d, F, 1, 1.f, s);
-      } else {
-        GemmSegs sg{{b.pl[l].wd, nullptr, nullptr}, {d / 16, 0, 0}, 1};
-        launch_gemm_bf16((const bf16_t*)b.act, M, sg, F, b.h, d, 1, 1.f, s);
-      } }
+      launch_gemm_f32(u, W(c->w_gate[l]), b.gu, 2 * F, M, F, d, 0, 1.f, s);
+      launch_gemm_f32(u, W(c->w_up[l]), b.gu + F, 2 * F, M, F, d, 0, 1.f, s); }
+    { Scope p(c, EC_K_SWIGLU); launch_swiglu_f32(b.gu, M, F, act, s); }
+    { Scope p(c, EC_K_DOWN); launch_gemm_f32(act, W(c->w_down[l]), b.h, d, M, d, F, 1, 1.f, s); }
   }
-  // logits only for the block's masked rows, then the fused-order vocabulary reduction
+  // logits only for the block's masked rows
   { Scope p(c, EC_K_NORM);
-    launch_rmsnorm(dt, b.h, lm_sel, n_mb, d, c->w.final_norm, m.rms_eps, b.u_lm, s); }
+    launch_rmsnorm_f32(b.h, lm_sel, n_mb, d, W(c->w.final_norm), m.rms_eps, u_lm, s); }
   { Scope p(c, EC_K_LMHEAD);
-    if (dt == EC_F32) {
-      launch_gemm_f32((const float*)b.u_lm, (const float*)c->w.lm_head, b.logits, m.vocab, n_mb,
-                      m.vocab, d, 0, m.logit_scale, s);
-    } else {
-      GemmSegs sg{{b.lm_head_p, nullptr, nullptr}, {m.vocab / 16, 0, 0}, 1};
-      launch_gemm_bf16((const bf16_t*)b.u_lm, n_mb, sg, d, b.logits, m.vocab, 0, m.logit_scale, s);
-    } }
+    launch_gemm_f32(u_lm, W(c->w.lm_head), b.logits, m.vocab, n_mb, m.vocab, d, 0, m.logit_scale, s); }
+  return EC_OK;
+}
+
+// bf16: five launches per layer.  Norms, RoPE, the KV scatter, SwiGLU and the residual adds run
+// in the GEMM epilogues; `u` always holds the next GEMM's operand bf16(h * gain).
+int forward_bf16(ec_ctx* c, int mode, int M, int n_mb) {
+  const ec_model_cfg& m = c->m;
+  Buffers& b = c->b;
+  hipStream_t s = c->stream;
+  const int d = m.d_model, F = m.d_ffn, hd = m.head_dim, L = m.n_layers;
+  const int nq = m.n_heads * hd, nkv = m.n_kv_heads * hd, nqkv = nq + 2 * nkv;
+  const int Tpad = kv_keys(EC_BF16, c->T), MT = (M + 15) / 16;
+  const int* rows = (mode == EC_FULL) ? nullptr : b.rows_partial;
+  const int* lm_sel = (mode == EC_FULL) ? b.mb_pos : b.mb_idx;
+  bf16_t* u = (bf16_t*)b.u; bf16_t* q = (bf16_t*)b.q; bf16_t* attn = (bf16_t*)b.attn;
+  bf16_t* act = (bf16_t*)b.act;
+  auto G = [](const void* p) { return (const bf16_t*)p; };
+  auto sums = [&](int i) { return b.sumsq + (size_t)i * b.sumsq_stride; };
+
+  { Scope p(c, EC_K_EMBED);
+    launch_embed_bf16(G(c->w.tok_emb), b.x, rows, M, d, G(c->attn_norm[0]), b.h, u, b.sumsq,
+                      2 * L + 1, b.sumsq_stride, s); }
+  for (int l = 0; l < L; ++l) {
+    bf16_t* kc = (bf16_t*)kv_ptr(c, l, 0); bf16_t* vc = (bf16_t*)kv_ptr(c, l, 1);
+    { Scope p(c, EC_K_QKV);
+      GemmEpi e{}; e.M = M; e.MT = MT; e.sumsq_in = sums(2 * l); e.d_in = d; e.eps = m.rms_eps;
+      e.rows = rows; e.cs = b.rope_cs; e.Hq = m.n_heads; e.Hkv = m.n_kv_heads; e.hd = hd;
+      e.Tpad = Tpad; e.q_out = q; e.kc = kc; e.vc = vc;
+      launch_gemm_bf16(EPI_QKV, u, M, b.pl[l].wqkv, nqkv, d, e, s); }
+    { Scope p(c, EC_K_ATTN);
+      launch_attention_mfma(q, kc, vc, M, c->T, Tpad, m.n_heads, m.n_kv_heads, hd, attn, s); }
+    { Scope p(c, EC_K_OPROJ);
+      GemmEpi e{}; e.M = M; e.MT = MT; e.h = b.h; e.d = d; e.gain_next = G(c->mlp_norm[l]);
+      e.a_next = u; e.sumsq_out = sums(2 * l + 1);
+      launch_gemm_bf16(EPI_RESID, attn, M, b.pl[l].wo, d, nq, e, s); }
+    { Scope p(c, EC_K_GATEUP);
+      GemmEpi e{}; e.M = M; e.MT = MT; e.sumsq_in = sums(2 * l + 1); e.d_in = d; e.eps = m.rms_eps;
+      e.act = act;
+      launch_gemm_bf16(EPI_SWIGLU, u, M, b.pl[l].wgu, 2 * F, d, e, s); }
+    { Scope p(c, EC_K_DOWN);
+      GemmEpi e{}; e.M = M; e.MT = MT; e.h = b.h; e.d = d;
+      e.gain_next = G(l + 1 < L ? c->attn_norm[l + 1] : c->w.final_norm);
+      e.a_next = u; e.sumsq_out = sums(2 * l + 2);
+      launch_gemm_bf16(EPI_RESID, act, M, b.pl[l].wd, d, F, e, s); }
+  }
+  // logits only for the block's masked rows: the LM head gathers them from `u`
+  { Scope p(c, EC_K_LMHEAD);
+    GemmEpi e{}; e.M = n_mb; e.MT = (n_mb + 15) / 16; e.row_sel = lm_sel; e.sumsq_in = sums(2 * L);
+    e.d_in = d; e.eps = m.rms_eps; e.scale = m.logit_scale; e.logits = b.logits; e.ldc = m.vocab;
+    launch_gemm_bf16(EPI_LOGITS, u, M, b.lm_head_p, m.vocab, d, e, s); }
+  return EC_OK;
+}
+
+int forward(ec_ctx* c, int mode, int M, int n_mb) {
+  int rc = (c->m.dtype == EC_F32) ? forward_f32(c, mode, M, n_mb) : forward_bf16(c, mode, M, n_mb);
+  if (rc != EC_OK) return rc;
   { Scope p(c, EC_K_VOCAB_REDUCE);
-    launch_vocab_reduce(b.logits, n_mb, m.vocab, b.partials, s); }
+    launch_vocab_reduce(c->b.logits, n_mb, c->m.vocab, c->b.partials, c->stream); }
   EC_HIP(c, hipGetLastError());
   return EC_OK;
 }
@@ -453,17 +486,22 @@ int ec_init(ec_ctx** out, const ec_model_cfg* model, const ec_weights* weights,
     if (e != hipSuccess) return bail(EC_ERR_HIP, std::string("hipMemsetAsync: ") + hipGetErrorString(e));
     const int d = c->m.d_model, F = c->m.d_ffn;
     const int nq = c->m.n_heads * c->m.head_dim, nkv = c->m.n_kv_heads * c->m.head_dim;
+    const int hd = c->m.head_dim;
+    auto B = [](const void* p) { return (const bf16_t*)p; };
     for (int l = 0; l < L; ++l) {
       PackedLayer& p = c->b.pl[l];
-      launch_repack_weight((const bf16_t*)c->wq[l], nq, d, p.wq, c->stream);
-      launch_repack_weight((const bf16_t*)c->wk[l], nkv, d, p.wk, c->stream);
-      launch_repack_weight((const bf16_t*)c->wv[l], nkv, d, p.wv, c->stream);
-      launch_repack_weight((const bf16_t*)c->wo[l], d, nq, p.wo, c->stream);
-      launch_repack_weight((const bf16_t*)c->w_gate[l], F, d, p.wg, c->stream);
-      launch_repack_weight((const bf16_t*)c->w_up[l], F, d, p.wu, c->stream);
-      launch_repack_weight((const bf16_t*)c->w_down[l], d, F, p.wd, c->stream);
+      launch_repack_weight(B(c->wq[l]), nq, d, p.wqkv, REPACK_ROPE_PAIRS, hd, c->stream);
+      launch_repack_weight(B(c->wk[l]), nkv, d, p.wqkv + (size_t)nq * d, REPACK_ROPE_PAIRS, hd,
+                           c->stream);
+      launch_repack_weight(B(c->wv[l]), nkv, d, p.wqkv + (size_t)(nq + nkv) * d, REPACK_PLAIN, hd,
+                           c->stream);
+      launch_repack_weight(B(c->wo[l]), d, nq, p.wo, REPACK_PLAIN, hd, c->stream);
+      launch_repack_weight(B(c->w_gate[l]), F, d, p.wgu, REPACK_EVEN, hd, c->stream);
+      launch_repack_weight(B(c->w_up[l]), F, d, p.wgu, REPACK_ODD, hd, c->stream);
+      launch_repack_weight(B(c->w_down[l]), d, F, p.wd, REPACK_PLAIN, hd, c->stream);
     }
-    launch_repack_weight((const bf16_t*)c->w.lm_head, c->m.vocab, d, c->b.lm_head_p, c->stream);
+    launch_repack_weight(B(c->w.lm_head), c->m.vocab, d, c->b.lm_head_p, REPACK_PLAIN, hd,
+                         c->stream);
   }
   e = hipGetLastError();
   if (e != hipSuccess) return bail(EC_ERR_HIP, std::string("set-up kernels: ") + hipGetErrorString(e));

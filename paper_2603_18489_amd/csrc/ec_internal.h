@@ -57,40 +57,70 @@ struct DecideArgs {
 };
 
 // ---- launchers (each enqueues on `s`; shapes are validated by the caller) --------------------
-void launch_embed(int dtype, const void* emb, const int* x, const int* rows, int M, int d,
-                  float* h, hipStream_t s);
-// out: row-major float [M,d] (dtype f32) or packed bf16 activations with MT = ceil(M/16).
-// sel (nullable) gathers source rows: out row r comes from h row sel[r].
-void launch_rmsnorm(int dtype, const float* h, const int* sel, int M, int d, const void* gain,
-                    float eps, void* out, hipStream_t s);
+// float32 path
+void launch_embed_f32(const float* emb, const int* x, const int* rows, int M, int d, float* h,
+                      hipStream_t s);
+// out row r = rmsnorm(h row sel[r] (or r)) * gain
+void launch_rmsnorm_f32(const float* h, const int* sel, int M, int d, const float* gain, float eps,
+                        float* out, hipStream_t s);
 void launch_rope_table(float2* cs, int T, int hd, float base, hipStream_t s);
-// f32: caches are row-major [T, Hkv*hd].  bf16: packed per kv head (k_common.h), Tpad keys.
-void launch_rope_scatter(int dtype, const float* qkv, const int* rows, int M, int Hq, int Hkv,
-                         int hd, const float2* cs, void* q_out, void* kcache, void* vcache,
-                         int Tpad, hipStream_t s);
-// bf16 only: packed cache of one layer -> row-major [T, Hkv*hd] (debug read-back).
-void launch_unpack_cache(const bf16_t* packed, int is_v, int T, int Tpad, int Hkv, int hd,
-                         bf16_t* out, hipStream_t s);
-void launch_swiglu(int dtype, const float* gu, int M, int F, void* act, hipStream_t s);
-void launch_repack_weight(const bf16_t* W, int N, int K, bf16_t* Wp, hipStream_t s);
-
+// caches row-major [T, Hkv*hd]
+void launch_rope_scatter_f32(const float* qkv, const int* rows, int M, int Hq, int Hkv, int hd,
+                             const float2* cs, float* q_out, float* kcache, float* vcache,
+                             hipStream_t s);
+void launch_swiglu_f32(const float* gu, int M, int F, float* act, hipStream_t s);
 // C[M,N] (ldc) = scale * A[M,K] W[N,K]^T, or C += ... when accumulate.
 void launch_gemm_f32(const float* A, const float* W, float* C, int ldc, int M, int N, int K,
                      int accumulate, float scale, hipStream_t s);
-// bf16: A packed activations (M rows), up to 3 packed weight segments laid side by side along N.
-struct GemmSegs {
-  const bf16_t* w[3];
-  int ntiles[3];  // 16-row tiles per segment
-  int nseg;
+void launch_attention_f32(const float* q, const float* kc, const float* vc, int M, int T, int Hq,
+                          int Hkv, int hd, float* out, hipStream_t s);
+
+// bf16 path
+enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3 };
+enum { REPACK_PLAIN = 0, REPACK_ROPE_PAIRS = 1, REPACK_EVEN = 2, REPACK_ODD = 3 };
+
+// What a GEMM epilogue needs (k_gemm_bf16.hip).  Row sums of squares are 32.32 fixed point.
+struct GemmEpi {
+  int M;                          // activation rows of this launch
+  int MT;                         // m-tiles of the packed buffers written (a_next, act)
+  const int* row_sel;             // nullable: activation row m is read from source row row_sel[m]
+  const unsigned long long* sumsq_in;  // per SOURCE row: sum of squares of the normed input
+  int d_in;                       // its length
+  float eps;
+  float scale;                    // EPI_LOGITS
+  float* logits; int ldc;
+  float* h; int d;                // EPI_RESID: residual stream [M, d]
+  const bf16_t* gain_next;        // gain of the norm that follows
+  bf16_t* a_next;                 // packed bf16(h * gain_next)
+  unsigned long long* sumsq_out;  // per row, accumulated with integer atomics
+  bf16_t* act;                    // EPI_SWIGLU: packed activations, K = d_ffn
+  const int* rows;                // EPI_QKV: position of each row (nullable = identity)
+  const float2* cs;               // RoPE table [T][hd/2]
+  int Hq, Hkv, hd, Tpad;
+  bf16_t* q_out;                  // [M, Hq*hd] row-major
+  bf16_t* kc; bf16_t* vc;         // the layer's packed caches
 };
-void launch_gemm_bf16(const bf16_t* Ap, int M, const GemmSegs& segs, int K, float* C, int ldc,
-                      int accumulate, float scale, hipStream_t s);
 
-// Non-causal attention of M query rows against all T cached positions.
-// q row-major [M, Hq*hd]; caches [T, Hkv*hd]; out row-major float (f32) or packed bf16.
-void launch_attention(int dtype, const void* q, const void* kc, const void* vc, int M, int T,
-                      int Tpad, int Hq, int Hkv, int hd, void* out, hipStream_t s);
+// h = Emb[x[pos]], packed bf16(h * gain) for the first GEMM, the rows' sums of squares into
+// sumsq[0..M), and zeroes the nbuf-1 further sum buffers (stride sumsq_stride) of the step.
+void launch_embed_bf16(const bf16_t* emb, const int* x, const int* rows, int M, int d,
+                       const bf16_t* gain, float* h, bf16_t* a_out, unsigned long long* sumsq,
+                       int nbuf, int sumsq_stride, hipStream_t s);
+// Re-tiles W[N,K] (row-major) into fragment order.  mode picks the destination tile of each
+// source tile: plain, rotary pairs (columns j and j+hd/2 of a head in adjacent tiles), or the
+// even / odd tiles of a two-matrix interleave.
+void launch_repack_weight(const bf16_t* W, int N, int K, bf16_t* Wp, int mode, int hd,
+                          hipStream_t s);
+void launch_unpack_cache(const bf16_t* packed, int is_v, int T, int Tpad, int Hkv, int hd,
+                         bf16_t* out, hipStream_t s);
+// A: packed activations holding M_src rows; W: packed [N/16 tiles][K/32]; see GemmEpi.
+void launch_gemm_bf16(int epi, const bf16_t* Ap, int M_src, const bf16_t* Wp, int N, int K,
+                      const GemmEpi& e, hipStream_t s);
+// q row-major [M, Hq*hd]; packed caches of one layer; out packed bf16 (K = Hq*hd).
+void launch_attention_mfma(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int M, int T,
+                           int Tpad, int Hq, int Hkv, int hd, bf16_t* out, hipStream_t s);
 
+// decision
 int vocab_reduce_parts(int V);
 void launch_vocab_reduce(const float* logits, int n_rows, int V, float4* partials, hipStream_t s);
 void launch_decide(const DecideArgs& a, hipStream_t s);

@@ -237,11 +237,9 @@ static void launch_attn_mfma_hd(const bf16_t* q, const uint4* kp, const uint4* v
   const int G = Hq / Hkv, nQ = M * G, qtiles = (nQ + 15) / 16, MT = (M + 15) / 16;
   const float sc = 1.4426950408889634f / sqrtf((float)HD);
   if (qtiles <= 64) {
-    // few queries: split the keys over the waves of a block
+    // few queries: split the keys over the waves of a block, at most 2 query tiles per block
     if (qtiles <= 1) launch_split<HD, 1>(q, kp, vp, M, T, Tpad, Hq, Hkv, sc, out, MT, qtiles, s);
-    else if (qtiles == 2 || qtiles == 4)
-      launch_split<HD, 2>(q, kp, vp, M, T, Tpad, Hq, Hkv, sc, out, MT, qtiles, s);
-    else launch_split<HD, 3>(q, kp, vp, M, T, Tpad, Hq, Hkv, sc, out, MT, qtiles, s);
+    else launch_split<HD, 2>(q, kp, vp, M, T, Tpad, Hq, Hkv, sc, out, MT, qtiles, s);
   } else {
     constexpr int QT = 2, NW = 4;
     dim3 grid((qtiles + QT * NW - 1) / (QT * NW), Hkv);
@@ -252,6 +250,7 @@ static void launch_attn_mfma_hd(const bf16_t* q, const uint4* kp, const uint4* v
 
 void launch_attention_mfma(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int M, int T,
                            int Tpad, int Hq, int Hkv, int hd, bf16_t* out, hipStream_t s) {
+  if (M <= 0) return;
   if (hd == 64)
     launch_attn_mfma_hd<64>(q, (const uint4*)kc, (const uint4*)vc, M, T, Tpad, Hq, Hkv, out, s);
   else

@@ -1,68 +1,175 @@
-// bf16 GEMMs on MFMA: C[M,N] = scale * A[M,K] W[N,K]^T (or C += ...), fp32 accumulation.
+// bf16 GEMMs on MFMA with the layer's element-wise work fused into their epilogues.
 //
-// Both operands arrive re-tiled into 16x32 fragments (k_common.h), so every wave-wide operand
-// load is one contiguous, fully coalesced KiB.  The weight fragment is the MFMA "A" operand
-// (16 weight rows) and the activation fragment the "B" operand (16 activation rows), hence a
-// lane of the 16x16 result holds 4 consecutive output features n of one activation row m.
+// C[M,N] = A[M,K] W[N,K]^T with fp32 accumulation.  Both operands arrive re-tiled into 16x32
+// fragments (k_common.h), so every wave-wide operand load is one contiguous, fully coalesced KiB.
+// The weight fragment is the MFMA "A" operand (16 weight rows) and the activation fragment the
+// "B" operand (16 activation rows): a lane of the 16x16 result holds 4 consecutive output
+// features n of one activation row m.
 //
-//  * skinny kernel (M <= 64): weight streaming.  A block of KS waves owns NTW weight tiles and
-//    splits K across its waves; each wave streams its slice of the weights exactly once from
-//    HBM while the small activation fragments come from L2.  The KS partial tiles are summed
-//    in LDS in a fixed order (deterministic).
-//  * tiled kernel (M > 64): 2x2 waves, block tile chosen per shape (up to 192x192) so that the
-//    grid fills the 256 CUs, K step 32, LDS double buffering with register prefetch two steps
-//    ahead.
+// RMSNorm is folded in: the A operand of a GEMM that follows a norm holds bf16(h * gain), NOT
+// normalised, and the row's 1/rms is applied to the fp32 accumulator in the epilogue (it is a
+// per-row scalar, so it commutes with the contraction).  The sum of squares of each row of h is
+// accumulated by the producing epilogue with integer (fixed-point) atomics, which are
+// order-independent and therefore bit-reproducible.
+//
+// Epilogues (template parameter EPI):
+//   EPI_QKV    x 1/rms, rotary embedding on q and k (weight tiles are stored so that columns j
+//              and j + hd/2 of a head sit in adjacent tiles), q -> query buffer, k / v -> the
+//              packed KV cache rows of the row's position
+//   EPI_RESID  h += result; writes bf16(h * next gain) as the next GEMM's operand and adds the
+//              row's sum of squares
+//   EPI_SWIGLU x 1/rms, silu(gate) * up (gate / up tiles interleaved), -> packed activations
+//   EPI_LOGITS x 1/rms x logit scale -> fp32 logits
+//
+// Kernels:
+//   skinny (M <= 64): weight streaming.  A block of KS waves owns NTW weight tiles and splits K
+//     across its waves; each weight byte is read from HBM exactly once while the small
+//     activation fragments come from L2.  The KS partial tiles are summed in LDS in a fixed
+//     order, then the epilogue runs on the sums.
+//   tiled (M > 64): 2x2 waves, block tile chosen per shape (up to 192x192) so that the grid
+//     fills the 256 CUs, K step 32, LDS double buffering with two register sets of global
+//     loads in flight.
 #include "ec_internal.h"
 
 namespace ec {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
 __device__ __forceinline__ bf16x8 v4_as_bf16x8(u32x4 v) {
   union { u32x4 u; bf16x8 b; } c;
   c.u = v;
   return c.b;
 }
-__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) {
-  union { uint4 u; bf16x8 b; } c;
-  c.u = v;
-  return c.b;
+__device__ __forceinline__ uint32_t pack2(float a, float b) {
+  return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+}
+__device__ __forceinline__ float silu_f(float x) { return x / (1.0f + expf(-x)); }
+
+__device__ __forceinline__ float rstd_of(const GemmEpi& e, int row) {
+  double ss = (double)e.sumsq_in[row] * (1.0 / 4294967296.0);
+  return 1.0f / sqrtf((float)(ss / (double)e.d_in) + e.eps);
 }
 
-// Segment lookup: global n-tile -> pointer to the tile's first fragment (kb = 0), or nullptr
-// past the end.
-__device__ __forceinline__ const uint4* seg_tile_ptr(const GemmSegs& sg, int nt, int KB) {
-  int base = 0;
+// ---- epilogues on one lane's values -----------------------------------------------------------
+// (m: activation row, < M;  vt: virtual weight tile;  q4: lane>>4, so the lane's 4 values are
+// output features vt*16 + q4*4 + 0..3.)
+
+__device__ __forceinline__ void epi_logits(const GemmEpi& e, int m, int vt, int q4, f32x4 v,
+                                           float rs) {
+  float s = rs * e.scale;
+  float4 o = make_float4(v[0] * s, v[1] * s, v[2] * s, v[3] * s);
+  *(float4*)(e.logits + (size_t)m * e.ldc + vt * 16 + q4 * 4) = o;
+}
+
+// returns the lane's contribution to the row's sum of squares
+__device__ __forceinline__ float epi_resid(const GemmEpi& e, int m, int vt, int q4, f32x4 v) {
+  int n = vt * 16 + q4 * 4;
+  float4* hp = (float4*)(e.h + (size_t)m * e.d + n);
+  float4 h = *hp;
+  h.x += v[0]; h.y += v[1]; h.z += v[2]; h.w += v[3];
+  *hp = h;
+  const bf16_t* g = e.gain_next + n;
+  u32x2 pk;
+  pk[0] = pack2(h.x * bf16_to_f32(g[0]), h.y * bf16_to_f32(g[1]));
+  pk[1] = pack2(h.z * bf16_to_f32(g[2]), h.w * bf16_to_f32(g[3]));
+  *(u32x2*)(e.a_next + packed_act_index(m, n, e.MT)) = pk;
+  return h.x * h.x + h.y * h.y + h.z * h.z + h.w * h.w;
+}
+
+__device__ __forceinline__ void epi_add_sumsq(const GemmEpi& e, int m, bool valid, float part) {
+  // the 4 lanes l, l^16, l^32, l^48 hold the same row
+  part += __shfl_xor(part, 16, 64);
+  part += __shfl_xor(part, 32, 64);
+  if (valid && (threadIdx.x & 63) < 16) {
+    unsigned long long fx = (unsigned long long)((double)part * 4294967296.0 + 0.5);
+    atomicAdd((unsigned long long*)(e.sumsq_out + m), fx);
+  }
+}
+
+// gate = tile 2p, up = tile 2p+1 of the interleaved matrix; feature tile p
+__device__ __forceinline__ void epi_swiglu(const GemmEpi& e, int m, int p, int q4, f32x4 g,
+                                           f32x4 u, float rs) {
+  u32x2 pk;
+  pk[0] = pack2(silu_f(g[0] * rs) * (u[0] * rs), silu_f(g[1] * rs) * (u[1] * rs));
+  pk[1] = pack2(silu_f(g[2] * rs) * (u[2] * rs), silu_f(g[3] * rs) * (u[3] * rs));
+  *(u32x2*)(e.act + packed_act_index(m, p * 16 + q4 * 4, e.MT)) = pk;
+}
+
+// Virtual tile pair (2p, 2p+1) of the [q | k | v] matrix.  In the q and k regions the pair
+// holds columns j.. and j+hd/2.. of one head; in the v region the tiles are in natural order.
+__device__ __forceinline__ void epi_qkv(const GemmEpi& e, int m, int vpair, int q4, f32x4 a,
+                                        f32x4 b, float rs) {
+  const int hd = e.hd, tph = hd >> 4;  // tiles per head
+  const int nqt = e.Hq * tph, nkt = e.Hkv * tph;
+  const int vt = vpair * 2;
+  const int pos = e.rows ? e.rows[m] : m;
+  if (vt < nqt + nkt) {
+    const bool is_q = vt < nqt;
+    const int t = is_q ? vt : vt - nqt;
+    const int head = t / tph, j = ((t % tph) >> 1) * 16 + q4 * 4;  // column within the head
+    const float2* cs = e.cs + (size_t)pos * (hd >> 1) + j;
+    float lo[4], hi[4];
 #pragma unroll
-  for (int i = 0; i < 3; ++i) {
-    if (i < sg.nseg) {
-      if (nt < base + sg.ntiles[i])
-        return (const uint4*)sg.w[i] + (size_t)(nt - base) * KB * 64;
-      base += sg.ntiles[i];
+    for (int r = 0; r < 4; ++r) {
+      float x = a[r] * rs, y = b[r] * rs;
+      float2 c = cs[r];
+      lo[r] = x * c.x - y * c.y;
+      hi[r] = y * c.x + x * c.y;
+    }
+    u32x2 plo, phi;
+    plo[0] = pack2(lo[0], lo[1]); plo[1] = pack2(lo[2], lo[3]);
+    phi[0] = pack2(hi[0], hi[1]); phi[1] = pack2(hi[2], hi[3]);
+    if (is_q) {
+      bf16_t* dst = e.q_out + (size_t)m * (e.Hq * hd) + head * hd + j;
+      *(u32x2*)dst = plo;
+      *(u32x2*)(dst + (hd >> 1)) = phi;
+    } else {
+      bf16_t* slab = e.kc + (size_t)head * e.Tpad * hd;
+      *(u32x2*)(slab + kcache_index(pos, j, hd)) = plo;
+      *(u32x2*)(slab + kcache_index(pos, j + (hd >> 1), hd)) = phi;
+    }
+  } else {
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const int t = vt + half - nqt - nkt;
+      const int head = t / tph, c0 = (t % tph) * 16 + q4 * 4;
+      bf16_t* slab = e.vc + (size_t)head * e.Tpad * hd;
+      f32x4 v = half ? b : a;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) slab[vcache_index(pos, c0 + r, e.Tpad)] = f32_to_bf16(v[r] * rs);
     }
   }
-  return nullptr;
 }
 
 // ---------------------------------------------------------------------------------------------
-// skinny: grid = ceil(total n-tiles / NTW) blocks of KS*64 threads
+// skinny: grid = ceil(n-tiles / NTW) blocks of KS*64 threads
 // ---------------------------------------------------------------------------------------------
-template <int MT, int NTW, int KS>
-__global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(
-    const uint4* __restrict__ Ap, GemmSegs sg, int KB, float* __restrict__ C, int ldc, int M,
-    int accumulate, float scale) {
+template <int EPI, int MT, int NTW, int KS>
+__global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* __restrict__ Ap,
+                                                                   const u32x4* __restrict__ Wp,
+                                                                   int total_nt, int KB,
+                                                                   int MT_src, GemmEpi e) {
   extern __shared__ float4 red[];  // [KS][NTW*MT][64]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nt0 = blockIdx.x * NTW;
   const int kb_lo = (int)(((long)wave * KB) / KS), kb_hi = (int)(((long)(wave + 1) * KB) / KS);
 
-  const uint4* wp[NTW];
+  // a tile past the end streams tile 0 instead (valid memory) and is dropped at the store
+  const u32x4* wp[NTW];
 #pragma unroll
   for (int i = 0; i < NTW; ++i) {
-    // a tile past the end streams tile 0 instead (valid memory) and is dropped at the store
-    const uint4* p = seg_tile_ptr(sg, nt0 + i, KB);
-    wp[i] = (p ? p : (const uint4*)sg.w[0]) + (size_t)kb_lo * 64 + lane;
+    int nt = nt0 + i < total_nt ? nt0 + i : 0;
+    wp[i] = Wp + ((size_t)nt * KB + kb_lo) * 64 + lane;
   }
-  const uint4* ap = Ap + (size_t)kb_lo * MT * 64 + lane;
+  // activation rows may be gathered (LM head: only the block's masked rows)
+  const u32x4* ap[MT];
+#pragma unroll
+  for (int j = 0; j < MT; ++j) {
+    int m = j * 16 + (lane & 15);
+    int row = (m < e.M) ? (e.row_sel ? e.row_sel[m] : m) : 0;
+    ap[j] = Ap + ((size_t)kb_lo * MT_src + (row >> 4)) * 64 + (lane >> 4) * 16 + (row & 15);
+  }
 
   f32x4 acc[NTW][MT];
 #pragma unroll
@@ -73,17 +180,17 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(
   const int nkb = kb_hi - kb_lo;
 #pragma unroll 4
   for (int it = 0; it < nkb; ++it) {
-    uint4 wf[NTW], af[MT];
+    u32x4 wf[NTW], af[MT];
 #pragma unroll
     for (int i = 0; i < NTW; ++i) wf[i] = wp[i][(size_t)it * 64];
 #pragma unroll
-    for (int j = 0; j < MT; ++j) af[j] = ap[((size_t)it * MT + j) * 64];
+    for (int j = 0; j < MT; ++j) af[j] = ap[j][(size_t)it * MT_src * 64];
 #pragma unroll
     for (int i = 0; i < NTW; ++i)
 #pragma unroll
       for (int j = 0; j < MT; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wf[i]), as_bf16x8(af[j]),
-                                                            acc[i][j], 0, 0, 0);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v4_as_bf16x8(wf[i]),
+                                                            v4_as_bf16x8(af[j]), acc[i][j], 0, 0, 0);
   }
 
   // fixed-order reduction over the KS waves
@@ -95,53 +202,71 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(
       red[(wave * NTW * MT + i * MT + j) * 64 + lane] = make_float4(v[0], v[1], v[2], v[3]);
     }
   __syncthreads();
-  for (int o = threadIdx.x; o < NTW * MT * 64; o += KS * 64) {
-    float4 s = red[o];
+
+  auto ksum = [&](int idx) {
+    float4 s = red[idx];
 #pragma unroll
     for (int w = 1; w < KS; ++w) {
-      float4 v = red[w * NTW * MT * 64 + o];
+      float4 v = red[w * NTW * MT * 64 + idx];
       s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
     }
-    int l = o & 63, tile = o >> 6, i = tile / MT, j = tile - i * MT;
-    int m = j * 16 + (l & 15);
-    int nt = nt0 + i;
-    if (m < M && seg_tile_ptr(sg, nt, KB) != nullptr) {
-      float4* c = (float4*)(C + (size_t)m * ldc + nt * 16 + (l >> 4) * 4);
-      s.x *= scale; s.y *= scale; s.z *= scale; s.w *= scale;
-      if (accumulate) {
-        float4 old = *c;
-        s.x += old.x; s.y += old.y; s.z += old.z; s.w += old.w;
+    return (f32x4){s.x, s.y, s.z, s.w};
+  };
+
+  constexpr bool PAIR = (EPI == EPI_QKV || EPI == EPI_SWIGLU);
+  static_assert(!PAIR || NTW % 2 == 0, "pair epilogues need an even number of tiles per block");
+  constexpr int UNITS = (PAIR ? NTW / 2 : NTW) * MT * 64;  // whole waves: UNITS % 64 == 0
+  for (int o = threadIdx.x; o < UNITS; o += KS * 64) {
+    const int l = o & 63, unit = o >> 6, iu = unit / MT, j = unit - iu * MT;
+    const int m = j * 16 + (l & 15), q4 = l >> 4;
+    const bool mvalid = m < e.M;
+    if constexpr (EPI == EPI_RESID) {
+      const int vt = nt0 + iu;
+      f32x4 v = ksum((iu * MT + j) * 64 + l);
+      float part = 0.f;
+      if (mvalid && vt < total_nt) part = epi_resid(e, m, vt, q4, v);
+      epi_add_sumsq(e, m, mvalid, part);
+    } else if constexpr (EPI == EPI_LOGITS) {
+      const int vt = nt0 + iu;
+      if (mvalid && vt < total_nt) {
+        f32x4 v = ksum((iu * MT + j) * 64 + l);
+        epi_logits(e, m, vt, q4, v, rstd_of(e, e.row_sel ? e.row_sel[m] : m));
       }
-      *c = s;
+    } else {
+      const int vt = nt0 + 2 * iu;
+      if (mvalid && vt < total_nt) {
+        f32x4 a = ksum(((2 * iu) * MT + j) * 64 + l);
+        f32x4 b = ksum(((2 * iu + 1) * MT + j) * 64 + l);
+        float rs = rstd_of(e, m);
+        if constexpr (EPI == EPI_SWIGLU) epi_swiglu(e, m, vt >> 1, q4, a, b, rs);
+        else epi_qkv(e, m, vt >> 1, q4, a, b, rs);
+      }
     }
   }
 }
 
-template <int MT, int NTW, int KS>
-static void launch_skinny_t(const bf16_t* Ap, int M, const GemmSegs& sg, int total_nt, int KB,
-                            float* C, int ldc, int accumulate, float scale, hipStream_t s) {
+template <int EPI, int MT, int NTW, int KS>
+static void launch_skinny_t(const bf16_t* Ap, int MT_src, const bf16_t* Wp, int total_nt, int KB,
+                            const GemmEpi& e, hipStream_t s) {
   int grid = (total_nt + NTW - 1) / NTW;
   size_t smem = (size_t)KS * NTW * MT * 64 * sizeof(float4);
-  gemm_bf16_skinny_kernel<MT, NTW, KS><<<grid, KS * 64, smem, s>>>((const uint4*)Ap, sg, KB, C, ldc,
-                                                                  M, accumulate, scale);
+  gemm_bf16_skinny_kernel<EPI, MT, NTW, KS><<<grid, KS * 64, smem, s>>>(
+      (const u32x4*)Ap, (const u32x4*)Wp, total_nt, KB, MT_src, e);
 }
 
-template <int MT>
-static void launch_skinny_mt(const bf16_t* Ap, int M, const GemmSegs& sg, int total_nt, int KB,
-                             float* C, int ldc, int accumulate, float scale, hipStream_t s) {
-  // enough blocks to cover 256 CUs a few times over, as many weight tiles per block as that allows
-  if (total_nt >= 4096)
-    launch_skinny_t<MT, 4, 4>(Ap, M, sg, total_nt, KB, C, ldc, accumulate, scale, s);
-  else if (total_nt >= 1024)
-    launch_skinny_t<MT, 2, 8>(Ap, M, sg, total_nt, KB, C, ldc, accumulate, scale, s);
+template <int EPI, int MT>
+static void launch_skinny_mt(const bf16_t* Ap, int MT_src, const bf16_t* Wp, int total_nt, int KB,
+                             const GemmEpi& e, hipStream_t s) {
+  if constexpr (EPI == EPI_LOGITS)
+    launch_skinny_t<EPI, MT, 4, 4>(Ap, MT_src, Wp, total_nt, KB, e, s);
+  else if constexpr (EPI == EPI_RESID)
+    launch_skinny_t<EPI, MT, 1, 8>(Ap, MT_src, Wp, total_nt, KB, e, s);
   else
-    launch_skinny_t<MT, 1, 8>(Ap, M, sg, total_nt, KB, C, ldc, accumulate, scale, s);
+    launch_skinny_t<EPI, MT, 2, 8>(Ap, MT_src, Wp, total_nt, KB, e, s);
 }
 
 // ---------------------------------------------------------------------------------------------
 // tiled: 2x2 waves, wave tile = WTM x WTN fragments of 16 rows (activations x weights), K step 32.
-// Operands are double-buffered in LDS; global loads run R k-steps ahead through R register sets
-// so that L2/HBM latency is covered by R iterations of MFMA work.
 // grid = (ceil(n-tiles / (2*WTN)), ceil(m-tiles / (2*WTM)))
 // ---------------------------------------------------------------------------------------------
 #define EC_TILED_GLOAD(REGS, KBV)                                                   \
@@ -159,22 +284,22 @@ static void launch_skinny_mt(const bf16_t* Ap, int M, const GemmSegs& sg, int to
   {                                                                                 \
     bf16x8 af_[WTM], wf_[WTN];                                                      \
     _Pragma("unroll") for (int j = 0; j < WTM; ++j)                                 \
-        af_[j] = v4_as_bf16x8(lds[STAGE][wm * WTM + j][lane]);                         \
+        af_[j] = v4_as_bf16x8(lds[STAGE][wm * WTM + j][lane]);                      \
     _Pragma("unroll") for (int i = 0; i < WTN; ++i)                                 \
-        wf_[i] = v4_as_bf16x8(lds[STAGE][BMT + wn * WTN + i][lane]);                   \
+        wf_[i] = v4_as_bf16x8(lds[STAGE][BMT + wn * WTN + i][lane]);                \
     _Pragma("unroll") for (int i = 0; i < WTN; ++i)                                 \
       _Pragma("unroll") for (int j = 0; j < WTM; ++j)                               \
         acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf_[i], af_[j], acc[i][j], 0, 0, 0); \
   }
 
-template <int WTM, int WTN>
+template <int EPI, int WTM, int WTN>
 __global__ __launch_bounds__(256) void gemm_bf16_tiled_kernel(const u32x4* __restrict__ Ap,
-                                                              GemmSegs sg, int total_nt, int KB,
-                                                              int MT, float* __restrict__ C,
-                                                              int ldc, int M, int accumulate,
-                                                              float scale) {
+                                                              const u32x4* __restrict__ Wp,
+                                                              int total_nt, int KB, int MT,
+                                                              GemmEpi e) {
   constexpr int BMT = 2 * WTM, BNT = 2 * WTN, NF = BMT + BNT;  // fragments per k-step
   constexpr int LF = (NF + 3) / 4;                             // fragments loaded per wave
+  static_assert(WTN % 2 == 0, "pair epilogues need an even number of weight tiles per wave");
   __shared__ u32x4 lds[2][NF][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int mt0 = blockIdx.y * BMT, nt0 = blockIdx.x * BNT;
@@ -184,7 +309,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_tiled_kernel(const u32x4* __res
   // A fragment outside the matrix streams fragment 0 instead (valid memory); what it produces
   // lands in rows / columns that are never stored.
   const u32x4* src[LF];
-  size_t stride[LF];  // uint4 per k-step
+  size_t stride[LF];  // u32x4 per k-step
 #pragma unroll
   for (int i = 0; i < LF; ++i) {
     int f = wave + 4 * i;
@@ -193,9 +318,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_tiled_kernel(const u32x4* __res
     if (f < BMT) {
       int mt = mt0 + f;
       if (mt < MT) src[i] = Ap + (size_t)mt * 64 + lane;
-    } else {
-      const u32x4* p = (const u32x4*)seg_tile_ptr(sg, nt0 + (f - BMT), KB);
-      if (f < NF && p) { src[i] = p + lane; stride[i] = 64; }
+    } else if (f < NF) {
+      int nt = nt0 + (f - BMT);
+      if (nt < total_nt) { src[i] = Wp + (size_t)nt * KB * 64 + lane; stride[i] = 64; }
     }
   }
 
@@ -227,22 +352,40 @@ __global__ __launch_bounds__(256) void gemm_bf16_tiled_kernel(const u32x4* __res
     __syncthreads();
   }
 
+  const int q4 = lane >> 4;
 #pragma unroll
-  for (int i = 0; i < WTN; ++i) {
-    int nt = nt0 + wn * WTN + i;
-    if (nt >= total_nt) continue;
+  for (int j = 0; j < WTM; ++j) {
+    const int m = (mt0 + wm * WTM + j) * 16 + (lane & 15);
+    const bool mvalid = m < e.M;
+    if constexpr (EPI == EPI_RESID) {
+      float part = 0.f;
 #pragma unroll
-    for (int j = 0; j < WTM; ++j) {
-      int m = (mt0 + wm * WTM + j) * 16 + (lane & 15);
-      if (m >= M) continue;
-      float4* c = (float4*)(C + (size_t)m * ldc + nt * 16 + (lane >> 4) * 4);
-      f32x4 v = acc[i][j];
-      float4 o = make_float4(v[0] * scale, v[1] * scale, v[2] * scale, v[3] * scale);
-      if (accumulate) {
-        float4 old = *c;
-        o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w;
+      for (int i = 0; i < WTN; ++i) {
+        int vt = nt0 + wn * WTN + i;
+        if (mvalid && vt < total_nt) part += epi_resid(e, m, vt, q4, acc[i][j]);
       }
-      *c = o;
+      epi_add_sumsq(e, m, mvalid, part);
+    } else if constexpr (EPI == EPI_LOGITS) {
+      if (mvalid) {
+        float rs = rstd_of(e, e.row_sel ? e.row_sel[m] : m);
+#pragma unroll
+        for (int i = 0; i < WTN; ++i) {
+          int vt = nt0 + wn * WTN + i;
+          if (vt < total_nt) epi_logits(e, m, vt, q4, acc[i][j], rs);
+        }
+      }
+    } else {
+      if (mvalid) {
+        float rs = rstd_of(e, m);
+#pragma unroll
+        for (int i = 0; i < WTN; i += 2) {
+          int vt = nt0 + wn * WTN + i;
+          if (vt < total_nt) {
+            if constexpr (EPI == EPI_SWIGLU) epi_swiglu(e, m, vt >> 1, q4, acc[i][j], acc[i + 1][j], rs);
+            else epi_qkv(e, m, vt >> 1, q4, acc[i][j], acc[i + 1][j], rs);
+          }
+        }
+      }
     }
   }
 }
@@ -250,12 +393,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_tiled_kernel(const u32x4* __res
 #undef EC_TILED_LSTORE
 #undef EC_TILED_COMPUTE
 
-template <int WTM, int WTN>
-static void launch_tiled_t(const bf16_t* Ap, int M, int MT, const GemmSegs& sg, int total_nt,
-                           int KB, float* C, int ldc, int accumulate, float scale, hipStream_t s) {
+template <int EPI, int WTM, int WTN>
+static void launch_tiled_t(const bf16_t* Ap, int MT, const bf16_t* Wp, int total_nt, int KB,
+                           const GemmEpi& e, hipStream_t s) {
   dim3 grid((total_nt + 2 * WTN - 1) / (2 * WTN), (MT + 2 * WTM - 1) / (2 * WTM));
-  gemm_bf16_tiled_kernel<WTM, WTN><<<grid, 256, 0, s>>>((const u32x4*)Ap, sg, total_nt, KB, MT, C,
-                                                        ldc, M, accumulate, scale);
+  gemm_bf16_tiled_kernel<EPI, WTM, WTN><<<grid, 256, 0, s>>>((const u32x4*)Ap, (const u32x4*)Wp,
+                                                             total_nt, KB, MT, e);
 }
 
 // Picks the block tile whose grid wastes the least of the 256 CUs: the score is the useful
@@ -275,26 +418,45 @@ static int pick_tile(int MT, int total_nt) {
   return best;
 }
 
-void launch_gemm_bf16(const bf16_t* Ap, int M, const GemmSegs& sg, int K, float* C, int ldc,
-                      int accumulate, float scale, hipStream_t s) {
-  if (M <= 0) return;
-  int total_nt = 0;
-  for (int i = 0; i < sg.nseg; ++i) total_nt += sg.ntiles[i];
-  int KB = K / 32, MT = (M + 15) / 16;
+template <int EPI>
+static void launch_epi(const bf16_t* Ap, int M_src, const bf16_t* Wp, int N, int K,
+                       const GemmEpi& e, hipStream_t s) {
+  const int total_nt = N / 16, KB = K / 32, MT = (e.M + 15) / 16, MT_src = (M_src + 15) / 16;
   if (MT <= 4) {
     switch (MT) {
-      case 1: launch_skinny_mt<1>(Ap, M, sg, total_nt, KB, C, ldc, accumulate, scale, s); break;
-      case 2: launch_skinny_mt<2>(Ap, M, sg, total_nt, KB, C, ldc, accumulate, scale, s); break;
-      case 3: launch_skinny_mt<3>(Ap, M, sg, total_nt, KB, C, ldc, accumulate, scale, s); break;
-      default: launch_skinny_mt<4>(Ap, M, sg, total_nt, KB, C, ldc, accumulate, scale, s); break;
+      case 1: launch_skinny_mt<EPI, 1>(Ap, MT_src, Wp, total_nt, KB, e, s); break;
+      case 2: launch_skinny_mt<EPI, 2>(Ap, MT_src, Wp, total_nt, KB, e, s); break;
+      case 3: launch_skinny_mt<EPI, 3>(Ap, MT_src, Wp, total_nt, KB, e, s); break;
+      default: launch_skinny_mt<EPI, 4>(Ap, MT_src, Wp, total_nt, KB, e, s); break;
     }
   } else {
+    // the tiled kernel reads its activation rows in place (no gather): M_src == M
     switch (pick_tile(MT, total_nt)) {
-      case 0: launch_tiled_t<6, 6>(Ap, M, MT, sg, total_nt, KB, C, ldc, accumulate, scale, s); break;
-      case 1: launch_tiled_t<6, 4>(Ap, M, MT, sg, total_nt, KB, C, ldc, accumulate, scale, s); break;
-      case 2: launch_tiled_t<4, 4>(Ap, M, MT, sg, total_nt, KB, C, ldc, accumulate, scale, s); break;
-      default: launch_tiled_t<3, 4>(Ap, M, MT, sg, total_nt, KB, C, ldc, accumulate, scale, s); break;
+      case 0: launch_tiled_t<EPI, 6, 6>(Ap, MT, Wp, total_nt, KB, e, s); break;
+      case 1: launch_tiled_t<EPI, 6, 4>(Ap, MT, Wp, total_nt, KB, e, s); break;
+      case 2: launch_tiled_t<EPI, 4, 4>(Ap, MT, Wp, total_nt, KB, e, s); break;
+      default: launch_tiled_t<EPI, 3, 4>(Ap, MT, Wp, total_nt, KB, e, s); break;
     }
+  }
+}
+
+void launch_gemm_bf16(int epi, const bf16_t* Ap, int M_src, const bf16_t* Wp, int N, int K,
+                      const GemmEpi& e, hipStream_t s) {
+  if (e.M <= 0) return;
+  switch (epi) {
+    case EPI_QKV: launch_epi<EPI_QKV>(Ap, M_src, Wp, N, K, e, s); break;
+    case EPI_RESID: launch_epi<EPI_RESID>(Ap, M_src, Wp, N, K, e, s); break;
+    case EPI_SWIGLU: launch_epi<EPI_SWIGLU>(Ap, M_src, Wp, N, K, e, s); break;
+    default:
+      // gathered rows are only handled by the skinny kernel: more than 64 rows go in chunks
+      for (int r0 = 0; r0 < e.M; r0 += 64) {
+        GemmEpi c = e;
+        c.M = e.M - r0 < 64 ? e.M - r0 : 64;
+        c.row_sel = e.row_sel + r0;
+        c.logits = e.logits + (size_t)r0 * e.ldc;
+        launch_epi<EPI_LOGITS>(Ap, M_src, Wp, N, K, c, s);
+      }
+      break;
   }
 }
 
