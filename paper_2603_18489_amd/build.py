@@ -25,6 +25,34 @@ def _hipcc() -> str:
     return "hipcc"
 
 
+MFMA_SOURCES = ["k_gemm_bf16.hip", "k_attn_mfma.hip"]
+
+
+def check_no_masked_mfma(hipcc: str) -> None:
+    """MFMA instructions ignore the EXEC mask.  If the compiler if-converts a guarded MFMA into
+    an EXEC-masked one (it does so for conditions it cannot prove wave-uniform), the MFMA runs
+    anyway and corrupts the accumulator.  This scans the generated ISA and fails the build if an
+    MFMA sits inside an EXEC-masked region that has no branch around it."""
+    for src in MFMA_SOURCES:
+        asm = os.path.join(OBJ_DIR, src.replace(".hip", ".s"))
+        cmd = [hipcc, *FLAGS, "-S", "--cuda-device-only", os.path.join(CSRC, src), "-o", asm]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc -S failed on {src}:\n{r.stderr}")
+        masked, kernel = False, "?"
+        for line in open(asm):
+            t = line.strip()
+            if line.startswith("_ZN2ec") and ":" in line:
+                kernel = line.split(":")[0]
+            if t.startswith(("s_and_saveexec", "s_andn2_saveexec", "s_or_saveexec")):
+                masked = True
+            elif t.startswith(("s_cbranch_exec", "s_or_b64 exec", "s_mov_b64 exec")):
+                masked = False
+            elif t.startswith("v_mfma") and masked:
+                raise RuntimeError(f"{src}: EXEC-masked MFMA in {kernel}: make its condition "
+                                   "wave-uniform (readfirstlane) or remove the guard")
+
+
 def build(verbose: bool = False) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
     hipcc = _hipcc()
@@ -42,8 +70,10 @@ def build(verbose: bool = False) -> str:
             print(out, file=sys.stderr)
         return obj
 
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES) + 1)) as pool:
+        chk = pool.submit(check_no_masked_mfma, hipcc)
         objs = list(pool.map(compile_one, SOURCES))
+        chk.result()
     cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:

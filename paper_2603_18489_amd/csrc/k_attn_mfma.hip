@@ -35,7 +35,9 @@ __global__ __launch_bounds__(SPLIT_KEYS ? 512 : 256) void attn_mfma_kernel(
     int MT) {
   constexpr int HB = HD / 32, HT = HD / 16;
   extern __shared__ float4 lds[];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, NW = blockDim.x >> 6;
+  // scalar wave index: no MFMA may sit under a condition the compiler could treat as divergent
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int NW = blockDim.x >> 6;
   const int kvh = blockIdx.y, G = Hq / Hkv, nQ = M * G;
   const int nchunks = (T + 31) >> 5, KB32 = Tpad >> 5;
   const int tile0 = SPLIT_KEYS ? blockIdx.x * QT : (blockIdx.x * NW + wave) * QT;

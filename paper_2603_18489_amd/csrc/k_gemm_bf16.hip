@@ -151,7 +151,10 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* 
                                                                    int total_nt, int KB,
                                                                    int MT_src, GemmEpi e) {
   extern __shared__ float4 red[];  // [KS][NTW*MT][64]
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // the wave index is made a scalar so that everything derived from it (the K slice) is
+  // provably wave-uniform: MFMA ignores the EXEC mask, so it must never sit under a condition
+  // the compiler could treat as divergent
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nt0 = blockIdx.x * NTW;
   const int kb_lo = (int)(((long)wave * KB) / KS), kb_hi = (int)(((long)(wave + 1) * KB) / KS);
 
@@ -177,21 +180,37 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* 
 #pragma unroll
     for (int j = 0; j < MT; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
+  // Two register sets of U k-steps each: while one set feeds the MFMAs the other set's loads
+  // are in flight, so a wave always has up to 2*U*(NTW+MT) KiB outstanding.  k-steps past the
+  // slice load zeros (the loads honour EXEC; the MFMAs run unconditionally and add nothing).
+  constexpr int U = 4;
   const int nkb = kb_hi - kb_lo;
-#pragma unroll 4
-  for (int it = 0; it < nkb; ++it) {
-    u32x4 wf[NTW], af[MT];
-#pragma unroll
-    for (int i = 0; i < NTW; ++i) wf[i] = wp[i][(size_t)it * 64];
-#pragma unroll
-    for (int j = 0; j < MT; ++j) af[j] = ap[j][(size_t)it * MT_src * 64];
-#pragma unroll
-    for (int i = 0; i < NTW; ++i)
-#pragma unroll
-      for (int j = 0; j < MT; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v4_as_bf16x8(wf[i]),
-                                                            v4_as_bf16x8(af[j]), acc[i][j], 0, 0, 0);
+  const u32x4 zero4 = {0u, 0u, 0u, 0u};
+  u32x4 wa[U][NTW], aa[U][MT], wb[U][NTW], ab[U][MT];
+#define EC_SK_LOAD(WSET, ASET, IT0)                                                        \
+  _Pragma("unroll") for (int u = 0; u < U; ++u) {                                          \
+    const int it_ = (IT0) + u;                                                             \
+    const bool in_ = it_ < nkb;                                                            \
+    _Pragma("unroll") for (int i = 0; i < NTW; ++i)                                        \
+        WSET[u][i] = in_ ? wp[i][(size_t)it_ * 64] : zero4;                                \
+    _Pragma("unroll") for (int j = 0; j < MT; ++j)                                         \
+        ASET[u][j] = in_ ? ap[j][(size_t)it_ * MT_src * 64] : zero4;                       \
   }
+#define EC_SK_MMA(WSET, ASET)                                                              \
+  _Pragma("unroll") for (int u = 0; u < U; ++u)                                            \
+    _Pragma("unroll") for (int i = 0; i < NTW; ++i)                                        \
+      _Pragma("unroll") for (int j = 0; j < MT; ++j)                                       \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                               \
+            v4_as_bf16x8(WSET[u][i]), v4_as_bf16x8(ASET[u][j]), acc[i][j], 0, 0, 0);
+  EC_SK_LOAD(wa, aa, 0)
+  for (int it0 = 0; it0 < nkb; it0 += 2 * U) {
+    EC_SK_LOAD(wb, ab, it0 + U)
+    EC_SK_MMA(wa, aa)
+    EC_SK_LOAD(wa, aa, it0 + 2 * U)
+    EC_SK_MMA(wb, ab)
+  }
+#undef EC_SK_LOAD
+#undef EC_SK_MMA
 
   // fixed-order reduction over the KS waves
 #pragma unroll
@@ -301,7 +320,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_tiled_kernel(const u32x4* __res
   constexpr int LF = (NF + 3) / 4;                             // fragments loaded per wave
   static_assert(WTN % 2 == 0, "pair epilogues need an even number of weight tiles per wave");
   __shared__ u32x4 lds[2][NF][64];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int mt0 = blockIdx.y * BMT, nt0 = blockIdx.x * BNT;
   const int wm = wave >> 1, wn = wave & 1;
 
