@@ -145,7 +145,7 @@ __device__ __forceinline__ void epi_qkv(const GemmEpi& e, int m, int vpair, int 
 // ---------------------------------------------------------------------------------------------
 // skinny: grid = ceil(n-tiles / NTW) blocks of KS*64 threads
 // ---------------------------------------------------------------------------------------------
-template <int EPI, int MT, int NTW, int KS>
+template <int EPI, int MT, int NTW, int KS, int U>
 __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* __restrict__ Ap,
                                                                    const u32x4* __restrict__ Wp,
                                                                    int total_nt, int KB,
@@ -180,10 +180,9 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* 
 #pragma unroll
     for (int j = 0; j < MT; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  // Two register sets of U k-steps each: while one set feeds the MFMAs the other set's loads
+  // Two register sets of U k-steps each (U is a template parameter): while one set feeds the MFMAs the other set's loads
   // are in flight, so a wave always has up to 2*U*(NTW+MT) KiB outstanding.  k-steps past the
   // slice load zeros (the loads honour EXEC; the MFMAs run unconditionally and add nothing).
-  constexpr int U = 4;
   const int nkb = kb_hi - kb_lo;
   const u32x4 zero4 = {0u, 0u, 0u, 0u};
   u32x4 wa[U][NTW], aa[U][MT], wb[U][NTW], ab[U][MT];
@@ -264,24 +263,32 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* 
   }
 }
 
-template <int EPI, int MT, int NTW, int KS>
+template <int EPI, int MT, int NTW, int KS, int U = 4>
 static void launch_skinny_t(const bf16_t* Ap, int MT_src, const bf16_t* Wp, int total_nt, int KB,
                             const GemmEpi& e, hipStream_t s) {
   int grid = (total_nt + NTW - 1) / NTW;
   size_t smem = (size_t)KS * NTW * MT * 64 * sizeof(float4);
-  gemm_bf16_skinny_kernel<EPI, MT, NTW, KS><<<grid, KS * 64, smem, s>>>(
+  gemm_bf16_skinny_kernel<EPI, MT, NTW, KS, U><<<grid, KS * 64, smem, s>>>(
       (const u32x4*)Ap, (const u32x4*)Wp, total_nt, KB, MT_src, e);
 }
 
+// Tile counts per block were chosen by timing on MI355X: the kernels are bound by what the L2
+// delivers (weights once + the activation fragments once per block), so more weight tiles per
+// block (fewer re-reads of the activations) win as long as the grid still covers the CUs.
 template <int EPI, int MT>
 static void launch_skinny_mt(const bf16_t* Ap, int MT_src, const bf16_t* Wp, int total_nt, int KB,
                              const GemmEpi& e, hipStream_t s) {
-  if constexpr (EPI == EPI_LOGITS)
-    launch_skinny_t<EPI, MT, 4, 4>(Ap, MT_src, Wp, total_nt, KB, e, s);
-  else if constexpr (EPI == EPI_RESID)
-    launch_skinny_t<EPI, MT, 1, 8>(Ap, MT_src, Wp, total_nt, KB, e, s);
-  else
-    launch_skinny_t<EPI, MT, 2, 8>(Ap, MT_src, Wp, total_nt, KB, e, s);
+  if constexpr (EPI == EPI_LOGITS) {
+    launch_skinny_t<EPI, MT, 4, 4, 4>(Ap, MT_src, Wp, total_nt, KB, e, s);
+  } else if constexpr (EPI == EPI_RESID) {
+    launch_skinny_t<EPI, MT, 1, 8, 2>(Ap, MT_src, Wp, total_nt, KB, e, s);
+  } else if constexpr (EPI == EPI_SWIGLU) {
+    if (total_nt >= 6 * 256) launch_skinny_t<EPI, MT, 6, 4, 2>(Ap, MT_src, Wp, total_nt, KB, e, s);
+    else launch_skinny_t<EPI, MT, 2, 8, 2>(Ap, MT_src, Wp, total_nt, KB, e, s);
+  } else {
+    if (total_nt >= 4 * 160) launch_skinny_t<EPI, MT, 4, 8, 2>(Ap, MT_src, Wp, total_nt, KB, e, s);
+    else launch_skinny_t<EPI, MT, 2, 8, 2>(Ap, MT_src, Wp, total_nt, KB, e, s);
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
