@@ -27,7 +27,7 @@
 //     activation fragments come from L2.  The KS partial tiles are summed in LDS in a fixed
 //     order, then the epilogue runs on the sums.
 //   tiled (M > 64): 2x2 waves, block tile chosen per shape (up to 192x192) so that the grid
-//     fills the 256 CUs, K step 32, LDS double buffering with two register sets of global
+//     fills the 256 CUs, K step 32, LDS double buffering with four register sets of global
 //     loads in flight.
 #include "ec_internal.h"
 
@@ -356,27 +356,32 @@ __global__ __launch_bounds__(256) void gemm_bf16_tiled_kernel(const u32x4* __res
 #pragma unroll
     for (int j = 0; j < WTM; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  // prologue: k-step 0 into LDS stage 0, k-steps 1 and 2 in flight in the two register sets
-  u32x4 r0[LF], r1[LF];
+  // prologue: k-step 0 into LDS stage 0, k-steps 1..4 in flight in four register sets (the L2
+  // delivers by Little's law: bytes in flight / latency, so the sets are what buys bandwidth)
+  u32x4 r0[LF], r1[LF], r2[LF], r3[LF];
   EC_TILED_GLOAD(r0, 0)
   EC_TILED_LSTORE(r0, 0)
   EC_TILED_GLOAD(r0, 1)
   EC_TILED_GLOAD(r1, 2)
+  EC_TILED_GLOAD(r2, 3)
+  EC_TILED_GLOAD(r3, 4)
   __syncthreads();
   // iteration kb: compute stage kb&1; the register set holding k-step kb+1 goes to stage
-  // (kb+1)&1 and is reloaded with k-step kb+3
-  for (int kb = 0; kb < KB; kb += 2) {
-    EC_TILED_COMPUTE(0)
-    EC_TILED_LSTORE(r0, 1)
-    EC_TILED_GLOAD(r0, kb + 3)
-    __syncthreads();
-    if (kb + 1 < KB) {
-      EC_TILED_COMPUTE(1)
-      EC_TILED_LSTORE(r1, 0)
-      EC_TILED_GLOAD(r1, kb + 4)
-    }
-    __syncthreads();
+  // (kb+1)&1 and is reloaded with k-step kb+5
+#define EC_TILED_STEP(REGS, KBV, STAGE)       \
+  if ((KBV) < KB) {                           \
+    EC_TILED_COMPUTE(STAGE)                   \
+    EC_TILED_LSTORE(REGS, (STAGE) ^ 1)        \
+    EC_TILED_GLOAD(REGS, (KBV) + 5)           \
+  }                                           \
+  __syncthreads();
+  for (int kb = 0; kb < KB; kb += 4) {
+    EC_TILED_STEP(r0, kb, 0)
+    EC_TILED_STEP(r1, kb + 1, 1)
+    EC_TILED_STEP(r2, kb + 2, 0)
+    EC_TILED_STEP(r3, kb + 3, 1)
   }
+#undef EC_TILED_STEP
 
   const int q4 = lane >> 4;
 #pragma unroll
