@@ -136,6 +136,9 @@ def main():
     ap.add_argument("--logit-scale", type=float, default=0.0, help="skip calibration")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--threads", type=int, default=16)
+    ap.add_argument("--calib-copy-mb", type=int, default=0,
+                    help="run one plain device copy of this size first (a known-size dispatch "
+                         "that scales rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -159,6 +162,13 @@ def main():
     dw = ec.weights_to_device(cfg, w)
     torch.cuda.synchronize()
     log(f"[bench] weights uploaded in {time.perf_counter() - t0:.1f}s")
+
+    if args.calib_copy_mb > 0:
+        src = torch.ones(args.calib_copy_mb << 18, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     def make_ctx(scale):
         return ec.EntropyCache(cfg.replace(logit_scale=scale), dw, dec, prompt)
@@ -217,6 +227,13 @@ def main():
                      "achieved": ach_f, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": ach_f / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
                      "launch_ms": gu_full_ms, "flops_per_launch": gu_flops}
+    # HBM bytes per launch measured with rocprofv3 --pmc (committed summary of the same command)
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_llada8b.json")
+    if args.workload == "llada8b" and os.path.exists(tpath):
+        tj = json.load(open(tpath))
+        for rf, key in ((roofline, "partial_gateup"), (roofline_full, "full_gateup")):
+            rf["traffic"] = tj[key]["fetch_bytes"] + (tj[key]["write_bytes"] or 0.0)
+            rf["traffic_source"] = "profiles/gemm_kernels_llada8b_hbm_traffic.txt"
     step_bytes = algorithmic_bytes(cfg, T, rows_partial, dec.block)
     step_flops = full_step_flops(cfg, T, dec.block)
     decision_ms = pp["vocab_reduce"] + pp["decide"]
