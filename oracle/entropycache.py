@@ -58,6 +58,28 @@ def to_f64(w: np.ndarray) -> np.ndarray:
     return w.astype(np.float64)
 
 
+# Optional memo of up-cast matrices, keyed by the stored array's identity.  Tests that run many
+# steps on a model whose float64 copy fits in memory switch it on to skip the repeated
+# conversion; it changes no arithmetic.  Off by default (the 8B-shaped models would not fit).
+_F64_CACHE: Optional[dict] = None
+
+
+def enable_f64_cache(on: bool) -> None:
+    global _F64_CACHE
+    _F64_CACHE = {} if on else None
+
+
+def _w64(w: np.ndarray) -> np.ndarray:
+    if _F64_CACHE is None or w.ndim < 2:
+        return to_f64(w)
+    key = id(w)
+    hit = _F64_CACHE.get(key)
+    if hit is None or hit[0] is not w:
+        hit = (w, to_f64(w))
+        _F64_CACHE[key] = hit
+    return hit[1]
+
+
 # ----------------------------------------------------------------------------------------------
 # building blocks of the transformer layer ("W(.)" and "TransformerBlock" of the appendix)
 # ----------------------------------------------------------------------------------------------
@@ -209,18 +231,18 @@ def forward_rows(st: OracleState, S: np.ndarray, want_rows: np.ndarray) -> np.nd
     h = to_f64(w["tok_emb"][st.x[S]])                                    # H^{t,0} = Emb[x^t]
     for l in range(cfg.n_layers):
         u = rmsnorm(h, to_f64(w["attn_norm"][l]), cfg.rms_eps)
-        q = (u @ to_f64(w["wq"][l]).T).reshape(-1, hq, hd)
-        k = (u @ to_f64(w["wk"][l]).T).reshape(-1, hkv, hd)
-        v = (u @ to_f64(w["wv"][l]).T).reshape(-1, hkv, hd)
+        q = (u @ _w64(w["wq"][l]).T).reshape(-1, hq, hd)
+        k = (u @ _w64(w["wk"][l]).T).reshape(-1, hkv, hd)
+        v = (u @ _w64(w["wv"][l]).T).reshape(-1, hkv, hd)
         q = rope(q, S, cfg.rope_base)
         k = rope(k, S, cfg.rope_base)
         st.Kc[l, S] = k                                                  # scatter, then attend
         st.Vc[l, S] = v
         o = attend(q, st.Kc[l], st.Vc[l]).reshape(-1, hq * hd)
-        h = h + o @ to_f64(w["wo"][l]).T
+        h = h + o @ _w64(w["wo"][l]).T
         u = rmsnorm(h, to_f64(w["mlp_norm"][l]), cfg.rms_eps)
-        act = silu(u @ to_f64(w["w_gate"][l]).T) * (u @ to_f64(w["w_up"][l]).T)
-        h = h + act @ to_f64(w["w_down"][l]).T
+        act = silu(u @ _w64(w["w_gate"][l]).T) * (u @ _w64(w["w_up"][l]).T)
+        h = h + act @ _w64(w["w_down"][l]).T
     sel = np.searchsorted(S, np.asarray(want_rows, dtype=np.int64))
     return rmsnorm(h[sel], to_f64(w["final_norm"]), cfg.rms_eps)
 
@@ -268,7 +290,7 @@ def eco_step(st: OracleState, mode: int = AUTO, forced: Optional[dict] = None,
     res = {"t": t, "mode": mode, "S": S, "Mb": Mb}
     if S.size == 0:                                  # test hook only: nothing decoded
         return res
-    z = cfg.logit_scale * (hfin @ to_f64(st.model.w["lm_head"]).T)       # [|Mb|, V]
+    z = cfg.logit_scale * (hfin @ _w64(st.model.w["lm_head"]).T)       # [|Mb|, V]
     stats = [softmax_stats(z[i]) for i in range(len(Mb))]
     tok = np.array([s[0] for s in stats], dtype=np.int64)
     conf = np.array([s[1] for s in stats])

@@ -48,6 +48,7 @@ struct Buffers {
   float* logits; float4* partials;
   // bf16 only: row sums of squares [2L+1][sumsq_stride] (32.32 fixed point), packed matrices
   unsigned long long* sumsq; int sumsq_stride;
+  float* ksplit_part;  // [kMaxKSplit][T][d] partial products of K-split residual GEMMs
   std::vector<PackedLayer> pl; bf16_t* lm_head_p;
 };
 
@@ -80,9 +81,11 @@ void carve(Carver& c, const ec_model_cfg& m, const ec_decode_cfg& d, int P, Buff
   b.pl.clear();
   b.lm_head_p = nullptr;
   b.sumsq = nullptr;
+  b.ksplit_part = nullptr;
   b.sumsq_stride = (int)T16;
   if (m.dtype == EC_BF16) {
     b.sumsq = c.take<unsigned long long>((size_t)(2 * m.n_layers + 1) * T16);
+    b.ksplit_part = c.take<float>((size_t)kMaxKSplit * T * m.d_model);
     b.pl.resize(m.n_layers);
     for (int l = 0; l < m.n_layers; ++l) {
       PackedLayer& p = b.pl[l];
@@ -298,7 +301,7 @@ int forward_bf16(ec_ctx* c, int mode, int M, int n_mb) {
       launch_attention_mfma(q, kc, vc, M, c->T, Tpad, m.n_heads, m.n_kv_heads, hd, attn, s); }
     { Scope p(c, EC_K_OPROJ);
       GemmEpi e{}; e.M = M; e.MT = MT; e.h = b.h; e.d = d; e.gain_next = G(c->mlp_norm[l]);
-      e.a_next = u; e.sumsq_out = sums(2 * l + 1);
+      e.a_next = u; e.sumsq_out = sums(2 * l + 1); e.partial = b.ksplit_part; e.max_ksplit = kMaxKSplit;
       launch_gemm_bf16(EPI_RESID, attn, M, b.pl[l].wo, d, nq, e, s); }
     { Scope p(c, EC_K_GATEUP);
       GemmEpi e{}; e.M = M; e.MT = MT; e.sumsq_in = sums(2 * l + 1); e.d_in = d; e.eps = m.rms_eps;
@@ -307,7 +310,7 @@ int forward_bf16(ec_ctx* c, int mode, int M, int n_mb) {
     { Scope p(c, EC_K_DOWN);
       GemmEpi e{}; e.M = M; e.MT = MT; e.h = b.h; e.d = d;
       e.gain_next = G(l + 1 < L ? c->attn_norm[l + 1] : c->w.final_norm);
-      e.a_next = u; e.sumsq_out = sums(2 * l + 2);
+      e.a_next = u; e.sumsq_out = sums(2 * l + 2); e.partial = b.ksplit_part; e.max_ksplit = kMaxKSplit;
       launch_gemm_bf16(EPI_RESID, act, M, b.pl[l].wd, d, F, e, s); }
   }
   // logits only for the block's masked rows: the LM head gathers them from `u`

@@ -76,7 +76,8 @@ void launch_attention_f32(const float* q, const float* kc, const float* vc, int 
                           int Hkv, int hd, float* out, hipStream_t s);
 
 // bf16 path
-enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3 };
+enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3, EPI_PARTIAL = 4 };
+constexpr int kMaxKSplit = 4;
 enum { REPACK_PLAIN = 0, REPACK_ROPE_PAIRS = 1, REPACK_EVEN = 2, REPACK_ODD = 3 };
 
 // What a GEMM epilogue needs (k_gemm_bf16.hip).  Row sums of squares are 32.32 fixed point.
@@ -90,6 +91,7 @@ struct GemmEpi {
   float scale;                    // EPI_LOGITS
   float* logits; int ldc;
   float* h; int d;                // EPI_RESID: residual stream [M, d]
+  float* partial; int max_ksplit; // nullable: room for [max_ksplit][M][d] fp32 partial products
   const bf16_t* gain_next;        // gain of the norm that follows
   bf16_t* a_next;                 // packed bf16(h * gain_next)
   unsigned long long* sumsq_out;  // per row, accumulated with integer atomics

@@ -238,8 +238,9 @@ static void launch_attn_mfma_hd(const bf16_t* q, const uint4* kp, const uint4* v
                                 int Tpad, int Hq, int Hkv, bf16_t* out, hipStream_t s) {
   const int G = Hq / Hkv, nQ = M * G, qtiles = (nQ + 15) / 16, MT = (M + 15) / 16;
   const float sc = 1.4426950408889634f / sqrtf((float)HD);
-  if (qtiles <= 64) {
-    // few queries: split the keys over the waves of a block, at most 2 query tiles per block
+  if (((qtiles + 1) / 2) * Hkv <= 128) {
+    // few (query tile, kv head) pairs: split the keys over the waves of a block, at most 2 query
+    // tiles per block; otherwise every wave walks all keys for its own query tiles
     if (qtiles <= 1) launch_split<HD, 1>(q, kp, vp, M, T, Tpad, Hq, Hkv, sc, out, MT, qtiles, s);
     else launch_split<HD, 2>(q, kp, vp, M, T, Tpad, Hq, Hkv, sc, out, MT, qtiles, s);
   } else {

@@ -231,6 +231,7 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* 
     return (f32x4){s.x, s.y, s.z, s.w};
   };
 
+  static_assert(EPI != EPI_PARTIAL, "K-split partial products are a tiled-kernel epilogue");
   constexpr bool PAIR = (EPI == EPI_QKV || EPI == EPI_SWIGLU);
   static_assert(!PAIR || NTW % 2 == 0, "pair epilogues need an even number of tiles per block");
   constexpr int UNITS = (PAIR ? NTW / 2 : NTW) * MT * 64;  // whole waves: UNITS % 64 == 0
@@ -321,7 +322,7 @@ static void launch_skinny_mt(const bf16_t* Ap, int MT_src, const bf16_t* Wp, int
 template <int EPI, int WTM, int WTN>
 __global__ __launch_bounds__(256) void gemm_bf16_tiled_kernel(const u32x4* __restrict__ Ap,
                                                               const u32x4* __restrict__ Wp,
-                                                              int total_nt, int KB, int MT,
+                                                              int total_nt, int KB_all, int MT,
                                                               GemmEpi e) {
   constexpr int BMT = 2 * WTM, BNT = 2 * WTN, NF = BMT + BNT;  // fragments per k-step
   constexpr int LF = (NF + 3) / 4;                             // fragments loaded per wave
@@ -330,6 +331,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_tiled_kernel(const u32x4* __res
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int mt0 = blockIdx.y * BMT, nt0 = blockIdx.x * BNT;
   const int wm = wave >> 1, wn = wave & 1;
+  // blockIdx.z picks one of gridDim.z contiguous K ranges (EPI_PARTIAL; otherwise gridDim.z = 1)
+  const int kb_first = (int)(((long)blockIdx.z * KB_all) / gridDim.z);
+  const int KB = (int)(((long)(blockIdx.z + 1) * KB_all) / gridDim.z) - kb_first;
 
   // Fragment f of the block (0..BMT-1 activations, BMT.. weights) is loaded by wave f % 4.
   // A fragment outside the matrix streams fragment 0 instead (valid memory); what it produces
@@ -346,8 +350,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_tiled_kernel(const u32x4* __res
       if (mt < MT) src[i] = Ap + (size_t)mt * 64 + lane;
     } else if (f < NF) {
       int nt = nt0 + (f - BMT);
-      if (nt < total_nt) { src[i] = Wp + (size_t)nt * KB * 64 + lane; stride[i] = 64; }
+      if (nt < total_nt) { src[i] = Wp + (size_t)nt * KB_all * 64 + lane; stride[i] = 64; }
     }
+    src[i] += (size_t)kb_first * stride[i];
   }
 
   f32x4 acc[WTN][WTM];
@@ -405,6 +410,18 @@ __global__ __launch_bounds__(256) void gemm_bf16_tiled_kernel(const u32x4* __res
           if (vt < total_nt) epi_logits(e, m, vt, q4, acc[i][j], rs);
         }
       }
+    } else if constexpr (EPI == EPI_PARTIAL) {
+      if (mvalid) {
+#pragma unroll
+        for (int i = 0; i < WTN; ++i) {
+          int vt = nt0 + wn * WTN + i;
+          if (vt < total_nt) {
+            f32x4 v = acc[i][j];
+            *(float4*)(e.partial + ((size_t)blockIdx.z * e.M + m) * e.d + vt * 16 + q4 * 4) =
+                make_float4(v[0], v[1], v[2], v[3]);
+          }
+        }
+      }
     } else {
       if (mvalid) {
         float rs = rstd_of(e, m);
@@ -426,27 +443,67 @@ __global__ __launch_bounds__(256) void gemm_bf16_tiled_kernel(const u32x4* __res
 
 template <int EPI, int WTM, int WTN>
 static void launch_tiled_t(const bf16_t* Ap, int MT, const bf16_t* Wp, int total_nt, int KB,
-                           const GemmEpi& e, hipStream_t s) {
-  dim3 grid((total_nt + 2 * WTN - 1) / (2 * WTN), (MT + 2 * WTM - 1) / (2 * WTM));
+                           const GemmEpi& e, hipStream_t s, int ksplit = 1) {
+  dim3 grid((total_nt + 2 * WTN - 1) / (2 * WTN), (MT + 2 * WTM - 1) / (2 * WTM), ksplit);
   gemm_bf16_tiled_kernel<EPI, WTM, WTN><<<grid, 256, 0, s>>>((const u32x4*)Ap, (const u32x4*)Wp,
                                                              total_nt, KB, MT, e);
 }
 
-// Picks the block tile whose grid wastes the least of the 256 CUs: the score is the useful
-// fraction of the rounds the grid needs, weighted by how well the tile shape feeds the MFMAs.
-static int pick_tile(int MT, int total_nt) {
+// Second half of a K-split residual GEMM: h += sum over the splits (fixed order), then what
+// EPI_RESID does: next operand bf16(h * gain) and the row's sum of squares.
+// grid (ceil(d / 1024), M), 256 threads, 4 columns per thread.
+__global__ __launch_bounds__(256) void resid_finish_kernel(GemmEpi e, int ksplit) {
+  __shared__ float red[4];
+  const int m = blockIdx.y, n = (blockIdx.x * 256 + threadIdx.x) * 4;
+  float part = 0.f;
+  if (n < e.d) {
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int z = 0; z < ksplit; ++z) {
+      float4 p = *(const float4*)(e.partial + ((size_t)z * e.M + m) * e.d + n);
+      v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+    }
+    part = epi_resid(e, m, n >> 4, (n >> 2) & 3, (f32x4){v.x, v.y, v.z, v.w});
+  }
+  part = block_sum<4>(part, red);
+  if (threadIdx.x == 0) {
+    unsigned long long fx = (unsigned long long)((double)part * 4294967296.0 + 0.5);
+    atomicAdd((unsigned long long*)(e.sumsq_out + m), fx);
+  }
+}
+
+// Block tile and K split for the tiled kernel, from a cost model calibrated on MI355X timings
+// (a 6x6 wave tile spends about 0.68 us per k-step; smaller tiles feed the MFMAs less well
+// because they re-read more operand bytes per flop from L2).  A grid that does not fill the
+// 256 CUs in whole rounds wastes the remainder, so narrow outputs (N = d_model) are split
+// along K into partial products that a small second kernel sums.
+struct TilePick { int tile, ksplit; };
+static TilePick pick_tile(int MT, int total_nt, int KB, int max_ksplit, int M, int N) {
   static const int wtm[4] = {6, 6, 4, 3}, wtn[4] = {6, 4, 4, 4};
-  static const float shape_eff[4] = {1.00f, 0.90f, 0.80f, 0.62f};
-  int best = 0;
-  float best_score = -1.f;
+  static const float rel_eff[4] = {1.00f, 0.92f, 0.80f, 0.45f};
+  TilePick best{0, 1};
+  float best_t = 1e30f;
   for (int i = 0; i < 4; ++i) {
     long gm = (MT + 2 * wtm[i] - 1) / (2 * wtm[i]), gn = (total_nt + 2 * wtn[i] - 1) / (2 * wtn[i]);
-    long blocks = gm * gn, rounds = (blocks + 255) / 256;
-    float useful = (float)((double)MT * total_nt / ((double)rounds * 256 * 4 * wtm[i] * wtn[i]));
-    float score = useful * shape_eff[i];
-    if (score > best_score) { best_score = score; best = i; }
+    for (int ks = 1; ks <= max_ksplit; ++ks) {
+      long blocks = gm * gn * ks, rounds = (blocks + 255) / 256;
+      float ksteps = (float)((KB + ks - 1) / ks);
+      float t = rounds * (wtm[i] * wtn[i] * ksteps * 0.0189f / rel_eff[i] + 3.0f);
+      if (ks > 1) t += 2.5f + (float)M * N * (ks + 4) * 4.0f / 3.0e6f;  // finish: ~3 TB/s
+      if (t < best_t) { best_t = t; best = TilePick{i, ks}; }
+    }
   }
   return best;
+}
+
+template <int EPI>
+static void launch_tiled_pick(const bf16_t* Ap, int MT, const bf16_t* Wp, int total_nt, int KB,
+                              const GemmEpi& e, hipStream_t s, int tile, int ksplit) {
+  switch (tile) {
+    case 0: launch_tiled_t<EPI, 6, 6>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
+    case 1: launch_tiled_t<EPI, 6, 4>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
+    case 2: launch_tiled_t<EPI, 4, 4>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
+    default: launch_tiled_t<EPI, 3, 4>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
+  }
 }
 
 template <int EPI>
@@ -462,11 +519,13 @@ static void launch_epi(const bf16_t* Ap, int M_src, const bf16_t* Wp, int N, int
     }
   } else {
     // the tiled kernel reads its activation rows in place (no gather): M_src == M
-    switch (pick_tile(MT, total_nt)) {
-      case 0: launch_tiled_t<EPI, 6, 6>(Ap, MT, Wp, total_nt, KB, e, s); break;
-      case 1: launch_tiled_t<EPI, 6, 4>(Ap, MT, Wp, total_nt, KB, e, s); break;
-      case 2: launch_tiled_t<EPI, 4, 4>(Ap, MT, Wp, total_nt, KB, e, s); break;
-      default: launch_tiled_t<EPI, 3, 4>(Ap, MT, Wp, total_nt, KB, e, s); break;
+    const int max_ks = (EPI == EPI_RESID && e.partial) ? e.max_ksplit : 1;
+    TilePick tp = pick_tile(MT, total_nt, KB, max_ks, e.M, N);
+    if (tp.ksplit > 1) {
+      launch_tiled_pick<EPI_PARTIAL>(Ap, MT, Wp, total_nt, KB, e, s, tp.tile, tp.ksplit);
+      resid_finish_kernel<<<dim3((N + 1023) / 1024, e.M), 256, 0, s>>>(e, tp.ksplit);
+    } else {
+      launch_tiled_pick<EPI>(Ap, MT, Wp, total_nt, KB, e, s, tp.tile, 1);
     }
   }
 }

@@ -27,9 +27,10 @@ def gpu_cache(g, which, layer):
 
 
 def run_teacher_forced(cfg, w, dec, prompt, tol, max_steps=None, check_cache_every=1,
-                       dev_weights=None, verbose=False):
-    """Runs the oracle free (AUTO) and the GPU teacher-forced by it.  Returns a summary dict;
-    raises AssertionError on any parity violation."""
+                       dev_weights=None, verbose=False, mode_fn=None, cache_layers=None):
+    """Runs the oracle free (AUTO, or with the modes mode_fn(step_index) forces on both sides)
+    and the GPU teacher-forced by it.  Returns a summary dict; raises AssertionError on any
+    parity violation."""
     st = eco.eco_init(eco.OracleModel(cfg, w), dec, prompt)
     dw = dev_weights if dev_weights is not None else ec.weights_to_device(cfg, w)
     g = ec.EntropyCache(cfg, dw, dec, prompt)
@@ -45,7 +46,7 @@ def run_teacher_forced(cfg, w, dec, prompt, tol, max_steps=None, check_cache_eve
             if steps > 0:
                 rows = g.debug_read(ec.EC_DBG_ROWS, count=len(exp_rows))
                 assert rows.tolist() == exp_rows, f"step {st.t}: row set differs"
-            r = eco.eco_step(st, eco.AUTO)
+            r = eco.eco_step(st, eco.AUTO if mode_fn is None else mode_fn(steps))
             q = g.step_forced(r["mode"], r["positions"], r["tokens"])
             steps += 1
             modes[r["mode"]] += 1
@@ -90,13 +91,14 @@ def run_teacher_forced(cfg, w, dec, prompt, tol, max_steps=None, check_cache_eve
                 if abs(r["E_own"] - dec.tau) > 2 * stat_tol * lnV:
                     assert q["next_mode"] == (eco.PARTIAL if r["E_own"] <= dec.tau else eco.FULL)
             if check_cache_every and (steps % check_cache_every == 0 or st.done):
-                for l in range(cfg.n_layers):
+                for l in (range(cfg.n_layers) if cache_layers is None else cache_layers):
                     for name, which, oc in (("K", ec.EC_DBG_KCACHE, st.Kc), ("V", ec.EC_DBG_VCACHE, st.Vc)):
                         e = relerr(gpu_cache(g, which, l), oc[l])
                         worst[name] = max(worst[name], e)
                         assert e <= tol, f"step {r['t']} layer {l}: {name} cache rel err {e:.3e}"
             if verbose:
-                print(f"t={r['t']} mode={r['mode']} |S|={len(r['S'])} logits={worst['logits']:.2e}", flush=True)
+                print(f"t={r['t']} mode={r['mode']} |S|={len(r['S'])} E={r['E']:.3f} "
+                      f"logits={worst['logits']:.2e}", flush=True)
         # integer state is bit-exact
         assert np.array_equal(g.debug_read(ec.EC_DBG_X), st.x.astype(np.int32))
         assert np.array_equal(g.debug_read(ec.EC_DBG_MASKED).astype(bool), st.masked)
