@@ -26,9 +26,9 @@
 //     across its waves; each weight byte is read from HBM exactly once while the small
 //     activation fragments come from L2.  The KS partial tiles are summed in LDS in a fixed
 //     order, then the epilogue runs on the sums.
-//   tiled (M > 64): 2x2 waves, block tile chosen per shape (up to 192x192) so that the grid
-//     fills the 256 CUs, K step 32, LDS double buffering with four register sets of global
-//     loads in flight.
+//   tiled (M > 64): block tile chosen per shape so that the grid fills the 256 CUs.  Up to
+//     192x192: 4 waves, LDS double buffer fed through four register sets.  192x256 / 192x384:
+//     8 waves, operands loaded from global memory directly into a 3-stage LDS ring.
 #include "ec_internal.h"
 
 namespace ec {
@@ -293,8 +293,67 @@ static void launch_skinny_mt(const bf16_t* Ap, int MT_src, const bf16_t* Wp, int
 }
 
 // ---------------------------------------------------------------------------------------------
-// tiled: 2x2 waves, wave tile = WTM x WTN fragments of 16 rows (activations x weights), K step 32.
-// grid = (ceil(n-tiles / (2*WTN)), ceil(m-tiles / (2*WTM)))
+// Epilogue of the tiled kernels: one wave's WTN x WTM accumulator tiles (weights x activations).
+// ---------------------------------------------------------------------------------------------
+template <int EPI, int WTM, int WTN>
+__device__ __forceinline__ void tiled_epilogue(const GemmEpi& e, f32x4 (&acc)[WTN][WTM],
+                                               int mt_base, int nt_base, int total_nt, int lane,
+                                               int kz) {
+  const int q4 = lane >> 4;
+#pragma unroll
+  for (int j = 0; j < WTM; ++j) {
+    const int m = (mt_base + j) * 16 + (lane & 15);
+    const bool mvalid = m < e.M;
+    if constexpr (EPI == EPI_RESID) {
+      float part = 0.f;
+#pragma unroll
+      for (int i = 0; i < WTN; ++i) {
+        int vt = nt_base + i;
+        if (mvalid && vt < total_nt) part += epi_resid(e, m, vt, q4, acc[i][j]);
+      }
+      epi_add_sumsq(e, m, mvalid, part);
+    } else if constexpr (EPI == EPI_LOGITS) {
+      if (mvalid) {
+        float rs = rstd_of(e, e.row_sel ? e.row_sel[m] : m);
+#pragma unroll
+        for (int i = 0; i < WTN; ++i) {
+          int vt = nt_base + i;
+          if (vt < total_nt) epi_logits(e, m, vt, q4, acc[i][j], rs);
+        }
+      }
+    } else if constexpr (EPI == EPI_PARTIAL) {
+      if (mvalid) {
+#pragma unroll
+        for (int i = 0; i < WTN; ++i) {
+          int vt = nt_base + i;
+          if (vt < total_nt) {
+            f32x4 v = acc[i][j];
+            *(float4*)(e.partial + ((size_t)kz * e.M + m) * e.d + vt * 16 + q4 * 4) =
+                make_float4(v[0], v[1], v[2], v[3]);
+          }
+        }
+      }
+    } else {
+      if (mvalid) {
+        float rs = rstd_of(e, m);
+#pragma unroll
+        for (int i = 0; i < WTN; i += 2) {
+          int vt = nt_base + i;
+          if (vt < total_nt) {
+            if constexpr (EPI == EPI_SWIGLU) epi_swiglu(e, m, vt >> 1, q4, acc[i][j], acc[i + 1][j], rs);
+            else epi_qkv(e, m, vt >> 1, q4, acc[i][j], acc[i + 1][j], rs);
+          }
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// tiled, 4 waves (2x2): wave tile = WTM x WTN fragments, K step 32.  Operands are double-buffered
+// in LDS; global loads run through four register sets, four k-steps ahead.  This variant is the
+// faster one for block tiles up to 192 x 192 (one wave per SIMD, nothing to overlap with).
+// grid = (ceil(n-tiles / (2*WTN)), ceil(m-tiles / (2*WTM)), k splits)
 // ---------------------------------------------------------------------------------------------
 #define EC_TILED_GLOAD(REGS, KBV)                                                   \
   {                                                                                 \
@@ -320,7 +379,7 @@ static void launch_skinny_mt(const bf16_t* Ap, int MT_src, const bf16_t* Wp, int
   }
 
 template <int EPI, int WTM, int WTN>
-__global__ __launch_bounds__(256) void gemm_bf16_tiled_kernel(const u32x4* __restrict__ Ap,
+__global__ __launch_bounds__(256) void gemm_bf16_tiled4_kernel(const u32x4* __restrict__ Ap,
                                                               const u32x4* __restrict__ Wp,
                                                               int total_nt, int KB_all, int MT,
                                                               GemmEpi e) {
@@ -388,65 +447,125 @@ __global__ __launch_bounds__(256) void gemm_bf16_tiled_kernel(const u32x4* __res
   }
 #undef EC_TILED_STEP
 
-  const int q4 = lane >> 4;
-#pragma unroll
-  for (int j = 0; j < WTM; ++j) {
-    const int m = (mt0 + wm * WTM + j) * 16 + (lane & 15);
-    const bool mvalid = m < e.M;
-    if constexpr (EPI == EPI_RESID) {
-      float part = 0.f;
-#pragma unroll
-      for (int i = 0; i < WTN; ++i) {
-        int vt = nt0 + wn * WTN + i;
-        if (mvalid && vt < total_nt) part += epi_resid(e, m, vt, q4, acc[i][j]);
-      }
-      epi_add_sumsq(e, m, mvalid, part);
-    } else if constexpr (EPI == EPI_LOGITS) {
-      if (mvalid) {
-        float rs = rstd_of(e, e.row_sel ? e.row_sel[m] : m);
-#pragma unroll
-        for (int i = 0; i < WTN; ++i) {
-          int vt = nt0 + wn * WTN + i;
-          if (vt < total_nt) epi_logits(e, m, vt, q4, acc[i][j], rs);
-        }
-      }
-    } else if constexpr (EPI == EPI_PARTIAL) {
-      if (mvalid) {
-#pragma unroll
-        for (int i = 0; i < WTN; ++i) {
-          int vt = nt0 + wn * WTN + i;
-          if (vt < total_nt) {
-            f32x4 v = acc[i][j];
-            *(float4*)(e.partial + ((size_t)blockIdx.z * e.M + m) * e.d + vt * 16 + q4 * 4) =
-                make_float4(v[0], v[1], v[2], v[3]);
-          }
-        }
-      }
-    } else {
-      if (mvalid) {
-        float rs = rstd_of(e, m);
-#pragma unroll
-        for (int i = 0; i < WTN; i += 2) {
-          int vt = nt0 + wn * WTN + i;
-          if (vt < total_nt) {
-            if constexpr (EPI == EPI_SWIGLU) epi_swiglu(e, m, vt >> 1, q4, acc[i][j], acc[i + 1][j], rs);
-            else epi_qkv(e, m, vt >> 1, q4, acc[i][j], acc[i + 1][j], rs);
-          }
-        }
-      }
-    }
-  }
+  tiled_epilogue<EPI, WTM, WTN>(e, acc, mt0 + wm * WTM, nt0 + wn * WTN, total_nt, lane, blockIdx.z);
 }
 #undef EC_TILED_GLOAD
 #undef EC_TILED_LSTORE
 #undef EC_TILED_COMPUTE
 
 template <int EPI, int WTM, int WTN>
-static void launch_tiled_t(const bf16_t* Ap, int MT, const bf16_t* Wp, int total_nt, int KB,
-                           const GemmEpi& e, hipStream_t s, int ksplit = 1) {
+static void launch_tiled4_t(const bf16_t* Ap, int MT, const bf16_t* Wp, int total_nt, int KB,
+                           const GemmEpi& e, hipStream_t s, int ksplit) {
   dim3 grid((total_nt + 2 * WTN - 1) / (2 * WTN), (MT + 2 * WTM - 1) / (2 * WTM), ksplit);
-  gemm_bf16_tiled_kernel<EPI, WTM, WTN><<<grid, 256, 0, s>>>((const u32x4*)Ap, (const u32x4*)Wp,
+  gemm_bf16_tiled4_kernel<EPI, WTM, WTN><<<grid, 256, 0, s>>>((const u32x4*)Ap, (const u32x4*)Wp,
                                                              total_nt, KB, MT, e);
+}
+
+// ---------------------------------------------------------------------------------------------
+// tiled, 8 waves (WM x WN): wave tile = WTM x WTN fragments of 16 rows (activations x weights),
+// K step 32.  Operand fragments go from global memory straight into LDS (global_load_lds_dwordx4:
+// lane l's 16 bytes land at base + 16 l, so a 1 KiB fragment keeps its order), NSTAGE stages deep,
+// no staging registers; one barrier per k-step.
+// grid = (ceil(n-tiles / (WN*WTN)), ceil(m-tiles / (WM*WTM)), k splits)
+// ---------------------------------------------------------------------------------------------
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int EPI, int WM, int WN, int WTM, int WTN, int NSTAGE>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_tiled8_kernel(
+    const u32x4* __restrict__ Ap, const u32x4* __restrict__ Wp, int total_nt, int KB_all, int MT,
+    GemmEpi e) {
+  constexpr int NW = WM * WN, BMT = WM * WTM, BNT = WN * WTN, NF = BMT + BNT;
+  constexpr int LF = (NF + NW - 1) / NW;  // loads per wave and stage (all waves issue LF)
+  static_assert(WTN % 2 == 0, "pair epilogues need an even number of weight tiles per wave");
+  static_assert(LF * (NSTAGE - 1) <= 63, "vmcnt counts at most 63 outstanding loads");
+  extern __shared__ u32x4 lds[];  // [NSTAGE][NF][64] + one dump fragment
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int mt0 = blockIdx.y * BMT, nt0 = blockIdx.x * BNT;
+  const int wm = wave / WN, wn = wave % WN;
+  // blockIdx.z picks one of gridDim.z contiguous K ranges (EPI_PARTIAL; otherwise gridDim.z = 1)
+  const int kb_first = (int)(((long)blockIdx.z * KB_all) / gridDim.z);
+  const int KB = (int)(((long)(blockIdx.z + 1) * KB_all) / gridDim.z) - kb_first;
+
+  // Fragment f of the block (0..BMT-1 activations, BMT.. weights) is loaded by wave f % NW.
+  // A fragment outside the matrix streams fragment 0 instead (valid memory); what it produces
+  // lands in rows / columns that are never stored.  Slots past NF go to the dump fragment, so
+  // that every wave has the same number of loads in flight (the vmcnt arithmetic needs that).
+  const u32x4* src[LF];
+  size_t stride[LF];  // u32x4 per k-step
+  int dst[LF];        // fragment slot within a stage, or -1 = dump
+#pragma unroll
+  for (int i = 0; i < LF; ++i) {
+    int f = wave + NW * i;
+    src[i] = Ap + lane;
+    stride[i] = (size_t)MT * 64;
+    dst[i] = f < NF ? f : -1;
+    if (f < BMT) {
+      int mt = mt0 + f;
+      if (mt < MT) src[i] = Ap + (size_t)mt * 64 + lane;
+    } else if (f < NF) {
+      int nt = nt0 + (f - BMT);
+      if (nt < total_nt) { src[i] = Wp + (size_t)nt * KB_all * 64 + lane; stride[i] = 64; }
+    }
+    src[i] += (size_t)kb_first * stride[i];
+  }
+  auto issue = [&](int kb) {  // k-step kb (clamped) -> stage kb % NSTAGE
+    const int kbc = min(kb, KB - 1), stage = kb % NSTAGE;
+#pragma unroll
+    for (int i = 0; i < LF; ++i) {
+      u32x4* slot = dst[i] >= 0 ? lds + ((size_t)stage * NF + dst[i]) * 64
+                                : lds + (size_t)NSTAGE * NF * 64;
+      __builtin_amdgcn_global_load_lds(
+          (const void __attribute__((address_space(1)))*)(src[i] + (size_t)kbc * stride[i]),
+          (void __attribute__((address_space(3)))*)slot, 16, 0, 0);
+    }
+  };
+
+  f32x4 acc[WTN][WTM];
+#pragma unroll
+  for (int i = 0; i < WTN; ++i)
+#pragma unroll
+    for (int j = 0; j < WTM; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+#pragma unroll
+  for (int sgl = 0; sgl < NSTAGE - 1; ++sgl) issue(sgl);
+  for (int kb = 0; kb < KB; ++kb) {
+    // this wave's loads of k-step kb have landed once at most LF*(NSTAGE-2) newer ones remain
+    wait_vmcnt<LF*(NSTAGE - 2)>();
+    __syncthreads();  // ... and so have everyone else's; the stage read last iteration is free
+    issue(kb + NSTAGE - 1);
+    const u32x4* st = lds + (size_t)(kb % NSTAGE) * NF * 64;
+    bf16x8 af[WTM], wf[WTN];
+#pragma unroll
+    for (int j = 0; j < WTM; ++j) af[j] = v4_as_bf16x8(st[(wm * WTM + j) * 64 + lane]);
+#pragma unroll
+    for (int i = 0; i < WTN; ++i) wf[i] = v4_as_bf16x8(st[(BMT + wn * WTN + i) * 64 + lane]);
+#pragma unroll
+    for (int i = 0; i < WTN; ++i)
+#pragma unroll
+      for (int j = 0; j < WTM; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[i], af[j], acc[i][j], 0, 0, 0);
+  }
+  wait_vmcnt<0>();  // drain the clamped tail loads before the LDS goes away
+
+  tiled_epilogue<EPI, WTM, WTN>(e, acc, mt0 + wm * WTM, nt0 + wn * WTN, total_nt, lane, blockIdx.z);
+}
+
+template <int EPI, int WM, int WN, int WTM, int WTN, int NSTAGE>
+static void launch_tiled8_t(const bf16_t* Ap, int MT, const bf16_t* Wp, int total_nt, int KB,
+                            const GemmEpi& e, hipStream_t s, int ksplit) {
+  constexpr int NF = WM * WTM + WN * WTN;
+  const size_t smem = ((size_t)NSTAGE * NF + 1) * 1024;
+  auto kern = gemm_bf16_tiled8_kernel<EPI, WM, WN, WTM, WTN, NSTAGE>;
+  static bool attr_set = false;
+  if (!attr_set && smem > 48 * 1024) {
+    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)smem);
+    attr_set = true;
+  }
+  dim3 grid((total_nt + WN * WTN - 1) / (WN * WTN), (MT + WM * WTM - 1) / (WM * WTM), ksplit);
+  kern<<<grid, WM * WN * 64, smem, s>>>((const u32x4*)Ap, (const u32x4*)Wp, total_nt, KB, MT, e);
 }
 
 // Second half of a K-split residual GEMM: h += sum over the splits (fixed order), then what
@@ -471,24 +590,30 @@ __global__ __launch_bounds__(256) void resid_finish_kernel(GemmEpi e, int ksplit
   }
 }
 
-// Block tile and K split for the tiled kernel, from a cost model calibrated on MI355X timings
-// (a 6x6 wave tile spends about 0.68 us per k-step; smaller tiles feed the MFMAs less well
-// because they re-read more operand bytes per flop from L2).  A grid that does not fill the
-// 256 CUs in whole rounds wastes the remainder, so narrow outputs (N = d_model) are split
-// along K into partial products that a small second kernel sums.
+// Block shapes of the tiled kernel (rows x weight rows, waves) and what one k-step of a block
+// costs on MI355X (us, measured with all 256 CUs busy):
+//   0: 192 x 384, 8 waves   1: 192 x 256, 8 waves   2: 192 x 192   3: 192 x 128   4: 128 x 128
+//   5: 96 x 128 (4 waves each)
+// Eight waves (two per SIMD) overlap one wave's LDS reads and barrier waits with the other's
+// MFMAs, and the wider the block the fewer operand bytes per flop cross the L2, which is what
+// bounds these kernels.  A grid that does not fill the 256 CUs in whole rounds wastes the
+// remainder, so narrow outputs (N = d_model) are also split along K into partial products that
+// a small second kernel sums.
 struct TilePick { int tile, ksplit; };
+constexpr int kNumTiles = 6;
+static const int kTileM[kNumTiles] = {12, 12, 12, 12, 8, 6}, kTileN[kNumTiles] = {24, 16, 12, 8, 8, 8};
+static const float kTileUsPerKstep[kNumTiles] = {1.03f, 0.86f, 0.68f, 0.53f, 0.53f, 0.50f};
+
 static TilePick pick_tile(int MT, int total_nt, int KB, int max_ksplit, int M, int N) {
-  static const int wtm[4] = {6, 6, 4, 3}, wtn[4] = {6, 4, 4, 4};
-  static const float rel_eff[4] = {1.00f, 0.92f, 0.80f, 0.45f};
-  TilePick best{0, 1};
+  TilePick best{1, 1};
   float best_t = 1e30f;
-  for (int i = 0; i < 4; ++i) {
-    long gm = (MT + 2 * wtm[i] - 1) / (2 * wtm[i]), gn = (total_nt + 2 * wtn[i] - 1) / (2 * wtn[i]);
+  for (int i = 0; i < kNumTiles; ++i) {
+    long gm = (MT + kTileM[i] - 1) / kTileM[i], gn = (total_nt + kTileN[i] - 1) / kTileN[i];
     for (int ks = 1; ks <= max_ksplit; ++ks) {
       long blocks = gm * gn * ks, rounds = (blocks + 255) / 256;
       float ksteps = (float)((KB + ks - 1) / ks);
-      float t = rounds * (wtm[i] * wtn[i] * ksteps * 0.0189f / rel_eff[i] + 3.0f);
-      if (ks > 1) t += 2.5f + (float)M * N * (ks + 4) * 4.0f / 3.0e6f;  // finish: ~3 TB/s
+      float t = rounds * (ksteps * kTileUsPerKstep[i] + 3.0f);
+      if (ks > 1) t += 2.5f + (float)M * N * (ks + 4) * 4.0f / 5.0e6f;  // finish kernel
       if (t < best_t) { best_t = t; best = TilePick{i, ks}; }
     }
   }
@@ -499,10 +624,12 @@ template <int EPI>
 static void launch_tiled_pick(const bf16_t* Ap, int MT, const bf16_t* Wp, int total_nt, int KB,
                               const GemmEpi& e, hipStream_t s, int tile, int ksplit) {
   switch (tile) {
-    case 0: launch_tiled_t<EPI, 6, 6>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
-    case 1: launch_tiled_t<EPI, 6, 4>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
-    case 2: launch_tiled_t<EPI, 4, 4>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
-    default: launch_tiled_t<EPI, 3, 4>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
+    case 0: launch_tiled8_t<EPI, 2, 4, 6, 6, 3>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
+    case 1: launch_tiled8_t<EPI, 2, 4, 6, 4, 3>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
+    case 2: launch_tiled4_t<EPI, 6, 6>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
+    case 3: launch_tiled4_t<EPI, 6, 4>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
+    case 4: launch_tiled4_t<EPI, 4, 4>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
+    default: launch_tiled4_t<EPI, 3, 4>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
   }
 }
 
