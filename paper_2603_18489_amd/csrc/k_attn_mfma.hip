@@ -24,8 +24,63 @@ __device__ __forceinline__ bf16x8 u4_as_bf16x8(uint4 v) {
   c.u = v;
   return c.b;
 }
-__device__ __forceinline__ uint32_t pack2_bf16(float a, float b) {
-  return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+
+// One 32-key chunk for one 16-query tile: S^T = K Q^T, online softmax down the keys, O^T += V^T P^T.
+// kf / vf: the chunk's K and V^T fragments; qf: the tile's Q fragments; the lane owns query
+// (lane & 15) and keys key0 .. key0+7.  mask_tail (wave-uniform): keys >= T are padding.
+template <int HB, int HT>
+__device__ __forceinline__ void attn_chunk_tile(const bf16x8 (&kf)[2][HB], const bf16x8 (&vf)[HT],
+                                                const bf16x8 (&qf)[HB], f32x4 (&acc)[HT],
+                                                float& m_run, float& l_run, float scale_log2e,
+                                                int key0, int T, bool mask_tail) {
+  f32x4 s2[2];
+#pragma unroll
+  for (int t2 = 0; t2 < 2; ++t2) {
+    s2[t2] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb)
+      s2[t2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[t2][hb], qf[hb], s2[t2], 0, 0, 0);
+  }
+  float sv[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) sv[e] = s2[e >> 2][e & 3];
+  if (mask_tail) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      if (key0 + e >= T) sv[e] = -INFINITY;
+  }
+  float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
+                   fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+  mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  const float m_new = fmaxf(m_run, mx * scale_log2e);  // scale > 0: max commutes with it
+  float rs = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    sv[e] = exp2f(fmaf(sv[e], scale_log2e, -m_new));
+    rs += sv[e];
+  }
+  rs += __shfl_xor(rs, 16, 64);
+  rs += __shfl_xor(rs, 32, 64);
+  // the accumulators are rescaled only when some query of the wave saw a new maximum
+  if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
+    const float alpha = exp2f(m_run - m_new);  // 0 on the first chunk, 1 where nothing changed
+    l_run *= alpha;
+#pragma unroll
+    for (int h = 0; h < HT; ++h) {
+      f32x4 a = acc[h];
+      a[0] *= alpha; a[1] *= alpha; a[2] *= alpha; a[3] *= alpha;
+      acc[h] = a;
+    }
+  }
+  l_run += rs;
+  m_run = m_new;
+  uint4 pu = make_uint4(pack2_bf16(sv[0], sv[1]), pack2_bf16(sv[2], sv[3]),
+                        pack2_bf16(sv[4], sv[5]), pack2_bf16(sv[6], sv[7]));
+  const bf16x8 pf = u4_as_bf16x8(pu);
+#pragma unroll
+  for (int h = 0; h < HT; ++h)
+    acc[h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[h], pf, acc[h], 0, 0, 0);
 }
 
 template <int HD, int QT, bool SPLIT_KEYS>
@@ -89,49 +144,11 @@ __global__ __launch_bounds__(SPLIT_KEYS ? 512 : 256) void attn_mfma_kernel(
     for (int h = 0; h < HT; ++h) vf[h] = u4_as_bf16x8(vbase[((size_t)h * KB32 + c) * 64]);
 
     const int key0 = c * 32 + grp * 8;  // the lane's 8 consecutive keys
+    const bool mask_tail = (c == nchunks - 1) && (T & 31);
 #pragma unroll
-    for (int t = 0; t < QT; ++t) {
-      f32x4 s[2];
-#pragma unroll
-      for (int t2 = 0; t2 < 2; ++t2) {
-        s[t2] = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int hb = 0; hb < HB; ++hb)
-          s[t2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[t2][hb], qf[t][hb], s[t2], 0, 0, 0);
-      }
-      float sv[8];
-      float mx = -INFINITY;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        float v = s[e >> 2][e & 3] * scale_log2e;
-        if (key0 + e >= T) v = -INFINITY;  // padding keys of the last chunk
-        sv[e] = v;
-        mx = fmaxf(mx, v);
-      }
-      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      float m_new = fmaxf(m_run[t], mx);       // finite: every chunk has at least one real key
-      float alpha = exp2f(m_run[t] - m_new);   // 0 on the first chunk
-      float rs = 0.f;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        sv[e] = exp2f(sv[e] - m_new);
-        rs += sv[e];
-      }
-      rs += __shfl_xor(rs, 16, 64);
-      rs += __shfl_xor(rs, 32, 64);
-      l_run[t] = l_run[t] * alpha + rs;
-      m_run[t] = m_new;
-      uint4 pu = make_uint4(pack2_bf16(sv[0], sv[1]), pack2_bf16(sv[2], sv[3]),
-                            pack2_bf16(sv[4], sv[5]), pack2_bf16(sv[6], sv[7]));
-      bf16x8 pf = u4_as_bf16x8(pu);
-#pragma unroll
-      for (int h = 0; h < HT; ++h) {
-        f32x4 a = acc[t][h];
-        a[0] *= alpha; a[1] *= alpha; a[2] *= alpha; a[3] *= alpha;
-        acc[t][h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[h], pf, a, 0, 0, 0);
-      }
-    }
+    for (int t = 0; t < QT; ++t)
+      attn_chunk_tile<HB, HT>(kf, vf, qf[t], acc[t], m_run[t], l_run[t], scale_log2e, key0, T,
+                              mask_tail);
   }
 
   // ---- merge the waves' partial results (fixed binary tree over wave ids) --------------------
@@ -195,6 +212,119 @@ __global__ __launch_bounds__(SPLIT_KEYS ? 512 : 256) void attn_mfma_kernel(
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Many query rows (full step): a block of NW waves owns NW*QT query tiles of one kv head and
+// walks all keys.  Each 32-key chunk (K and V^T fragments, 16 KiB at hd = 128) is loaded once per
+// block, straight from global memory into a 3-stage LDS ring (global_load_lds_dwordx4), and read
+// by all waves.  Two waves per SIMD let one wave's softmax arithmetic run under the other's
+// MFMAs.
+// ---------------------------------------------------------------------------------------------
+template <int N> __device__ __forceinline__ void attn_wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+typedef uint32_t au32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ bf16x8 av4_as_bf16x8(au32x4 v) {
+  union { au32x4 u; bf16x8 b; } c;
+  c.u = v;
+  return c.b;
+}
+
+template <int HD, int QT, int NW>
+__global__ __launch_bounds__(NW * 64) void attn_mfma_shared_kernel(
+    const bf16_t* __restrict__ q, const au32x4* __restrict__ kp, const au32x4* __restrict__ vp,
+    int M, int T, int Tpad, int Hq, int Hkv, float scale_log2e, bf16_t* __restrict__ out,
+    int MT) {
+  constexpr int HB = HD / 32, HT = HD / 16, NSTAGE = 3;
+  constexpr int NFRAG = 2 * HB + HT, LF = NFRAG / NW;
+  static_assert(NFRAG % NW == 0, "fragments per chunk must divide over the waves");
+  extern __shared__ au32x4 ring[];  // [NSTAGE][NFRAG][64]
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int kvh = blockIdx.y, G = Hq / Hkv, nQ = M * G;
+  const int nchunks = (T + 31) >> 5, KB32 = Tpad >> 5;
+  const int tile0 = (blockIdx.x * NW + wave) * QT;
+  const int qcol = lane & 15, grp = lane >> 4;
+
+  // fragment f of a chunk: f < 2*HB is K tile f / HB, hd block f % HB; the rest are V^T hd tiles
+  const au32x4* kbase = kp + (size_t)kvh * KB32 * 2 * HB * 64 + lane;
+  const au32x4* vbase = vp + (size_t)kvh * HT * KB32 * 64 + lane;
+  auto issue = [&](int c) {
+    const int cc = min(c, nchunks - 1), stage = c % NSTAGE;
+#pragma unroll
+    for (int i = 0; i < LF; ++i) {
+      const int f = wave + NW * i;
+      const au32x4* src = f < 2 * HB ? kbase + ((size_t)(cc * 2 + f / HB) * HB + f % HB) * 64
+                                     : vbase + ((size_t)(f - 2 * HB) * KB32 + cc) * 64;
+      __builtin_amdgcn_global_load_lds(
+          (const void __attribute__((address_space(1)))*)src,
+          (void __attribute__((address_space(3)))*)(ring + ((size_t)stage * NFRAG + f) * 64), 16,
+          0, 0);
+    }
+  };
+
+  bf16x8 qf[QT][HB];
+  int qrow[QT], qhead[QT];
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    int qi = (tile0 + t) * 16 + qcol;
+    bool valid = qi < nQ;
+    qrow[t] = valid ? qi / G : -1;
+    qhead[t] = kvh * G + (valid ? qi % G : 0);
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) {
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (valid)
+        v = *(const uint4*)(q + (size_t)qrow[t] * Hq * HD + qhead[t] * HD + hb * 32 + grp * 8);
+      qf[t][hb] = u4_as_bf16x8(v);
+    }
+  }
+  f32x4 acc[QT][HT];
+  float m_run[QT], l_run[QT];
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    m_run[t] = -INFINITY;
+    l_run[t] = 0.f;
+#pragma unroll
+    for (int h = 0; h < HT; ++h) acc[t][h] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  }
+
+#pragma unroll
+  for (int sg = 0; sg < NSTAGE - 1; ++sg) issue(sg);
+  for (int c = 0; c < nchunks; ++c) {
+    attn_wait_vmcnt<LF*(NSTAGE - 2)>();  // this wave's loads of chunk c have landed
+    __syncthreads();                     // ... everyone's have; the stage read last is free
+    issue(c + NSTAGE - 1);
+    const au32x4* st = ring + (size_t)(c % NSTAGE) * NFRAG * 64 + lane;
+    bf16x8 kf[2][HB], vf[HT];
+#pragma unroll
+    for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+      for (int hb = 0; hb < HB; ++hb) kf[t2][hb] = av4_as_bf16x8(st[(t2 * HB + hb) * 64]);
+#pragma unroll
+    for (int h = 0; h < HT; ++h) vf[h] = av4_as_bf16x8(st[(2 * HB + h) * 64]);
+
+    const int key0 = c * 32 + grp * 8;
+    const bool mask_tail = (c == nchunks - 1) && (T & 31);
+#pragma unroll
+    for (int t = 0; t < QT; ++t)
+      attn_chunk_tile<HB, HT>(kf, vf, qf[t], acc[t], m_run[t], l_run[t], scale_log2e, key0, T,
+                              mask_tail);
+  }
+  attn_wait_vmcnt<0>();  // drain the clamped tail loads before the LDS goes away
+
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    if (qrow[t] < 0) continue;
+    float inv = 1.0f / l_run[t];
+#pragma unroll
+    for (int h = 0; h < HT; ++h) {
+      f32x4 a = acc[t][h];
+      uint2 pk = make_uint2(pack2_bf16(a[0] * inv, a[1] * inv), pack2_bf16(a[2] * inv, a[3] * inv));
+      int k = qhead[t] * HD + h * 16 + grp * 4;
+      *(uint2*)(out + packed_act_index(qrow[t], k, MT)) = pk;
+    }
+  }
+}
+
 // LDS a block may use on this device (queried once).
 static size_t max_lds_per_block() {
   static size_t v = 0;
@@ -244,10 +374,18 @@ static void launch_attn_mfma_hd(const bf16_t* q, const uint4* kp, const uint4* v
     if (qtiles <= 1) launch_split<HD, 1>(q, kp, vp, M, T, Tpad, Hq, Hkv, sc, out, MT, qtiles, s);
     else launch_split<HD, 2>(q, kp, vp, M, T, Tpad, Hq, Hkv, sc, out, MT, qtiles, s);
   } else {
-    constexpr int QT = 2, NW = 4;
-    dim3 grid((qtiles + QT * NW - 1) / (QT * NW), Hkv);
-    attn_mfma_kernel<HD, QT, false><<<grid, NW * 64, 0, s>>>(q, kp, vp, M, T, Tpad, Hq, Hkv, sc,
-                                                            out, MT);
+    // two query tiles per wave halve the LDS reads per MFMA, but only pay once the grid still
+    // covers the chip's 256 compute units
+    constexpr int NW = 8, NFRAG = 2 * (HD / 32) + HD / 16;
+    if (((qtiles + 2 * NW - 1) / (2 * NW)) * Hkv >= 256) {
+      dim3 grid((qtiles + 2 * NW - 1) / (2 * NW), Hkv);
+      attn_mfma_shared_kernel<HD, 2, NW><<<grid, NW * 64, 3 * NFRAG * 1024, s>>>(
+          q, (const au32x4*)kp, (const au32x4*)vp, M, T, Tpad, Hq, Hkv, sc, out, MT);
+    } else {
+      dim3 grid((qtiles + NW - 1) / NW, Hkv);
+      attn_mfma_shared_kernel<HD, 1, NW><<<grid, NW * 64, 3 * NFRAG * 1024, s>>>(
+          q, (const au32x4*)kp, (const au32x4*)vp, M, T, Tpad, Hq, Hkv, sc, out, MT);
+    }
   }
 }
 

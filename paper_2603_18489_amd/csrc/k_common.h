@@ -24,6 +24,16 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
   return (bf16_t)(u >> 16);
 }
 
+// two floats -> packed bf16 pair (low half = a), one v_cvt_pk_bf16_f32 on gfx950 (RNE)
+typedef __bf16 bf16x2_hw __attribute__((ext_vector_type(2)));
+typedef float f32x2_hw __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack2_bf16(float a, float b) {
+  f32x2_hw v = {a, b};
+  union { bf16x2_hw h; uint32_t u; } c;
+  c.h = __builtin_convertvector(v, bf16x2_hw);
+  return c.u;
+}
+
 template <typename T> __device__ __forceinline__ float load_f32(const T* p);
 template <> __device__ __forceinline__ float load_f32<float>(const float* p) { return *p; }
 template <> __device__ __forceinline__ float load_f32<bf16_t>(const bf16_t* p) { return bf16_to_f32(*p); }

@@ -41,9 +41,7 @@ __device__ __forceinline__ bf16x8 v4_as_bf16x8(u32x4 v) {
   c.u = v;
   return c.b;
 }
-__device__ __forceinline__ uint32_t pack2(float a, float b) {
-  return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
-}
+__device__ __forceinline__ uint32_t pack2(float a, float b) { return pack2_bf16(a, b); }
 __device__ __forceinline__ float silu_f(float x) { return x / (1.0f + expf(-x)); }
 
 __device__ __forceinline__ float rstd_of(const GemmEpi& e, int row) {
