@@ -46,7 +46,7 @@ struct Buffers {
   // activations
   float* h; void* u; float* qkv; void* q; void* attn; float* gu; void* act; void* u_lm;
   float* logits; float4* partials;
-  // bf16 only: row sums of squares [2L+1][sumsq_stride] (32.32 fixed point), packed matrices
+  // bf16 only: row sums of squares [2L+1][kSumSlots][sumsq_stride] (32.32 fixed point), packed matrices
   unsigned long long* sumsq; int sumsq_stride;
   float* ksplit_part;  // [kMaxKSplit][T][d] partial products of K-split residual GEMMs
   std::vector<PackedLayer> pl; bf16_t* lm_head_p;
@@ -84,7 +84,7 @@ void carve(Carver& c, const ec_model_cfg& m, const ec_decode_cfg& d, int P, Buff
   b.ksplit_part = nullptr;
   b.sumsq_stride = (int)T16;
   if (m.dtype == EC_BF16) {
-    b.sumsq = c.take<unsigned long long>((size_t)(2 * m.n_layers + 1) * T16);
+    b.sumsq = c.take<unsigned long long>((size_t)(2 * m.n_layers + 1) * kSumSlots * T16);
     b.ksplit_part = c.take<float>((size_t)kMaxKSplit * T * m.d_model);
     b.pl.resize(m.n_layers);
     for (int l = 0; l < m.n_layers; ++l) {
@@ -285,15 +285,15 @@ int forward_bf16(ec_ctx* c, int mode, int M, int n_mb) {
   bf16_t* u = (bf16_t*)b.u; bf16_t* q = (bf16_t*)b.q; bf16_t* attn = (bf16_t*)b.attn;
   bf16_t* act = (bf16_t*)b.act;
   auto G = [](const void* p) { return (const bf16_t*)p; };
-  auto sums = [&](int i) { return b.sumsq + (size_t)i * b.sumsq_stride; };
+  auto sums = [&](int i) { return b.sumsq + (size_t)i * kSumSlots * b.sumsq_stride; };
 
   { Scope p(c, EC_K_EMBED);
     launch_embed_bf16(G(c->w.tok_emb), b.x, rows, M, d, G(c->attn_norm[0]), b.h, u, b.sumsq,
-                      2 * L + 1, b.sumsq_stride, s); }
+                      (2 * L + 1) * kSumSlots, b.sumsq_stride, s); }
   for (int l = 0; l < L; ++l) {
     bf16_t* kc = (bf16_t*)kv_ptr(c, l, 0); bf16_t* vc = (bf16_t*)kv_ptr(c, l, 1);
     { Scope p(c, EC_K_QKV);
-      GemmEpi e{}; e.M = M; e.MT = MT; e.sumsq_in = sums(2 * l); e.d_in = d; e.eps = m.rms_eps;
+      GemmEpi e{}; e.M = M; e.MT = MT; e.sumsq_in = sums(2 * l); e.d_in = d; e.eps = m.rms_eps; e.sum_stride = b.sumsq_stride;
       e.rows = rows; e.cs = b.rope_cs; e.Hq = m.n_heads; e.Hkv = m.n_kv_heads; e.hd = hd;
       e.Tpad = Tpad; e.q_out = q; e.kc = kc; e.vc = vc;
       launch_gemm_bf16(EPI_QKV, u, M, b.pl[l].wqkv, nqkv, d, e, s); }
@@ -301,22 +301,24 @@ int forward_bf16(ec_ctx* c, int mode, int M, int n_mb) {
       launch_attention_mfma(q, kc, vc, M, c->T, Tpad, m.n_heads, m.n_kv_heads, hd, attn, s); }
     { Scope p(c, EC_K_OPROJ);
       GemmEpi e{}; e.M = M; e.MT = MT; e.h = b.h; e.d = d; e.gain_next = G(c->mlp_norm[l]);
-      e.a_next = u; e.sumsq_out = sums(2 * l + 1); e.partial = b.ksplit_part; e.max_ksplit = kMaxKSplit;
+      e.a_next = u; e.sumsq_out = sums(2 * l + 1); e.sum_stride = b.sumsq_stride; e.partial = b.ksplit_part;
+      e.max_ksplit = kMaxKSplit;
       launch_gemm_bf16(EPI_RESID, attn, M, b.pl[l].wo, d, nq, e, s); }
     { Scope p(c, EC_K_GATEUP);
-      GemmEpi e{}; e.M = M; e.MT = MT; e.sumsq_in = sums(2 * l + 1); e.d_in = d; e.eps = m.rms_eps;
+      GemmEpi e{}; e.M = M; e.MT = MT; e.sumsq_in = sums(2 * l + 1); e.d_in = d; e.eps = m.rms_eps; e.sum_stride = b.sumsq_stride;
       e.act = act;
       launch_gemm_bf16(EPI_SWIGLU, u, M, b.pl[l].wgu, 2 * F, d, e, s); }
     { Scope p(c, EC_K_DOWN);
       GemmEpi e{}; e.M = M; e.MT = MT; e.h = b.h; e.d = d;
       e.gain_next = G(l + 1 < L ? c->attn_norm[l + 1] : c->w.final_norm);
-      e.a_next = u; e.sumsq_out = sums(2 * l + 2); e.partial = b.ksplit_part; e.max_ksplit = kMaxKSplit;
+      e.a_next = u; e.sumsq_out = sums(2 * l + 2); e.sum_stride = b.sumsq_stride; e.partial = b.ksplit_part;
+      e.max_ksplit = kMaxKSplit;
       launch_gemm_bf16(EPI_RESID, act, M, b.pl[l].wd, d, F, e, s); }
   }
   // logits only for the block's masked rows: the LM head gathers them from `u`
   { Scope p(c, EC_K_LMHEAD);
     GemmEpi e{}; e.M = n_mb; e.MT = (n_mb + 15) / 16; e.row_sel = lm_sel; e.sumsq_in = sums(2 * L);
-    e.d_in = d; e.eps = m.rms_eps; e.scale = m.logit_scale; e.logits = b.logits; e.ldc = m.vocab;
+    e.d_in = d; e.eps = m.rms_eps; e.sum_stride = b.sumsq_stride; e.scale = m.logit_scale; e.logits = b.logits; e.ldc = m.vocab;
     launch_gemm_bf16(EPI_LOGITS, u, M, b.lm_head_p, m.vocab, d, e, s); }
   return EC_OK;
 }

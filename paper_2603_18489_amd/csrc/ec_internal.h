@@ -78,6 +78,10 @@ void launch_attention_f32(const float* q, const float* kc, const float* vc, int 
 // bf16 path
 enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3, EPI_PARTIAL = 4 };
 constexpr int kMaxKSplit = 4;
+// A row's sum of squares is accumulated by many blocks at once.  Atomics on one address
+// serialise, so each row has kSumSlots counters (a block adds to the one its index selects) and
+// the reader adds them up; integer addition keeps the total independent of the order.
+constexpr int kSumSlots = 8;
 enum { REPACK_PLAIN = 0, REPACK_ROPE_PAIRS = 1, REPACK_EVEN = 2, REPACK_ODD = 3 };
 
 // What a GEMM epilogue needs (k_gemm_bf16.hip).  Row sums of squares are 32.32 fixed point.
@@ -85,7 +89,9 @@ struct GemmEpi {
   int M;                          // activation rows of this launch
   int MT;                         // m-tiles of the packed buffers written (a_next, act)
   const int* row_sel;             // nullable: activation row m is read from source row row_sel[m]
-  const unsigned long long* sumsq_in;  // per SOURCE row: sum of squares of the normed input
+  const unsigned long long* sumsq_in;  // [kSumSlots][sum_stride], per SOURCE row: the slots add up
+                                       // to the sum of squares of the normed input (32.32)
+  int sum_stride;
   int d_in;                       // its length
   float eps;
   float scale;                    // EPI_LOGITS
@@ -94,7 +100,7 @@ struct GemmEpi {
   float* partial; int max_ksplit; // nullable: room for [max_ksplit][M][d] fp32 partial products
   const bf16_t* gain_next;        // gain of the norm that follows
   bf16_t* a_next;                 // packed bf16(h * gain_next)
-  unsigned long long* sumsq_out;  // per row, accumulated with integer atomics
+  unsigned long long* sumsq_out;  // [kSumSlots][sum_stride], accumulated with integer atomics
   bf16_t* act;                    // EPI_SWIGLU: packed activations, K = d_ffn
   const int* rows;                // EPI_QKV: position of each row (nullable = identity)
   const float2* cs;               // RoPE table [T][hd/2]

@@ -8,17 +8,24 @@
 //                                            other 24 are 2 xor-shuffles away)
 //   O^T[hd x queries] += V^T . P^T          (HD/16 MFMAs; the lane's 8 probabilities ARE the
 //                                            B operand, V^T fragments straight from the cache)
-// Nothing is staged in LDS: every operand load is a coalesced 1 KiB fragment.
+// Every operand load is a coalesced 1 KiB fragment in the cache's own layout.
 //
-// Two work splits:
-//   SPLIT_KEYS  (few query rows, partial step): a block owns QT query tiles of one kv head and
-//               its waves stride over the key chunks; the waves' partial (m, l, O) are merged in
-//               LDS by a fixed binary tree.
-//   !SPLIT_KEYS (many rows, full step): every wave owns QT query tiles and walks all keys.
+// Two kernels:
+//   split   (few query rows, partial step): a block owns one query tile of one kv head and its
+//           waves stride over the key chunks, fragments going straight to registers; the waves'
+//           partial (m, l, O) are combined through LDS in wave order.
+//   shared  (many rows, full step): a block's waves own query tiles of one kv head and walk all
+//           keys together, each chunk's fragments loaded once into an LDS ring.
 #include "ec_internal.h"
 
 namespace ec {
 
+typedef uint32_t au32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ bf16x8 av4_as_bf16x8(au32x4 v) {
+  union { au32x4 u; bf16x8 b; } c;
+  c.u = v;
+  return c.b;
+}
 __device__ __forceinline__ bf16x8 u4_as_bf16x8(uint4 v) {
   union { uint4 u; bf16x8 b; } c;
   c.u = v;
@@ -83,132 +90,117 @@ __device__ __forceinline__ void attn_chunk_tile(const bf16x8 (&kf)[2][HB], const
     acc[h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[h], pf, acc[h], 0, 0, 0);
 }
 
-template <int HD, int QT, bool SPLIT_KEYS>
-__global__ __launch_bounds__(SPLIT_KEYS ? 512 : 256) void attn_mfma_kernel(
-    const bf16_t* __restrict__ q, const uint4* __restrict__ kp, const uint4* __restrict__ vp,
+// Few query rows (partial step): a block owns ONE 16-query tile of one kv head and its 8 waves
+// stride over the 32-key chunks; each wave keeps two chunks' fragments in flight (the second is
+// loaded while the first is multiplied), and the waves' partial (m, l, O) are combined through
+// LDS in wave order.  grid (kv heads, query tiles): blocks of one head are Hkv apart in launch
+// order, which for Hkv a multiple of 8 puts them on the same XCD, whose L2 then serves the
+// head's K/V to all its query tiles.
+template <int HD>
+__global__ __launch_bounds__(512) void attn_mfma_split_kernel(
+    const bf16_t* __restrict__ q, const au32x4* __restrict__ kp, const au32x4* __restrict__ vp,
     int M, int T, int Tpad, int Hq, int Hkv, float scale_log2e, bf16_t* __restrict__ out,
     int MT) {
-  constexpr int HB = HD / 32, HT = HD / 16;
+  constexpr int HB = HD / 32, HT = HD / 16, NW = 8;
   extern __shared__ float4 lds[];
   // scalar wave index: no MFMA may sit under a condition the compiler could treat as divergent
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int NW = blockDim.x >> 6;
-  const int kvh = blockIdx.y, G = Hq / Hkv, nQ = M * G;
+  const int kvh = blockIdx.x, G = Hq / Hkv, nQ = M * G;
   const int nchunks = (T + 31) >> 5, KB32 = Tpad >> 5;
-  const int tile0 = SPLIT_KEYS ? blockIdx.x * QT : (blockIdx.x * NW + wave) * QT;
   const int qcol = lane & 15, grp = lane >> 4;
-  if constexpr (!SPLIT_KEYS) {
-    if (tile0 * 16 >= nQ) return;  // no block-wide barrier on this path
-  }
 
   // ---- Q fragments (B operand): lane (query qcol, group grp) holds 8 hd columns -------------
-  bf16x8 qf[QT][HB];
-  int qrow[QT], qhead[QT];
+  const int qi = blockIdx.y * 16 + qcol;
+  const bool qvalid = qi < nQ;
+  const int qrow = qvalid ? qi / G : 0, qhead = kvh * G + (qvalid ? qi % G : 0);
+  bf16x8 qf[HB];
 #pragma unroll
-  for (int t = 0; t < QT; ++t) {
-    int qi = (tile0 + t) * 16 + qcol;
-    bool valid = qi < nQ;
-    qrow[t] = valid ? qi / G : -1;
-    qhead[t] = kvh * G + (valid ? qi % G : 0);
-#pragma unroll
-    for (int hb = 0; hb < HB; ++hb) {
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (valid)
-        v = *(const uint4*)(q + (size_t)qrow[t] * Hq * HD + qhead[t] * HD + hb * 32 + grp * 8);
-      qf[t][hb] = u4_as_bf16x8(v);
-    }
+  for (int hb = 0; hb < HB; ++hb) {
+    au32x4 v = *(const au32x4*)(q + (size_t)qrow * Hq * HD + qhead * HD + hb * 32 + grp * 8);
+    qf[hb] = av4_as_bf16x8(qvalid ? v : (au32x4){0u, 0u, 0u, 0u});
   }
 
-  f32x4 acc[QT][HT];
-  float m_run[QT], l_run[QT];
+  f32x4 acc[HT];
+  float m_run = -INFINITY, l_run = 0.f;
 #pragma unroll
-  for (int t = 0; t < QT; ++t) {
-    m_run[t] = -INFINITY;
-    l_run[t] = 0.f;
-#pragma unroll
-    for (int h = 0; h < HT; ++h) acc[t][h] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  for (int h = 0; h < HT; ++h) acc[h] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  const au32x4* kbase = kp + (size_t)kvh * KB32 * 2 * HB * 64 + lane;
+  const au32x4* vbase = vp + (size_t)kvh * HT * KB32 * 64 + lane;
+  // the wave's chunks are wave, wave + NW, ...: n_my of them.  Loads are unconditional (a chunk
+  // past the end re-reads the last one, which is in cache); a chunk past the end is computed
+  // with every key masked, which changes nothing once the wave has seen one real chunk.
+  const int n_my = wave < nchunks ? (nchunks - wave + NW - 1) / NW : 0;
+  bf16x8 kfa[2][HB], vfa[HT], kfb[2][HB], vfb[HT];
+#define EC_AT_LOAD(KF, VF, I)                                                               \
+  {                                                                                         \
+    const int c_ = min(wave + NW * (I), nchunks - 1);                                       \
+    _Pragma("unroll") for (int t2 = 0; t2 < 2; ++t2)                                        \
+      _Pragma("unroll") for (int hb = 0; hb < HB; ++hb)                                     \
+        KF[t2][hb] = av4_as_bf16x8(kbase[((size_t)(c_ * 2 + t2) * HB + hb) * 64]);          \
+    _Pragma("unroll") for (int h = 0; h < HT; ++h)                                          \
+      VF[h] = av4_as_bf16x8(vbase[((size_t)h * KB32 + c_) * 64]);                           \
   }
-
-  const uint4* kbase = kp + (size_t)kvh * KB32 * 2 * HB * 64 + lane;
-  const uint4* vbase = vp + (size_t)kvh * HT * KB32 * 64 + lane;
-  const int c_begin = SPLIT_KEYS ? wave : 0, c_step = SPLIT_KEYS ? NW : 1;
-  for (int c = c_begin; c < nchunks; c += c_step) {
-    bf16x8 kf[2][HB];
-#pragma unroll
-    for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-      for (int hb = 0; hb < HB; ++hb)
-        kf[t2][hb] = u4_as_bf16x8(kbase[((size_t)(c * 2 + t2) * HB + hb) * 64]);
-    bf16x8 vf[HT];
-#pragma unroll
-    for (int h = 0; h < HT; ++h) vf[h] = u4_as_bf16x8(vbase[((size_t)h * KB32 + c) * 64]);
-
-    const int key0 = c * 32 + grp * 8;  // the lane's 8 consecutive keys
-    const bool mask_tail = (c == nchunks - 1) && (T & 31);
-#pragma unroll
-    for (int t = 0; t < QT; ++t)
-      attn_chunk_tile<HB, HT>(kf, vf, qf[t], acc[t], m_run[t], l_run[t], scale_log2e, key0, T,
-                              mask_tail);
+#define EC_AT_COMPUTE(KF, VF, I)                                                            \
+  {                                                                                         \
+    const int c_ = wave + NW * (I);                                                         \
+    const bool real_ = (I) < n_my;                                                          \
+    attn_chunk_tile<HB, HT>(KF, VF, qf, acc, m_run, l_run, scale_log2e, c_ * 32 + grp * 8,  \
+                            real_ ? T : 0, !real_ || ((c_ == nchunks - 1) && (T & 31)));    \
   }
-
-  // ---- merge the waves' partial results (fixed binary tree over wave ids) --------------------
-  if constexpr (SPLIT_KEYS) {
-    constexpr int SLOT = QT * HT * 64 + QT * 32;  // float4 per slot: O tiles + (m,l) pairs
-    for (int half = NW >> 1; half >= 1; half >>= 1) {
-      if (wave >= half && wave < 2 * half) {
-        float4* slot = lds + (size_t)(wave - half) * SLOT;
-#pragma unroll
-        for (int t = 0; t < QT; ++t) {
-#pragma unroll
-          for (int h = 0; h < HT; ++h) {
-            f32x4 a = acc[t][h];
-            slot[(t * HT + h) * 64 + lane] = make_float4(a[0], a[1], a[2], a[3]);
-          }
-          ((float2*)(slot + QT * HT * 64))[t * 64 + lane] = make_float2(m_run[t], l_run[t]);
-        }
-      }
-      __syncthreads();
-      if (wave < half) {
-        const float4* slot = lds + (size_t)wave * SLOT;
-#pragma unroll
-        for (int t = 0; t < QT; ++t) {
-          float2 ml = ((const float2*)(slot + QT * HT * 64))[t * 64 + lane];
-          if (ml.y > 0.f) {  // the other wave saw at least one key
-            float m_new = fmaxf(m_run[t], ml.x);
-            float a_self = (l_run[t] > 0.f) ? exp2f(m_run[t] - m_new) : 0.f;
-            float a_oth = exp2f(ml.x - m_new);
-            l_run[t] = l_run[t] * a_self + ml.y * a_oth;
-            m_run[t] = m_new;
-#pragma unroll
-            for (int h = 0; h < HT; ++h) {
-              float4 o = slot[(t * HT + h) * 64 + lane];
-              f32x4 a = acc[t][h];
-              a[0] = a[0] * a_self + o.x * a_oth;
-              a[1] = a[1] * a_self + o.y * a_oth;
-              a[2] = a[2] * a_self + o.z * a_oth;
-              a[3] = a[3] * a_self + o.w * a_oth;
-              acc[t][h] = a;
-            }
-          }
-        }
-      }
-      __syncthreads();
-    }
-    if (wave != 0) return;
+  EC_AT_LOAD(kfa, vfa, 0)
+  for (int i = 0; i < n_my; i += 2) {
+    EC_AT_LOAD(kfb, vfb, i + 1)
+    __builtin_amdgcn_sched_barrier(0);
+    EC_AT_COMPUTE(kfa, vfa, i)
+    __builtin_amdgcn_sched_barrier(0);
+    EC_AT_LOAD(kfa, vfa, i + 2)
+    __builtin_amdgcn_sched_barrier(0);
+    EC_AT_COMPUTE(kfb, vfb, i + 1)
+    __builtin_amdgcn_sched_barrier(0);
   }
+#undef EC_AT_LOAD
+#undef EC_AT_COMPUTE
 
-  // ---- normalise and store: lane holds hd rows h*16 + grp*4 .. +3 of query qcol --------------
-#pragma unroll
-  for (int t = 0; t < QT; ++t) {
-    if (qrow[t] < 0) continue;
-    float inv = 1.0f / l_run[t];
+  // ---- merge the waves' partial results ------------------------------------------------------
+  // Every wave parks (m, l, O) in LDS; after one barrier wave w combines the NW copies of hd tile
+  // w (and w + NW, ...) in wave order, normalises and stores it.
+  constexpr int SLOT = HT * 64 + 32;  // float4 per wave: O tiles + (m, l) pairs
+  {
+    float4* slot = lds + (size_t)wave * SLOT;
 #pragma unroll
     for (int h = 0; h < HT; ++h) {
-      f32x4 a = acc[t][h];
-      uint2 pk = make_uint2(pack2_bf16(a[0] * inv, a[1] * inv), pack2_bf16(a[2] * inv, a[3] * inv));
-      int k = qhead[t] * HD + h * 16 + grp * 4;
-      *(uint2*)(out + packed_act_index(qrow[t], k, MT)) = pk;
+      f32x4 a = acc[h];
+      slot[h * 64 + lane] = make_float4(a[0], a[1], a[2], a[3]);
     }
+    ((float2*)(slot + HT * 64))[lane] = make_float2(m_run, l_run);
+  }
+  __syncthreads();
+  if (!qvalid) return;
+  float wgt[NW], m_all = -INFINITY, l_all = 0.f;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    float2 ml = ((const float2*)(lds + (size_t)w * SLOT + HT * 64))[lane];
+    wgt[w] = ml.x;
+    m_all = fmaxf(m_all, ml.x);
+  }
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    float2 ml = ((const float2*)(lds + (size_t)w * SLOT + HT * 64))[lane];
+    wgt[w] = ml.y > 0.f ? exp2f(wgt[w] - m_all) : 0.f;  // a wave without keys has weight 0
+    l_all += ml.y * wgt[w];
+  }
+  const float inv = 1.0f / l_all;
+  for (int h = wave; h < HT; h += NW) {
+    float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      float4 v = lds[(size_t)w * SLOT + h * 64 + lane];
+      o.x += v.x * wgt[w]; o.y += v.y * wgt[w]; o.z += v.z * wgt[w]; o.w += v.w * wgt[w];
+    }
+    // lane holds hd rows h*16 + grp*4 .. +3 of query qcol
+    uint2 pk = make_uint2(pack2_bf16(o.x * inv, o.y * inv), pack2_bf16(o.z * inv, o.w * inv));
+    *(uint2*)(out + packed_act_index(qrow, qhead * HD + h * 16 + grp * 4, MT)) = pk;
   }
 }
 
@@ -221,12 +213,6 @@ __global__ __launch_bounds__(SPLIT_KEYS ? 512 : 256) void attn_mfma_kernel(
 // ---------------------------------------------------------------------------------------------
 template <int N> __device__ __forceinline__ void attn_wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-typedef uint32_t au32x4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ bf16x8 av4_as_bf16x8(au32x4 v) {
-  union { au32x4 u; bf16x8 b; } c;
-  c.u = v;
-  return c.b;
 }
 
 template <int HD, int QT, int NW>
@@ -325,54 +311,23 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_shared_kernel(
   }
 }
 
-// LDS a block may use on this device (queried once).
-static size_t max_lds_per_block() {
-  static size_t v = 0;
-  if (v == 0) {
-    int dev = 0, val = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&val, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess &&
-        val > 0)
-      v = (size_t)val;
-    else
-      v = 64 * 1024;
-  }
-  return v;
-}
-
-template <int HD, int QT>
-static void launch_split(const bf16_t* q, const uint4* kp, const uint4* vp, int M, int T, int Tpad,
-                         int Hq, int Hkv, float sc, bf16_t* out, int MT, int qtiles,
-                         hipStream_t s) {
-  constexpr int SLOT = QT * (HD / 16) * 64 + QT * 32;
-  // 8 waves stream more keys at once; 4 waves if the merge buffers of 8 do not fit in LDS
-  int NW = 8;
-  size_t smem = (size_t)(NW / 2) * SLOT * sizeof(float4);
-  if (smem > max_lds_per_block()) {
-    NW = 4;
-    smem = (size_t)(NW / 2) * SLOT * sizeof(float4);
-  }
-  auto kern = attn_mfma_kernel<HD, QT, true>;
-  static size_t attr_set = 0;
-  if (smem > 48 * 1024 && attr_set < smem) {
-    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)smem);
-    attr_set = smem;
-  }
-  dim3 grid((qtiles + QT - 1) / QT, Hkv);
-  kern<<<grid, NW * 64, smem, s>>>(q, kp, vp, M, T, Tpad, Hq, Hkv, sc, out, MT);
-}
-
 template <int HD>
 static void launch_attn_mfma_hd(const bf16_t* q, const uint4* kp, const uint4* vp, int M, int T,
                                 int Tpad, int Hq, int Hkv, bf16_t* out, hipStream_t s) {
   const int G = Hq / Hkv, nQ = M * G, qtiles = (nQ + 15) / 16, MT = (M + 15) / 16;
   const float sc = 1.4426950408889634f / sqrtf((float)HD);
-  if (((qtiles + 1) / 2) * Hkv <= 128) {
-    // few (query tile, kv head) pairs: split the keys over the waves of a block, at most 2 query
-    // tiles per block; otherwise every wave walks all keys for its own query tiles
-    if (qtiles <= 1) launch_split<HD, 1>(q, kp, vp, M, T, Tpad, Hq, Hkv, sc, out, MT, qtiles, s);
-    else launch_split<HD, 2>(q, kp, vp, M, T, Tpad, Hq, Hkv, sc, out, MT, qtiles, s);
+  if (qtiles * Hkv <= 256) {
+    // few (query tile, kv head) pairs: one block each, the keys split over its waves
+    constexpr int SLOT = (HD / 16) * 64 + 32;
+    constexpr size_t smem = 8 * SLOT * sizeof(float4);
+    static bool attr_set = false;
+    if (smem > 48 * 1024 && !attr_set) {
+      (void)hipFuncSetAttribute((const void*)attn_mfma_split_kernel<HD>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+      attr_set = true;
+    }
+    attn_mfma_split_kernel<HD><<<dim3(Hkv, qtiles), 512, smem, s>>>(
+        q, (const au32x4*)kp, (const au32x4*)vp, M, T, Tpad, Hq, Hkv, sc, out, MT);
   } else {
     // two query tiles per wave halve the LDS reads per MFMA, but only pay once the grid still
     // covers the chip's 256 compute units

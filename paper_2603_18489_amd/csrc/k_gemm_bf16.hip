@@ -44,9 +44,15 @@ __device__ __forceinline__ bf16x8 v4_as_bf16x8(u32x4 v) {
 __device__ __forceinline__ uint32_t pack2(float a, float b) { return pack2_bf16(a, b); }
 __device__ __forceinline__ float silu_f(float x) { return x / (1.0f + expf(-x)); }
 
-__device__ __forceinline__ float rstd_of(const GemmEpi& e, int row) {
-  double ss = (double)e.sumsq_in[row] * (1.0 / 4294967296.0);
+__device__ __forceinline__ float rstd_from_sum(const GemmEpi& e, unsigned long long fx) {
+  double ss = (double)fx * (1.0 / 4294967296.0);
   return 1.0f / sqrtf((float)(ss / (double)e.d_in) + e.eps);
+}
+__device__ __forceinline__ float rstd_of(const GemmEpi& e, int row) {
+  unsigned long long fx = 0;
+#pragma unroll
+  for (int sl = 0; sl < kSumSlots; ++sl) fx += e.sumsq_in[(size_t)sl * e.sum_stride + row];
+  return rstd_from_sum(e, fx);
 }
 
 // ---- epilogues on one lane's values -----------------------------------------------------------
@@ -81,7 +87,8 @@ __device__ __forceinline__ void epi_add_sumsq(const GemmEpi& e, int m, bool vali
   part += __shfl_xor(part, 32, 64);
   if (valid && (threadIdx.x & 63) < 16) {
     unsigned long long fx = (unsigned long long)((double)part * 4294967296.0 + 0.5);
-    atomicAdd((unsigned long long*)(e.sumsq_out + m), fx);
+    const int slot = (blockIdx.x + blockIdx.y) & (kSumSlots - 1);
+    atomicAdd((unsigned long long*)(e.sumsq_out + (size_t)slot * e.sum_stride + m), fx);
   }
 }
 
@@ -154,7 +161,7 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* 
   // the compiler could treat as divergent
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nt0 = blockIdx.x * NTW;
-  const int kb_lo = (int)(((long)wave * KB) / KS), kb_hi = (int)(((long)(wave + 1) * KB) / KS);
+  const int kb_lo = (wave * KB) / KS, kb_hi = ((wave + 1) * KB) / KS;
 
   // a tile past the end streams tile 0 instead (valid memory) and is dropped at the store
   const u32x4* wp[NTW];
@@ -168,9 +175,13 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* 
 #pragma unroll
   for (int j = 0; j < MT; ++j) {
     int m = j * 16 + (lane & 15);
-    int row = (m < e.M) ? (e.row_sel ? e.row_sel[m] : m) : 0;
+    int row = m < e.M ? m : 0;
+    if constexpr (EPI == EPI_LOGITS) row = (m < e.M && e.row_sel) ? e.row_sel[m] : row;
     ap[j] = Ap + ((size_t)kb_lo * MT_src + (row >> 4)) * 64 + (lane >> 4) * 16 + (row & 15);
   }
+
+  constexpr bool NORMED = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LOGITS);
+  float* rstd_s = (float*)(red + KS * NTW * MT * 64);  // [MT*16]: 1/rms of the block's rows
 
   f32x4 acc[NTW][MT];
 #pragma unroll
@@ -178,20 +189,27 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* 
 #pragma unroll
     for (int j = 0; j < MT; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  // Two register sets of U k-steps each (U is a template parameter): while one set feeds the MFMAs the other set's loads
-  // are in flight, so a wave always has up to 2*U*(NTW+MT) KiB outstanding.  k-steps past the
-  // slice load zeros (the loads honour EXEC; the MFMAs run unconditionally and add nothing).
+  // Two register sets of U k-steps each (U is a template parameter): while one set feeds the
+  // MFMAs the other set's loads are in flight, so a wave always has up to 2*U*(NTW+MT) KiB
+  // outstanding.  Every load is issued unconditionally (straight-line code lets the compiler
+  // count outstanding loads exactly): k-steps past the slice re-read the slice's last fragments,
+  // which are still in cache, and their activation operand is replaced by zeros, so the MFMAs,
+  // which ignore EXEC and must run unconditionally anyway, add nothing.
   const int nkb = kb_hi - kb_lo;
+  const int last = nkb > 0 ? nkb - 1 : 0;
   const u32x4 zero4 = {0u, 0u, 0u, 0u};
   u32x4 wa[U][NTW], aa[U][MT], wb[U][NTW], ab[U][MT];
 #define EC_SK_LOAD(WSET, ASET, IT0)                                                        \
   _Pragma("unroll") for (int u = 0; u < U; ++u) {                                          \
-    const int it_ = (IT0) + u;                                                             \
-    const bool in_ = it_ < nkb;                                                            \
-    _Pragma("unroll") for (int i = 0; i < NTW; ++i)                                        \
-        WSET[u][i] = in_ ? wp[i][(size_t)it_ * 64] : zero4;                                \
+    const int it_ = (IT0) + u < last ? (IT0) + u : last;                                   \
+    _Pragma("unroll") for (int i = 0; i < NTW; ++i) WSET[u][i] = wp[i][(size_t)it_ * 64];  \
     _Pragma("unroll") for (int j = 0; j < MT; ++j)                                         \
-        ASET[u][j] = in_ ? ap[j][(size_t)it_ * MT_src * 64] : zero4;                       \
+        ASET[u][j] = ap[j][(size_t)it_ * MT_src * 64];                                     \
+  }
+#define EC_SK_ZERO_TAIL(ASET, IT0)                                                         \
+  _Pragma("unroll") for (int u = 0; u < U; ++u) {                                          \
+    const bool in_ = (IT0) + u < nkb;                                                      \
+    _Pragma("unroll") for (int j = 0; j < MT; ++j) ASET[u][j] = in_ ? ASET[u][j] : zero4;  \
   }
 #define EC_SK_MMA(WSET, ASET)                                                              \
   _Pragma("unroll") for (int u = 0; u < U; ++u)                                            \
@@ -200,12 +218,44 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* 
         acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                               \
             v4_as_bf16x8(WSET[u][i]), v4_as_bf16x8(ASET[u][j]), acc[i][j], 0, 0, 0);
   EC_SK_LOAD(wa, aa, 0)
-  for (int it0 = 0; it0 < nkb; it0 += 2 * U) {
-    EC_SK_LOAD(wb, ab, it0 + U)
-    EC_SK_MMA(wa, aa)
-    EC_SK_LOAD(wa, aa, it0 + 2 * U)
-    EC_SK_MMA(wb, ab)
+  // The rows' sum-of-squares counters are fetched behind the first operand loads and turned
+  // into 1/rms after the main loop, so neither the loop nor the epilogue waits on them.  All
+  // threads load (those without a row of their own read row 0): no branch, so the compiler
+  // still counts outstanding loads exactly.
+  unsigned long long ssq[kSumSlots];
+  if constexpr (NORMED) {
+#pragma unroll
+    for (int sl = 0; sl < kSumSlots; ++sl) ssq[sl] = 0;
+    __builtin_amdgcn_sched_barrier(0);
+    if (threadIdx.x < MT * 16) {
+      int row = (int)threadIdx.x < e.M ? (int)threadIdx.x : 0;
+      if constexpr (EPI == EPI_LOGITS) row = (e.row_sel && (int)threadIdx.x < e.M) ? e.row_sel[row] : row;
+#pragma unroll
+      for (int sl = 0; sl < kSumSlots; ++sl) ssq[sl] = e.sumsq_in[(size_t)sl * e.sum_stride + row];
+    }
+    __builtin_amdgcn_sched_barrier(0);
   }
+  // (the scheduling barriers keep the compiler from sinking a set's loads down to their first
+  // use, which would leave nothing in flight during the MFMAs)
+  int it0 = 0;
+  for (; it0 + 2 * U < nkb; it0 += 2 * U) {
+    EC_SK_LOAD(wb, ab, it0 + U)
+    __builtin_amdgcn_sched_barrier(0);
+    EC_SK_MMA(wa, aa)
+    __builtin_amdgcn_sched_barrier(0);
+    EC_SK_LOAD(wa, aa, it0 + 2 * U)
+    __builtin_amdgcn_sched_barrier(0);
+    EC_SK_MMA(wb, ab)
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  // last 1 .. 2U k-steps: nothing left to prefetch; only here can a k-step lie past the slice
+  EC_SK_LOAD(wb, ab, it0 + U)
+  __builtin_amdgcn_sched_barrier(0);
+  EC_SK_ZERO_TAIL(aa, it0)
+  EC_SK_MMA(wa, aa)
+  EC_SK_ZERO_TAIL(ab, it0 + U)
+  EC_SK_MMA(wb, ab)
+#undef EC_SK_ZERO_TAIL
 #undef EC_SK_LOAD
 #undef EC_SK_MMA
 
@@ -217,6 +267,16 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* 
       f32x4 v = acc[i][j];
       red[(wave * NTW * MT + i * MT + j) * 64 + lane] = make_float4(v[0], v[1], v[2], v[3]);
     }
+  if constexpr (NORMED) {
+    unsigned long long fx = 0;
+#pragma unroll
+    for (int sl = 0; sl < kSumSlots; ++sl) {
+      // keeps the compiler from adding the counters up (and waiting for them) before the loop
+      asm volatile("" : "+v"(ssq[sl]));
+      fx += ssq[sl];
+    }
+    if (threadIdx.x < MT * 16) rstd_s[threadIdx.x] = rstd_from_sum(e, fx);
+  }
   __syncthreads();
 
   auto ksum = [&](int idx) {
@@ -247,14 +307,14 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* 
       const int vt = nt0 + iu;
       if (mvalid && vt < total_nt) {
         f32x4 v = ksum((iu * MT + j) * 64 + l);
-        epi_logits(e, m, vt, q4, v, rstd_of(e, e.row_sel ? e.row_sel[m] : m));
+        epi_logits(e, m, vt, q4, v, rstd_s[m]);
       }
     } else {
       const int vt = nt0 + 2 * iu;
       if (mvalid && vt < total_nt) {
         f32x4 a = ksum(((2 * iu) * MT + j) * 64 + l);
         f32x4 b = ksum(((2 * iu + 1) * MT + j) * 64 + l);
-        float rs = rstd_of(e, m);
+        float rs = rstd_s[m];
         if constexpr (EPI == EPI_SWIGLU) epi_swiglu(e, m, vt >> 1, q4, a, b, rs);
         else epi_qkv(e, m, vt >> 1, q4, a, b, rs);
       }
@@ -266,7 +326,7 @@ template <int EPI, int MT, int NTW, int KS, int U = 4>
 static void launch_skinny_t(const bf16_t* Ap, int MT_src, const bf16_t* Wp, int total_nt, int KB,
                             const GemmEpi& e, hipStream_t s) {
   int grid = (total_nt + NTW - 1) / NTW;
-  size_t smem = (size_t)KS * NTW * MT * 64 * sizeof(float4);
+  size_t smem = (size_t)KS * NTW * MT * 64 * sizeof(float4) + MT * 16 * sizeof(float);
   gemm_bf16_skinny_kernel<EPI, MT, NTW, KS, U><<<grid, KS * 64, smem, s>>>(
       (const u32x4*)Ap, (const u32x4*)Wp, total_nt, KB, MT_src, e);
 }
@@ -285,8 +345,11 @@ static void launch_skinny_mt(const bf16_t* Ap, int MT_src, const bf16_t* Wp, int
     if (total_nt >= 6 * 256) launch_skinny_t<EPI, MT, 6, 4, 2>(Ap, MT_src, Wp, total_nt, KB, e, s);
     else launch_skinny_t<EPI, MT, 2, 8, 2>(Ap, MT_src, Wp, total_nt, KB, e, s);
   } else {
-    if (total_nt >= 4 * 160) launch_skinny_t<EPI, MT, 4, 8, 2>(Ap, MT_src, Wp, total_nt, KB, e, s);
-    else launch_skinny_t<EPI, MT, 2, 8, 2>(Ap, MT_src, Wp, total_nt, KB, e, s);
+    // (4 m-tiles x 4 weight tiles would not fit the register file)
+    if constexpr (MT < 4) {
+      if (total_nt >= 4 * 160) return launch_skinny_t<EPI, MT, 4, 8, 2>(Ap, MT_src, Wp, total_nt, KB, e, s);
+    }
+    launch_skinny_t<EPI, MT, 2, 8, 2>(Ap, MT_src, Wp, total_nt, KB, e, s);
   }
 }
 
@@ -584,7 +647,7 @@ __global__ __launch_bounds__(256) void resid_finish_kernel(GemmEpi e, int ksplit
   part = block_sum<4>(part, red);
   if (threadIdx.x == 0) {
     unsigned long long fx = (unsigned long long)((double)part * 4294967296.0 + 0.5);
-    atomicAdd((unsigned long long*)(e.sumsq_out + m), fx);
+    atomicAdd((unsigned long long*)(e.sumsq_out + (size_t)(blockIdx.x & (kSumSlots - 1)) * e.sum_stride + m), fx);
   }
 }
 
