@@ -34,7 +34,7 @@ struct Carver {
 // Re-tiled matrices of one layer: [q | k | v] as one matrix (rotary pairs adjacent), o, gate
 // and up interleaved tile by tile, down.
 struct PackedLayer {
-  bf16_t *wqkv, *wo, *wgu, *wd;
+  bf16_t *wqkv, *wo, *wgu, *wd;  // fragment order, tiles grouped by the matrix' skinny block width
 };
 
 struct Buffers {
@@ -55,6 +55,12 @@ struct Buffers {
 size_t esize(int dtype) { return dtype == EC_BF16 ? 2 : 4; }
 // keys held per cache slab: the packed bf16 cache is padded to whole 32-key blocks
 int kv_keys(int dtype, int T) { return dtype == EC_BF16 ? (T + 31) / 32 * 32 : T; }
+
+// elements of a packed [N, K] matrix whose tiles are grouped for the GEMM with epilogue `epi`
+size_t packed_elems(int epi, size_t N, size_t K) {
+  const size_t nt = N / 16, g = (size_t)skinny_tiles_per_block(epi, (int)nt);
+  return (nt + g - 1) / g * g * 16 * K;
+}
 
 void carve(Carver& c, const ec_model_cfg& m, const ec_decode_cfg& d, int P, Buffers& b) {
   const int T = P + d.gen_len, N = d.gen_len;
@@ -89,12 +95,12 @@ void carve(Carver& c, const ec_model_cfg& m, const ec_decode_cfg& d, int P, Buff
     b.pl.resize(m.n_layers);
     for (int l = 0; l < m.n_layers; ++l) {
       PackedLayer& p = b.pl[l];
-      p.wqkv = c.take<bf16_t>((nq + 2 * nkv) * m.d_model);
-      p.wo = c.take<bf16_t>((size_t)m.d_model * nq);
-      p.wgu = c.take<bf16_t>((size_t)2 * m.d_ffn * m.d_model);
-      p.wd = c.take<bf16_t>((size_t)m.d_model * m.d_ffn);
+      p.wqkv = c.take<bf16_t>(packed_elems(EPI_QKV, nq + 2 * nkv, m.d_model));
+      p.wo = c.take<bf16_t>(packed_elems(EPI_RESID, m.d_model, nq));
+      p.wgu = c.take<bf16_t>(packed_elems(EPI_SWIGLU, 2 * m.d_ffn, m.d_model));
+      p.wd = c.take<bf16_t>(packed_elems(EPI_RESID, m.d_model, m.d_ffn));
     }
-    b.lm_head_p = c.take<bf16_t>((size_t)m.vocab * m.d_model);
+    b.lm_head_p = c.take<bf16_t>(packed_elems(EPI_LOGITS, m.vocab, m.d_model));
   }
 }
 
@@ -296,6 +302,7 @@ int forward_bf16(ec_ctx* c, int mode, int M, int n_mb) {
       GemmEpi e{}; e.M = M; e.MT = MT; e.sumsq_in = sums(2 * l); e.d_in = d; e.eps = m.rms_eps; e.sum_stride = b.sumsq_stride;
       e.rows = rows; e.cs = b.rope_cs; e.Hq = m.n_heads; e.Hkv = m.n_kv_heads; e.hd = hd;
       e.Tpad = Tpad; e.q_out = q; e.kc = kc; e.vc = vc;
+      e.w_grp = skinny_tiles_per_block(EPI_QKV, nqkv / 16);
       launch_gemm_bf16(EPI_QKV, u, M, b.pl[l].wqkv, nqkv, d, e, s); }
     { Scope p(c, EC_K_ATTN);
       launch_attention_mfma(q, kc, vc, M, c->T, Tpad, m.n_heads, m.n_kv_heads, hd, attn, s); }
@@ -303,22 +310,26 @@ int forward_bf16(ec_ctx* c, int mode, int M, int n_mb) {
       GemmEpi e{}; e.M = M; e.MT = MT; e.h = b.h; e.d = d; e.gain_next = G(c->mlp_norm[l]);
       e.a_next = u; e.sumsq_out = sums(2 * l + 1); e.sum_stride = b.sumsq_stride; e.partial = b.ksplit_part;
       e.max_ksplit = kMaxKSplit;
+      e.w_grp = skinny_tiles_per_block(EPI_RESID, d / 16);
       launch_gemm_bf16(EPI_RESID, attn, M, b.pl[l].wo, d, nq, e, s); }
     { Scope p(c, EC_K_GATEUP);
       GemmEpi e{}; e.M = M; e.MT = MT; e.sumsq_in = sums(2 * l + 1); e.d_in = d; e.eps = m.rms_eps; e.sum_stride = b.sumsq_stride;
       e.act = act;
+      e.w_grp = skinny_tiles_per_block(EPI_SWIGLU, 2 * F / 16);
       launch_gemm_bf16(EPI_SWIGLU, u, M, b.pl[l].wgu, 2 * F, d, e, s); }
     { Scope p(c, EC_K_DOWN);
       GemmEpi e{}; e.M = M; e.MT = MT; e.h = b.h; e.d = d;
       e.gain_next = G(l + 1 < L ? c->attn_norm[l + 1] : c->w.final_norm);
       e.a_next = u; e.sumsq_out = sums(2 * l + 2); e.sum_stride = b.sumsq_stride; e.partial = b.ksplit_part;
       e.max_ksplit = kMaxKSplit;
+      e.w_grp = skinny_tiles_per_block(EPI_RESID, d / 16);
       launch_gemm_bf16(EPI_RESID, act, M, b.pl[l].wd, d, F, e, s); }
   }
   // logits only for the block's masked rows: the LM head gathers them from `u`
   { Scope p(c, EC_K_LMHEAD);
     GemmEpi e{}; e.M = n_mb; e.MT = (n_mb + 15) / 16; e.row_sel = lm_sel; e.sumsq_in = sums(2 * L);
     e.d_in = d; e.eps = m.rms_eps; e.sum_stride = b.sumsq_stride; e.scale = m.logit_scale; e.logits = b.logits; e.ldc = m.vocab;
+    e.w_grp = skinny_tiles_per_block(EPI_LOGITS, m.vocab / 16);
     launch_gemm_bf16(EPI_LOGITS, u, M, b.lm_head_p, m.vocab, d, e, s); }
   return EC_OK;
 }
@@ -495,18 +506,19 @@ int ec_init(ec_ctx** out, const ec_model_cfg* model, const ec_weights* weights,
     auto B = [](const void* p) { return (const bf16_t*)p; };
     for (int l = 0; l < L; ++l) {
       PackedLayer& p = c->b.pl[l];
-      launch_repack_weight(B(c->wq[l]), nq, d, p.wqkv, REPACK_ROPE_PAIRS, hd, c->stream);
-      launch_repack_weight(B(c->wk[l]), nkv, d, p.wqkv + (size_t)nq * d, REPACK_ROPE_PAIRS, hd,
-                           c->stream);
-      launch_repack_weight(B(c->wv[l]), nkv, d, p.wqkv + (size_t)(nq + nkv) * d, REPACK_PLAIN, hd,
-                           c->stream);
-      launch_repack_weight(B(c->wo[l]), d, nq, p.wo, REPACK_PLAIN, hd, c->stream);
-      launch_repack_weight(B(c->w_gate[l]), F, d, p.wgu, REPACK_EVEN, hd, c->stream);
-      launch_repack_weight(B(c->w_up[l]), F, d, p.wgu, REPACK_ODD, hd, c->stream);
-      launch_repack_weight(B(c->w_down[l]), d, F, p.wd, REPACK_PLAIN, hd, c->stream);
+      const int gq = skinny_tiles_per_block(EPI_QKV, (nq + 2 * nkv) / 16);
+      const int go = skinny_tiles_per_block(EPI_RESID, d / 16);
+      const int gg = skinny_tiles_per_block(EPI_SWIGLU, 2 * F / 16);
+      launch_repack_weight(B(c->wq[l]), nq, d, p.wqkv, REPACK_ROPE_HALVES, hd, gq, 0, c->stream);
+      launch_repack_weight(B(c->wk[l]), nkv, d, p.wqkv, REPACK_ROPE_HALVES, hd, gq, nq, c->stream);
+      launch_repack_weight(B(c->wv[l]), nkv, d, p.wqkv, REPACK_PLAIN, hd, gq, nq + nkv, c->stream);
+      launch_repack_weight(B(c->wo[l]), d, nq, p.wo, REPACK_PLAIN, hd, go, 0, c->stream);
+      launch_repack_weight(B(c->w_gate[l]), F, d, p.wgu, REPACK_LO8, hd, gg, 0, c->stream);
+      launch_repack_weight(B(c->w_up[l]), F, d, p.wgu, REPACK_HI8, hd, gg, 0, c->stream);
+      launch_repack_weight(B(c->w_down[l]), d, F, p.wd, REPACK_PLAIN, hd, go, 0, c->stream);
     }
     launch_repack_weight(B(c->w.lm_head), c->m.vocab, d, c->b.lm_head_p, REPACK_PLAIN, hd,
-                         c->stream);
+                         skinny_tiles_per_block(EPI_LOGITS, c->m.vocab / 16), 0, c->stream);
   }
   e = hipGetLastError();
   if (e != hipSuccess) return bail(EC_ERR_HIP, std::string("set-up kernels: ") + hipGetErrorString(e));

@@ -82,7 +82,7 @@ constexpr int kMaxKSplit = 4;
 // serialise, so each row has kSumSlots counters (a block adds to the one its index selects) and
 // the reader adds them up; integer addition keeps the total independent of the order.
 constexpr int kSumSlots = 8;
-enum { REPACK_PLAIN = 0, REPACK_ROPE_PAIRS = 1, REPACK_EVEN = 2, REPACK_ODD = 3 };
+enum { REPACK_PLAIN = 0, REPACK_ROPE_HALVES = 1, REPACK_LO8 = 2, REPACK_HI8 = 3 };
 
 // What a GEMM epilogue needs (k_gemm_bf16.hip).  Row sums of squares are 32.32 fixed point.
 struct GemmEpi {
@@ -92,6 +92,7 @@ struct GemmEpi {
   const unsigned long long* sumsq_in;  // [kSumSlots][sum_stride], per SOURCE row: the slots add up
                                        // to the sum of squares of the normed input (32.32)
   int sum_stride;
+  int w_grp;  // tiles per group of the weight matrix' layout (k_common.h)
   int d_in;                       // its length
   float eps;
   float scale;                    // EPI_LOGITS
@@ -114,11 +115,16 @@ struct GemmEpi {
 void launch_embed_bf16(const bf16_t* emb, const int* x, const int* rows, int M, int d,
                        const bf16_t* gain, float* h, bf16_t* a_out, unsigned long long* sumsq,
                        int nbuf, int sumsq_stride, hipStream_t s);
-// Re-tiles W[N,K] (row-major) into fragment order.  mode picks the destination tile of each
-// source tile: plain, rotary pairs (columns j and j+hd/2 of a head in adjacent tiles), or the
-// even / odd tiles of a two-matrix interleave.
-void launch_repack_weight(const bf16_t* W, int N, int K, bf16_t* Wp, int mode, int hd,
-                          hipStream_t s);
+// Re-tiles W[N,K] (row-major) into fragment order inside a packed matrix whose tiles are
+// grouped by `grp`.  mode picks the destination row of each source row (row0 = first destination
+// row of this source matrix): plain; rotary halves (a head's tile t holds its columns 8t..8t+7
+// in rows 0-7 and their rotary partners hd/2 later in rows 8-15); or rows 0-7 / 8-15 of every
+// tile of a two-matrix interleave (gate / up).
+void launch_repack_weight(const bf16_t* W, int N, int K, bf16_t* Wp, int mode, int hd, int grp,
+                          int row0, hipStream_t s);
+// Weight tiles per block the skinny GEMM uses for a matrix of total_nt tiles, which is also the
+// group size its packed layout should have.
+int skinny_tiles_per_block(int epi, int total_nt);
 void launch_unpack_cache(const bf16_t* packed, int is_v, int T, int Tpad, int Hkv, int hd,
                          bf16_t* out, hipStream_t s);
 // A: packed activations holding M_src rows; W: packed [N/16 tiles][K/32]; see GemmEpi.

@@ -34,6 +34,13 @@ __device__ __forceinline__ uint32_t pack2_bf16(float a, float b) {
   return c.u;
 }
 
+// value held by the lane 32 positions away (one v_permlane32_swap, no LDS traffic)
+__device__ __forceinline__ float other_half(float x) {
+  const unsigned u = __float_as_uint(x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);  // {[lo,lo], [hi,hi]} of u
+  return __uint_as_float((threadIdx.x & 32) ? r[0] : r[1]);
+}
+
 template <typename T> __device__ __forceinline__ float load_f32(const T* p);
 template <> __device__ __forceinline__ float load_f32<float>(const float* p) { return *p; }
 template <> __device__ __forceinline__ float load_f32<bf16_t>(const bf16_t* p) { return bf16_to_f32(*p); }
@@ -51,9 +58,14 @@ __device__ __forceinline__ size_t packed_act_index(int m, int k, int MT) {
   int kb = k >> 5, g = (k >> 3) & 3, e = k & 7, mt = m >> 4, r = m & 15;
   return ((size_t)(kb * MT + mt) * 64 + g * 16 + r) * 8 + e;
 }
-__device__ __forceinline__ size_t packed_w_index(int n, int k, int KB) {
+// Weight fragments are stored in groups of `grp` tiles: [tile / grp][kb][tile % grp], so that a
+// block that owns a whole group reads grp KiB of contiguous memory per k-step.
+__device__ __forceinline__ size_t packed_w_frag(int nt, int kb, int KB, int grp) {
+  return ((size_t)(nt / grp) * KB + kb) * grp + (nt % grp);
+}
+__device__ __forceinline__ size_t packed_w_index(int n, int k, int KB, int grp) {
   int kb = k >> 5, g = (k >> 3) & 3, e = k & 7, nt = n >> 4, r = n & 15;
-  return (((size_t)nt * KB + kb) * 64 + g * 16 + r) * 8 + e;
+  return (packed_w_frag(nt, kb, KB, grp) * 64 + g * 16 + r) * 8 + e;
 }
 
 // ---- packed bf16 KV cache (one kv head = one contiguous slab of Tpad * HD elements) -----------

@@ -42,7 +42,11 @@ __device__ __forceinline__ bf16x8 v4_as_bf16x8(u32x4 v) {
   return c.b;
 }
 __device__ __forceinline__ uint32_t pack2(float a, float b) { return pack2_bf16(a, b); }
-__device__ __forceinline__ float silu_f(float x) { return x / (1.0f + expf(-x)); }
+// x * sigmoid(x) with the hardware exp2 and reciprocal (about 1 ulp each; the result is rounded
+// to bf16 anyway).  exp overflow gives rcp(inf) = 0, the right limit.
+__device__ __forceinline__ float silu_f(float x) {
+  return x * __builtin_amdgcn_rcpf(1.0f + __expf(-x));
+}
 
 __device__ __forceinline__ float rstd_from_sum(const GemmEpi& e, unsigned long long fx) {
   double ss = (double)fx * (1.0 / 4294967296.0);
@@ -92,58 +96,79 @@ __device__ __forceinline__ void epi_add_sumsq(const GemmEpi& e, int m, bool vali
   }
 }
 
-// gate = tile 2p, up = tile 2p+1 of the interleaved matrix; feature tile p
-__device__ __forceinline__ void epi_swiglu(const GemmEpi& e, int m, int p, int q4, f32x4 g,
-                                           f32x4 u, float rs) {
-  u32x2 pk;
-  pk[0] = pack2(silu_f(g[0] * rs) * (u[0] * rs), silu_f(g[1] * rs) * (u[1] * rs));
-  pk[1] = pack2(silu_f(g[2] * rs) * (u[2] * rs), silu_f(g[3] * rs) * (u[3] * rs));
-  *(u32x2*)(e.act + packed_act_index(m, p * 16 + q4 * 4, e.MT)) = pk;
+// Tile p of the interleaved matrix holds gate rows 8p..8p+7 in its rows 0-7 and the matching up
+// rows in rows 8-15: lanes with q4 < 2 hold gates, their partners 32 lanes up hold the ups.
+// (Lanes l and l^32 share the activation row, so a row-validity condition around the call keeps
+// both or neither.)
+__device__ __forceinline__ void epi_swiglu(const GemmEpi& e, int m, int p, int q4, f32x4 v,
+                                           float rs) {
+  float o[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) o[r] = other_half(v[r]);
+  if (q4 < 2) {
+    u32x2 pk;
+    pk[0] = pack2(silu_f(v[0] * rs) * (o[0] * rs), silu_f(v[1] * rs) * (o[1] * rs));
+    pk[1] = pack2(silu_f(v[2] * rs) * (o[2] * rs), silu_f(v[3] * rs) * (o[3] * rs));
+    *(u32x2*)(e.act + packed_act_index(m, p * 8 + q4 * 4, e.MT)) = pk;
+  }
 }
 
-// Virtual tile pair (2p, 2p+1) of the [q | k | v] matrix.  In the q and k regions the pair
-// holds columns j.. and j+hd/2.. of one head; in the v region the tiles are in natural order.
-__device__ __forceinline__ void epi_qkv(const GemmEpi& e, int m, int vpair, int q4, f32x4 a,
-                                        f32x4 b, float rs) {
+// Tiles p and p+1 at once, so that every lane has an activation to compute: lanes with q4 < 2
+// finish tile p (own gates, partners' ups), the others tile p+1 (partners' gates, own ups).
+__device__ __forceinline__ void epi_swiglu2(const GemmEpi& e, int m, int p, int q4, f32x4 va,
+                                            f32x4 vb, float rs) {
+  const bool lo = q4 < 2;
+  u32x2 pk;
+  float a[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    float got = other_half(lo ? vb[r] : va[r]);
+    float g = lo ? va[r] : got, u = lo ? got : vb[r];
+    a[r] = silu_f(g * rs) * (u * rs);
+  }
+  pk[0] = pack2(a[0], a[1]); pk[1] = pack2(a[2], a[3]);
+  *(u32x2*)(e.act + packed_act_index(m, (lo ? p : p + 1) * 8 + (q4 & 1) * 4, e.MT)) = pk;
+}
+
+// Virtual tile vt of the [q | k | v] matrix.  In the q and k regions tile w of a head holds the
+// head's columns 8w..8w+7 in rows 0-7 and their rotary partners (hd/2 columns later) in rows
+// 8-15, so a lane and its partner 32 lanes away hold one rotation pair; in the v region the
+// tiles are in natural order.
+__device__ __forceinline__ void epi_qkv(const GemmEpi& e, int m, int vt, int q4, f32x4 v,
+                                        float rs) {
   const int hd = e.hd, tph = hd >> 4;  // tiles per head
   const int nqt = e.Hq * tph, nkt = e.Hkv * tph;
-  const int vt = vpair * 2;
   const int pos = e.rows ? e.rows[m] : m;
   if (vt < nqt + nkt) {
-    const bool is_q = vt < nqt;
+    float o[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) o[r] = other_half(v[r]);
+    const bool is_q = vt < nqt, hi = q4 >= 2;
     const int t = is_q ? vt : vt - nqt;
-    const int head = t / tph, j = ((t % tph) >> 1) * 16 + q4 * 4;  // column within the head
+    const int head = t / tph, j = (t % tph) * 8 + (q4 & 1) * 4;  // column within the half head
     const float2* cs = e.cs + (size_t)pos * (hd >> 1) + j;
-    float lo[4], hi[4];
+    float out[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      float x = a[r] * rs, y = b[r] * rs;
+      float x = v[r] * rs, y = o[r] * rs;
       float2 c = cs[r];
-      lo[r] = x * c.x - y * c.y;
-      hi[r] = y * c.x + x * c.y;
+      out[r] = hi ? x * c.x + y * c.y : x * c.x - y * c.y;
     }
-    u32x2 plo, phi;
-    plo[0] = pack2(lo[0], lo[1]); plo[1] = pack2(lo[2], lo[3]);
-    phi[0] = pack2(hi[0], hi[1]); phi[1] = pack2(hi[2], hi[3]);
+    u32x2 pk;
+    pk[0] = pack2(out[0], out[1]); pk[1] = pack2(out[2], out[3]);
+    const int col = j + (hi ? hd >> 1 : 0);
     if (is_q) {
-      bf16_t* dst = e.q_out + (size_t)m * (e.Hq * hd) + head * hd + j;
-      *(u32x2*)dst = plo;
-      *(u32x2*)(dst + (hd >> 1)) = phi;
+      *(u32x2*)(e.q_out + (size_t)m * (e.Hq * hd) + head * hd + col) = pk;
     } else {
       bf16_t* slab = e.kc + (size_t)head * e.Tpad * hd;
-      *(u32x2*)(slab + kcache_index(pos, j, hd)) = plo;
-      *(u32x2*)(slab + kcache_index(pos, j + (hd >> 1), hd)) = phi;
+      *(u32x2*)(slab + kcache_index(pos, col, hd)) = pk;
     }
   } else {
+    const int t = vt - nqt - nkt;
+    const int head = t / tph, c0 = (t % tph) * 16 + q4 * 4;
+    bf16_t* slab = e.vc + (size_t)head * e.Tpad * hd;
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      const int t = vt + half - nqt - nkt;
-      const int head = t / tph, c0 = (t % tph) * 16 + q4 * 4;
-      bf16_t* slab = e.vc + (size_t)head * e.Tpad * hd;
-      f32x4 v = half ? b : a;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) slab[vcache_index(pos, c0 + r, e.Tpad)] = f32_to_bf16(v[r] * rs);
-    }
+    for (int r = 0; r < 4; ++r) slab[vcache_index(pos, c0 + r, e.Tpad)] = f32_to_bf16(v[r] * rs);
   }
 }
 
@@ -164,12 +189,14 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* 
   const int kb_lo = (wave * KB) / KS, kb_hi = ((wave + 1) * KB) / KS;
 
   // a tile past the end streams tile 0 instead (valid memory) and is dropped at the store
+  const int grp = e.w_grp;
   const u32x4* wp[NTW];
 #pragma unroll
   for (int i = 0; i < NTW; ++i) {
     int nt = nt0 + i < total_nt ? nt0 + i : 0;
-    wp[i] = Wp + ((size_t)nt * KB + kb_lo) * 64 + lane;
+    wp[i] = Wp + packed_w_frag(nt, kb_lo, KB, grp) * 64 + lane;
   }
+  const size_t wstep = (size_t)grp * 64;  // u32x4 per k-step
   // activation rows may be gathered (LM head: only the block's masked rows)
   const u32x4* ap[MT];
 #pragma unroll
@@ -202,7 +229,7 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* 
 #define EC_SK_LOAD(WSET, ASET, IT0)                                                        \
   _Pragma("unroll") for (int u = 0; u < U; ++u) {                                          \
     const int it_ = (IT0) + u < last ? (IT0) + u : last;                                   \
-    _Pragma("unroll") for (int i = 0; i < NTW; ++i) WSET[u][i] = wp[i][(size_t)it_ * 64];  \
+    _Pragma("unroll") for (int i = 0; i < NTW; ++i) WSET[u][i] = wp[i][(size_t)it_ * wstep];  \
     _Pragma("unroll") for (int j = 0; j < MT; ++j)                                         \
         ASET[u][j] = ap[j][(size_t)it_ * MT_src * 64];                                     \
   }
@@ -290,34 +317,21 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* 
   };
 
   static_assert(EPI != EPI_PARTIAL, "K-split partial products are a tiled-kernel epilogue");
-  constexpr bool PAIR = (EPI == EPI_QKV || EPI == EPI_SWIGLU);
-  static_assert(!PAIR || NTW % 2 == 0, "pair epilogues need an even number of tiles per block");
-  constexpr int UNITS = (PAIR ? NTW / 2 : NTW) * MT * 64;  // whole waves: UNITS % 64 == 0
+  constexpr int UNITS = NTW * MT * 64;  // whole waves: the wave's 64 lanes share (tile, m-tile)
   for (int o = threadIdx.x; o < UNITS; o += KS * 64) {
     const int l = o & 63, unit = o >> 6, iu = unit / MT, j = unit - iu * MT;
     const int m = j * 16 + (l & 15), q4 = l >> 4;
     const bool mvalid = m < e.M;
+    const int vt = nt0 + iu;
+    f32x4 v = ksum((iu * MT + j) * 64 + l);
     if constexpr (EPI == EPI_RESID) {
-      const int vt = nt0 + iu;
-      f32x4 v = ksum((iu * MT + j) * 64 + l);
       float part = 0.f;
       if (mvalid && vt < total_nt) part = epi_resid(e, m, vt, q4, v);
       epi_add_sumsq(e, m, mvalid, part);
-    } else if constexpr (EPI == EPI_LOGITS) {
-      const int vt = nt0 + iu;
-      if (mvalid && vt < total_nt) {
-        f32x4 v = ksum((iu * MT + j) * 64 + l);
-        epi_logits(e, m, vt, q4, v, rstd_s[m]);
-      }
-    } else {
-      const int vt = nt0 + 2 * iu;
-      if (mvalid && vt < total_nt) {
-        f32x4 a = ksum(((2 * iu) * MT + j) * 64 + l);
-        f32x4 b = ksum(((2 * iu + 1) * MT + j) * 64 + l);
-        float rs = rstd_s[m];
-        if constexpr (EPI == EPI_SWIGLU) epi_swiglu(e, m, vt >> 1, q4, a, b, rs);
-        else epi_qkv(e, m, vt >> 1, q4, a, b, rs);
-      }
+    } else if (mvalid && vt < total_nt) {
+      if constexpr (EPI == EPI_LOGITS) epi_logits(e, m, vt, q4, v, rstd_s[m]);
+      else if constexpr (EPI == EPI_SWIGLU) epi_swiglu(e, m, vt, q4, v, rstd_s[m]);
+      else epi_qkv(e, m, vt, q4, v, rstd_s[m]);
     }
   }
 }
@@ -333,7 +347,15 @@ static void launch_skinny_t(const bf16_t* Ap, int MT_src, const bf16_t* Wp, int 
 
 // Tile counts per block were chosen by timing on MI355X: the kernels are bound by what the L2
 // delivers (weights once + the activation fragments once per block), so more weight tiles per
-// block (fewer re-reads of the activations) win as long as the grid still covers the CUs.
+// block (fewer re-reads of the activations) win as long as the grid still covers the 256 CUs.
+int skinny_tiles_per_block(int epi, int total_nt) {
+  if (epi == EPI_RESID) return 1;
+  if (epi == EPI_LOGITS) return 4;
+  if (total_nt >= 6 * 256) return 6;
+  if (total_nt >= 3 * 256) return 3;
+  return total_nt >= 2 * 256 ? 2 : 1;
+}
+
 template <int EPI, int MT>
 static void launch_skinny_mt(const bf16_t* Ap, int MT_src, const bf16_t* Wp, int total_nt, int KB,
                              const GemmEpi& e, hipStream_t s) {
@@ -341,26 +363,123 @@ static void launch_skinny_mt(const bf16_t* Ap, int MT_src, const bf16_t* Wp, int
     launch_skinny_t<EPI, MT, 4, 4, 4>(Ap, MT_src, Wp, total_nt, KB, e, s);
   } else if constexpr (EPI == EPI_RESID) {
     launch_skinny_t<EPI, MT, 1, 8, 2>(Ap, MT_src, Wp, total_nt, KB, e, s);
-  } else if constexpr (EPI == EPI_SWIGLU) {
-    if (total_nt >= 6 * 256) launch_skinny_t<EPI, MT, 6, 4, 2>(Ap, MT_src, Wp, total_nt, KB, e, s);
-    else launch_skinny_t<EPI, MT, 2, 8, 2>(Ap, MT_src, Wp, total_nt, KB, e, s);
   } else {
-    // (4 m-tiles x 4 weight tiles would not fit the register file)
-    if constexpr (MT < 4) {
-      if (total_nt >= 4 * 160) return launch_skinny_t<EPI, MT, 4, 8, 2>(Ap, MT_src, Wp, total_nt, KB, e, s);
+    switch (skinny_tiles_per_block(EPI, total_nt)) {
+      case 6: launch_skinny_t<EPI, MT, 6, 4, 2>(Ap, MT_src, Wp, total_nt, KB, e, s); break;
+      case 3: launch_skinny_t<EPI, MT, 3, 8, 2>(Ap, MT_src, Wp, total_nt, KB, e, s); break;
+      case 2: launch_skinny_t<EPI, MT, 2, 8, 2>(Ap, MT_src, Wp, total_nt, KB, e, s); break;
+      default: launch_skinny_t<EPI, MT, 1, 8, 2>(Ap, MT_src, Wp, total_nt, KB, e, s); break;
     }
-    launch_skinny_t<EPI, MT, 2, 8, 2>(Ap, MT_src, Wp, total_nt, KB, e, s);
   }
+}
+
+// ---------------------------------------------------------------------------------------------
+// QKV epilogue of the tiled kernels.  The rotation factors come from a table in global memory;
+// a load issued between two stores cannot be moved up by the compiler (the stores might alias
+// it), so one m-tile's factors are fetched while the previous m-tile is rotated and stored:
+// one exposed load latency per wave instead of one per accumulator tile.  (Needs registers the
+// 8-wave kernels do not have; they rotate tile by tile.)
+// ---------------------------------------------------------------------------------------------
+template <int WTM, int WTN>
+__device__ __forceinline__ void tiled_epilogue_qkv(const GemmEpi& e, f32x4 (&acc)[WTN][WTM],
+                                                   int mt_base, int nt_base, int total_nt,
+                                                   int lane) {
+  const int q4 = lane >> 4, hd = e.hd, tph = hd >> 4, half = hd >> 1;
+  const int nqt = e.Hq * tph, nkt = e.Hkv * tph;
+  const bool hi = q4 >= 2;
+  // wave-uniform description of the WTN weight tiles: kind 0 = q, 1 = k, 2 = v, 3 = past the end
+  int kind[WTN], head[WTN], w[WTN];
+#pragma unroll
+  for (int i = 0; i < WTN; ++i) {
+    const int vt = nt_base + i;
+    kind[i] = vt >= total_nt ? 3 : vt < nqt ? 0 : vt < nqt + nkt ? 1 : 2;
+    const int t = kind[i] == 0 ? vt : kind[i] == 1 ? vt - nqt : kind[i] == 2 ? vt - nqt - nkt : 0;
+    head[i] = t / tph;
+    w[i] = t - head[i] * tph;
+  }
+  int pos[WTM];
+  float rs[WTM];
+  bool mvalid[WTM];
+#pragma unroll
+  for (int j = 0; j < WTM; ++j) {
+    const int m = (mt_base + j) * 16 + (lane & 15);
+    mvalid[j] = m < e.M;
+    const int mm = mvalid[j] ? m : 0;
+    pos[j] = e.rows ? e.rows[mm] : mm;
+    rs[j] = rstd_of(e, mm);
+  }
+  float4 ca[WTN][2], cb[WTN][2];  // (cos, sin) x 4 columns for each rotary tile of one m-tile
+#define EC_QKV_LOADC(C, J)                                                                   \
+  _Pragma("unroll") for (int i = 0; i < WTN; ++i) if (kind[i] < 2) {                           \
+    const float4* src_ = (const float4*)(e.cs + (size_t)pos[J] * half + w[i] * 8 + (q4 & 1) * 4); \
+    C[i][0] = src_[0];                                                                       \
+    C[i][1] = src_[1];                                                                       \
+  }
+#define EC_QKV_STORE(C, J)                                                                   \
+  _Pragma("unroll") for (int i = 0; i < WTN; ++i) {                                            \
+    const f32x4 v = acc[i][J];                                                               \
+    const int m_ = (mt_base + (J)) * 16 + (lane & 15);                                       \
+    if (kind[i] < 2) {                                                                       \
+      float o_[4], out_[4];                                                                  \
+      _Pragma("unroll") for (int r = 0; r < 4; ++r) o_[r] = other_half(v[r]);                  \
+      const float cc_[4] = {C[i][0].x, C[i][0].z, C[i][1].x, C[i][1].z};                      \
+      const float ss_[4] = {C[i][0].y, C[i][0].w, C[i][1].y, C[i][1].w};                      \
+      _Pragma("unroll") for (int r = 0; r < 4; ++r) {                                          \
+        const float x = v[r] * rs[J], y = o_[r] * rs[J];                                     \
+        out_[r] = hi ? x * cc_[r] + y * ss_[r] : x * cc_[r] - y * ss_[r];                     \
+      }                                                                                      \
+      u32x2 pk_;                                                                             \
+      pk_[0] = pack2(out_[0], out_[1]);                                                      \
+      pk_[1] = pack2(out_[2], out_[3]);                                                      \
+      const int col_ = w[i] * 8 + (q4 & 1) * 4 + (hi ? half : 0);                             \
+      if (mvalid[J]) {                                                                       \
+        if (kind[i] == 0)                                                                    \
+          *(u32x2*)(e.q_out + (size_t)m_ * (e.Hq * hd) + head[i] * hd + col_) = pk_;          \
+        else                                                                                 \
+          *(u32x2*)(e.kc + (size_t)head[i] * e.Tpad * hd + kcache_index(pos[J], col_, hd)) = pk_; \
+      }                                                                                      \
+    } else if (kind[i] == 2 && mvalid[J]) {                                                  \
+      bf16_t* slab_ = e.vc + (size_t)head[i] * e.Tpad * hd;                                   \
+      _Pragma("unroll") for (int r = 0; r < 4; ++r)                                            \
+          slab_[vcache_index(pos[J], w[i] * 16 + q4 * 4 + r, e.Tpad)] = f32_to_bf16(v[r] * rs[J]); \
+    }                                                                                        \
+  }
+  EC_QKV_LOADC(ca, 0)
+#pragma unroll
+  for (int j = 0; j < WTM; j += 2) {
+    if (j + 1 < WTM) { EC_QKV_LOADC(cb, j + 1) }
+    EC_QKV_STORE(ca, j)
+    if (j + 1 < WTM) {
+      if (j + 2 < WTM) { EC_QKV_LOADC(ca, j + 2) }
+      EC_QKV_STORE(cb, j + 1)
+    }
+  }
+#undef EC_QKV_LOADC
+#undef EC_QKV_STORE
 }
 
 // ---------------------------------------------------------------------------------------------
 // Epilogue of the tiled kernels: one wave's WTN x WTM accumulator tiles (weights x activations).
 // ---------------------------------------------------------------------------------------------
-template <int EPI, int WTM, int WTN>
+template <int EPI, int WTM, int WTN, bool PIPE = true>
 __device__ __forceinline__ void tiled_epilogue(const GemmEpi& e, f32x4 (&acc)[WTN][WTM],
                                                int mt_base, int nt_base, int total_nt, int lane,
                                                int kz) {
+  if constexpr (EPI == EPI_QKV && PIPE) {
+    tiled_epilogue_qkv<WTM, WTN>(e, acc, mt_base, nt_base, total_nt, lane);
+    return;
+  }
   const int q4 = lane >> 4;
+  // every row's 1/rms first: these loads must not be strung out between the stores below
+  float rsj[WTM];
+  if constexpr (EPI == EPI_SWIGLU || EPI == EPI_LOGITS || EPI == EPI_QKV) {
+#pragma unroll
+    for (int j = 0; j < WTM; ++j) {
+      const int m = (mt_base + j) * 16 + (lane & 15);
+      const int mm = m < e.M ? m : 0;
+      rsj[j] = rstd_of(e, (EPI == EPI_LOGITS && e.row_sel) ? e.row_sel[mm] : mm);
+    }
+  }
 #pragma unroll
   for (int j = 0; j < WTM; ++j) {
     const int m = (mt_base + j) * 16 + (lane & 15);
@@ -375,7 +494,7 @@ __device__ __forceinline__ void tiled_epilogue(const GemmEpi& e, f32x4 (&acc)[WT
       epi_add_sumsq(e, m, mvalid, part);
     } else if constexpr (EPI == EPI_LOGITS) {
       if (mvalid) {
-        float rs = rstd_of(e, e.row_sel ? e.row_sel[m] : m);
+        const float rs = rsj[j];
 #pragma unroll
         for (int i = 0; i < WTN; ++i) {
           int vt = nt_base + i;
@@ -396,13 +515,17 @@ __device__ __forceinline__ void tiled_epilogue(const GemmEpi& e, f32x4 (&acc)[WT
       }
     } else {
       if (mvalid) {
-        float rs = rstd_of(e, m);
+        const float rs = rsj[j];
 #pragma unroll
-        for (int i = 0; i < WTN; i += 2) {
+        for (int i = 0; i < WTN; ++i) {
           int vt = nt_base + i;
-          if (vt < total_nt) {
-            if constexpr (EPI == EPI_SWIGLU) epi_swiglu(e, m, vt >> 1, q4, acc[i][j], acc[i + 1][j], rs);
-            else epi_qkv(e, m, vt >> 1, q4, acc[i][j], acc[i + 1][j], rs);
+          if constexpr (EPI == EPI_SWIGLU && WTN % 2 == 0) {
+            if (i & 1) continue;
+            if (vt + 1 < total_nt) epi_swiglu2(e, m, vt, q4, acc[i][j], acc[i + 1][j], rs);
+            else if (vt < total_nt) epi_swiglu(e, m, vt, q4, acc[i][j], rs);
+          } else if (vt < total_nt) {
+            if constexpr (EPI == EPI_SWIGLU) epi_swiglu(e, m, vt, q4, acc[i][j], rs);
+            else epi_qkv(e, m, vt, q4, acc[i][j], rs);
           }
         }
       }
@@ -470,7 +593,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_tiled4_kernel(const u32x4* __re
       if (mt < MT) src[i] = Ap + (size_t)mt * 64 + lane;
     } else if (f < NF) {
       int nt = nt0 + (f - BMT);
-      if (nt < total_nt) { src[i] = Wp + (size_t)nt * KB_all * 64 + lane; stride[i] = 64; }
+      if (nt < total_nt) {
+        src[i] = Wp + packed_w_frag(nt, 0, KB_all, e.w_grp) * 64 + lane;
+        stride[i] = (size_t)e.w_grp * 64;
+      }
     }
     src[i] += (size_t)kb_first * stride[i];
   }
@@ -567,7 +693,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_tiled8_kernel(
       if (mt < MT) src[i] = Ap + (size_t)mt * 64 + lane;
     } else if (f < NF) {
       int nt = nt0 + (f - BMT);
-      if (nt < total_nt) { src[i] = Wp + (size_t)nt * KB_all * 64 + lane; stride[i] = 64; }
+      if (nt < total_nt) {
+        src[i] = Wp + packed_w_frag(nt, 0, KB_all, e.w_grp) * 64 + lane;
+        stride[i] = (size_t)e.w_grp * 64;
+      }
     }
     src[i] += (size_t)kb_first * stride[i];
   }
@@ -610,7 +739,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_tiled8_kernel(
   }
   wait_vmcnt<0>();  // drain the clamped tail loads before the LDS goes away
 
-  tiled_epilogue<EPI, WTM, WTN>(e, acc, mt0 + wm * WTM, nt0 + wn * WTN, total_nt, lane, blockIdx.z);
+  tiled_epilogue<EPI, WTM, WTN, false>(e, acc, mt0 + wm * WTM, nt0 + wn * WTN, total_nt, lane, blockIdx.z);
 }
 
 template <int EPI, int WM, int WN, int WTM, int WTN, int NSTAGE>

@@ -167,38 +167,40 @@ void launch_swiglu_f32(const float* gu, int M, int F, float* act, hipStream_t s)
 
 // ---------------------------------------------------------------------------------------------
 // One-time re-tiling of a bf16 matrix W[N,K] into 16x32 MFMA fragments (k_common.h).  A pure
-// permutation; one thread moves 8 consecutive k (16 bytes).  The destination tile of source
-// tile s:
-//   REPACK_PLAIN       s
-//   REPACK_ROPE_PAIRS  within each head of hd columns, tiles of the first half go to even
-//                      slots and their partners hd/2 columns later to the odd slot next to them
-//   REPACK_EVEN / ODD  2s / 2s+1 (two matrices interleaved tile by tile)
+// permutation; one thread moves 8 consecutive k (16 bytes).  Destination row of source row n
+// (before adding row0):
+//   REPACK_PLAIN        n
+//   REPACK_ROPE_HALVES  within each head of hd rows: row c < hd/2 goes to tile c/8, row c%8; its
+//                       rotary partner c + hd/2 to row 8 + c%8 of the same tile
+//   REPACK_LO8 / HI8    (n/8)*16 + n%8  /  (n/8)*16 + 8 + n%8  (two matrices, 8 rows each per tile)
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void repack_weight_kernel(const bf16_t* __restrict__ W, int N,
                                                             int K, bf16_t* __restrict__ Wp,
-                                                            int mode, int hd) {
+                                                            int mode, int hd, int grp, int row0) {
   size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;  // over N * K/8 groups of 8
   size_t total = (size_t)N * (K / 8);
   if (i >= total) return;
   int n = (int)(i / (K / 8));
   int k = (int)(i % (K / 8)) * 8;
-  int st = n >> 4, dt = st;
-  if (mode == REPACK_ROPE_PAIRS) {
-    int tph = hd >> 4, head = st / tph, w = st - head * tph, hh = tph >> 1;
-    dt = head * tph + (w < hh ? 2 * w : 2 * (w - hh) + 1);
-  } else if (mode == REPACK_EVEN) {
-    dt = 2 * st;
-  } else if (mode == REPACK_ODD) {
-    dt = 2 * st + 1;
+  int dn = n;
+  if (mode == REPACK_ROPE_HALVES) {
+    int head = n / hd, c = n - head * hd, half = hd >> 1;
+    int cc = c < half ? c : c - half;
+    dn = head * hd + (cc >> 3) * 16 + (c < half ? 0 : 8) + (cc & 7);
+  } else if (mode == REPACK_LO8) {
+    dn = (n >> 3) * 16 + (n & 7);
+  } else if (mode == REPACK_HI8) {
+    dn = (n >> 3) * 16 + 8 + (n & 7);
   }
   uint4 v = *(const uint4*)(W + (size_t)n * K + k);
-  *(uint4*)(Wp + packed_w_index(dt * 16 + (n & 15), k, K / 32)) = v;
+  *(uint4*)(Wp + packed_w_index(row0 + dn, k, K / 32, grp)) = v;
 }
 
-void launch_repack_weight(const bf16_t* W, int N, int K, bf16_t* Wp, int mode, int hd,
-                          hipStream_t s) {
+void launch_repack_weight(const bf16_t* W, int N, int K, bf16_t* Wp, int mode, int hd, int grp,
+                          int row0, hipStream_t s) {
   size_t total = (size_t)N * (K / 8);
-  repack_weight_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(W, N, K, Wp, mode, hd);
+  repack_weight_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(W, N, K, Wp, mode, hd, grp,
+                                                                       row0);
 }
 
 // packed cache of one layer -> row-major [T, Hkv*hd]
