@@ -48,7 +48,10 @@ struct Buffers {
   float* logits; float4* partials;
   // bf16 only: row sums of squares [2L+1][kSumSlots][sumsq_stride] (32.32 fixed point), packed matrices
   unsigned long long* sumsq; int sumsq_stride;
-  float* ksplit_part;  // [kMaxKSplit][T][d] partial products of K-split residual GEMMs
+  float* ksplit_part;  // [kMaxKSplit][T][d] partial products of K-split residual GEMMs; between
+                       // them, the key slices of the partial-step attention
+  size_t ksplit_floats;
+  int* attn_tickets;   // [256] arrival counters of the key slices, zero between launches
   std::vector<PackedLayer> pl; bf16_t* lm_head_p;
 };
 
@@ -87,11 +90,13 @@ void carve(Carver& c, const ec_model_cfg& m, const ec_decode_cfg& d, int P, Buff
   b.pl.clear();
   b.lm_head_p = nullptr;
   b.sumsq = nullptr;
-  b.ksplit_part = nullptr;
+  b.ksplit_part = nullptr; b.ksplit_floats = 0; b.attn_tickets = nullptr;
   b.sumsq_stride = (int)T16;
   if (m.dtype == EC_BF16) {
     b.sumsq = c.take<unsigned long long>((size_t)(2 * m.n_layers + 1) * kSumSlots * T16);
-    b.ksplit_part = c.take<float>((size_t)kMaxKSplit * T * m.d_model);
+    b.ksplit_floats = (size_t)kMaxKSplit * T * m.d_model;
+    b.ksplit_part = c.take<float>(b.ksplit_floats);
+    b.attn_tickets = c.take<int>(256);
     b.pl.resize(m.n_layers);
     for (int l = 0; l < m.n_layers; ++l) {
       PackedLayer& p = b.pl[l];
@@ -305,7 +310,8 @@ int forward_bf16(ec_ctx* c, int mode, int M, int n_mb) {
       e.w_grp = skinny_tiles_per_block(EPI_QKV, nqkv / 16);
       launch_gemm_bf16(EPI_QKV, u, M, b.pl[l].wqkv, nqkv, d, e, s); }
     { Scope p(c, EC_K_ATTN);
-      launch_attention_mfma(q, kc, vc, M, c->T, Tpad, m.n_heads, m.n_kv_heads, hd, attn, s); }
+      launch_attention_mfma(q, kc, vc, M, c->T, Tpad, m.n_heads, m.n_kv_heads, hd, attn,
+                            b.ksplit_part, b.ksplit_floats, b.attn_tickets, s); }
     { Scope p(c, EC_K_OPROJ);
       GemmEpi e{}; e.M = M; e.MT = MT; e.h = b.h; e.d = d; e.gain_next = G(c->mlp_norm[l]);
       e.a_next = u; e.sumsq_out = sums(2 * l + 1); e.sum_stride = b.sumsq_stride; e.partial = b.ksplit_part;
@@ -499,6 +505,7 @@ int ec_init(ec_ctx** out, const ec_model_cfg* model, const ec_weights* weights,
   if (c->m.dtype == EC_BF16) {
     size_t kvbytes = (size_t)L * 2 * kv_keys(EC_BF16, c->T) * c->m.n_kv_heads * c->m.head_dim * 2;
     e = hipMemsetAsync(c->b.kv, 0, kvbytes, c->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(c->b.attn_tickets, 0, 256 * sizeof(int), c->stream);
     if (e != hipSuccess) return bail(EC_ERR_HIP, std::string("hipMemsetAsync: ") + hipGetErrorString(e));
     const int d = c->m.d_model, F = c->m.d_ffn;
     const int nq = c->m.n_heads * c->m.head_dim, nkv = c->m.n_kv_heads * c->m.head_dim;

@@ -131,8 +131,11 @@ void launch_unpack_cache(const bf16_t* packed, int is_v, int T, int Tpad, int Hk
 void launch_gemm_bf16(int epi, const bf16_t* Ap, int M_src, const bf16_t* Wp, int N, int K,
                       const GemmEpi& e, hipStream_t s);
 // q row-major [M, Hq*hd]; packed caches of one layer; out packed bf16 (K = Hq*hd).
+// part / tickets: scratch for splitting the keys over blocks when there are few query rows
+// (part_floats floats; 256 counters, zero on entry and again on exit); null = never split.
 void launch_attention_mfma(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int M, int T,
-                           int Tpad, int Hq, int Hkv, int hd, bf16_t* out, hipStream_t s);
+                           int Tpad, int Hq, int Hkv, int hd, bf16_t* out, float* part,
+                           size_t part_floats, int* tickets, hipStream_t s);
 
 // decision
 int vocab_reduce_parts(int V);

@@ -96,11 +96,36 @@ __device__ __forceinline__ void attn_chunk_tile(const bf16x8 (&kf)[2][HB], const
 // LDS in wave order.  grid (kv heads, query tiles): blocks of one head are Hkv apart in launch
 // order, which for Hkv a multiple of 8 puts them on the same XCD, whose L2 then serves the
 // head's K/V to all its query tiles.
+//
+// gridDim.z > 1 also splits the keys over blocks (a compute unit can only pull so many bytes per
+// microsecond, and one head's K/V is too much for one): every block leaves its unnormalised
+// (m, l, O) in `part`, takes a ticket, and the block that draws the last ticket of its (head,
+// query tile) adds the pieces up in slice order - so the result does not depend on which block
+// that is - and stores the output.  Pieces and tickets go through agent-scope atomics, which are
+// write-through / uncached on this chip, so no cache write-back or invalidate is needed; nobody
+// waits for anybody, so the scheme cannot hang.
+struct AttnSplit {
+  float* part;    // [pairs][gridDim.z][HT*64*4 + 64*2] floats
+  int* tickets;   // [pairs], zero between launches (the last block of a pair resets its own)
+  int chunks_per_block;
+};
+
+__device__ __forceinline__ void st_agent(float* p, float a, float b) {
+  union { float f[2]; unsigned long long u; } c;
+  c.f[0] = a; c.f[1] = b;
+  __hip_atomic_store((unsigned long long*)p, c.u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2 ld_agent(const float* p) {
+  union { float f[2]; unsigned long long u; } c;
+  c.u = __hip_atomic_load((const unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return make_float2(c.f[0], c.f[1]);
+}
+
 template <int HD>
 __global__ __launch_bounds__(512) void attn_mfma_split_kernel(
     const bf16_t* __restrict__ q, const au32x4* __restrict__ kp, const au32x4* __restrict__ vp,
     int M, int T, int Tpad, int Hq, int Hkv, float scale_log2e, bf16_t* __restrict__ out,
-    int MT) {
+    int MT, AttnSplit sp) {
   constexpr int HB = HD / 32, HT = HD / 16, NW = 8;
   extern __shared__ float4 lds[];
   // scalar wave index: no MFMA may sit under a condition the compiler could treat as divergent
@@ -108,6 +133,9 @@ __global__ __launch_bounds__(512) void attn_mfma_split_kernel(
   const int kvh = blockIdx.x, G = Hq / Hkv, nQ = M * G;
   const int nchunks = (T + 31) >> 5, KB32 = Tpad >> 5;
   const int qcol = lane & 15, grp = lane >> 4;
+  // this block's chunks: [c_lo, c_hi), never empty
+  const int c_lo = blockIdx.z * sp.chunks_per_block;
+  const int c_hi = min(c_lo + sp.chunks_per_block, nchunks);
 
   // ---- Q fragments (B operand): lane (query qcol, group grp) holds 8 hd columns -------------
   const int qi = blockIdx.y * 16 + qcol;
@@ -127,14 +155,14 @@ __global__ __launch_bounds__(512) void attn_mfma_split_kernel(
 
   const au32x4* kbase = kp + (size_t)kvh * KB32 * 2 * HB * 64 + lane;
   const au32x4* vbase = vp + (size_t)kvh * HT * KB32 * 64 + lane;
-  // the wave's chunks are wave, wave + NW, ...: n_my of them.  Loads are unconditional (a chunk
-  // past the end re-reads the last one, which is in cache); a chunk past the end is computed
-  // with every key masked, which changes nothing once the wave has seen one real chunk.
-  const int n_my = wave < nchunks ? (nchunks - wave + NW - 1) / NW : 0;
+  // the wave's chunks are c_lo + wave, + NW, ...: n_my of them.  Loads are unconditional (a
+  // chunk past the end re-reads the last one, which is in cache); a chunk past the end is
+  // computed with every key masked, which changes nothing once the wave has seen one real chunk.
+  const int n_my = c_lo + wave < c_hi ? (c_hi - c_lo - wave + NW - 1) / NW : 0;
   bf16x8 kfa[2][HB], vfa[HT], kfb[2][HB], vfb[HT];
 #define EC_AT_LOAD(KF, VF, I)                                                               \
   {                                                                                         \
-    const int c_ = min(wave + NW * (I), nchunks - 1);                                       \
+    const int c_ = min(c_lo + wave + NW * (I), c_hi - 1);                                   \
     _Pragma("unroll") for (int t2 = 0; t2 < 2; ++t2)                                        \
       _Pragma("unroll") for (int hb = 0; hb < HB; ++hb)                                     \
         KF[t2][hb] = av4_as_bf16x8(kbase[((size_t)(c_ * 2 + t2) * HB + hb) * 64]);          \
@@ -143,7 +171,7 @@ __global__ __launch_bounds__(512) void attn_mfma_split_kernel(
   }
 #define EC_AT_COMPUTE(KF, VF, I)                                                            \
   {                                                                                         \
-    const int c_ = wave + NW * (I);                                                         \
+    const int c_ = c_lo + wave + NW * (I);                                                  \
     const bool real_ = (I) < n_my;                                                          \
     attn_chunk_tile<HB, HT>(KF, VF, qf, acc, m_run, l_run, scale_log2e, c_ * 32 + grp * 8,  \
                             real_ ? T : 0, !real_ || ((c_ == nchunks - 1) && (T & 31)));    \
@@ -176,7 +204,6 @@ __global__ __launch_bounds__(512) void attn_mfma_split_kernel(
     ((float2*)(slot + HT * 64))[lane] = make_float2(m_run, l_run);
   }
   __syncthreads();
-  if (!qvalid) return;
   float wgt[NW], m_all = -INFINITY, l_all = 0.f;
 #pragma unroll
   for (int w = 0; w < NW; ++w) {
@@ -190,7 +217,10 @@ __global__ __launch_bounds__(512) void attn_mfma_split_kernel(
     wgt[w] = ml.y > 0.f ? exp2f(wgt[w] - m_all) : 0.f;  // a wave without keys has weight 0
     l_all += ml.y * wgt[w];
   }
-  const float inv = 1.0f / l_all;
+  const int nz = gridDim.z;
+  const int pair = blockIdx.y * gridDim.x + blockIdx.x;
+  constexpr int PSLOT = HT * 256 + 128;  // floats per (pair, slice)
+  float* mine = sp.part + ((size_t)pair * nz + blockIdx.z) * PSLOT;
   for (int h = wave; h < HT; h += NW) {
     float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
@@ -198,7 +228,46 @@ __global__ __launch_bounds__(512) void attn_mfma_split_kernel(
       float4 v = lds[(size_t)w * SLOT + h * 64 + lane];
       o.x += v.x * wgt[w]; o.y += v.y * wgt[w]; o.z += v.z * wgt[w]; o.w += v.w * wgt[w];
     }
-    // lane holds hd rows h*16 + grp*4 .. +3 of query qcol
+    if (nz == 1) {
+      // lane holds hd rows h*16 + grp*4 .. +3 of query qcol
+      const float inv = 1.0f / l_all;
+      uint2 pk = make_uint2(pack2_bf16(o.x * inv, o.y * inv), pack2_bf16(o.z * inv, o.w * inv));
+      if (qvalid) *(uint2*)(out + packed_act_index(qrow, qhead * HD + h * 16 + grp * 4, MT)) = pk;
+    } else {
+      st_agent(mine + (h * 64 + lane) * 4, o.x, o.y);
+      st_agent(mine + (h * 64 + lane) * 4 + 2, o.z, o.w);
+    }
+  }
+  if (nz == 1) return;
+
+  // ---- cross-block: leave (m, l), draw a ticket, the last block of the pair finishes ---------
+  if (wave == 0) st_agent(mine + HT * 256 + lane * 2, m_all, l_all);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this thread's pieces have reached memory
+  __syncthreads();
+  int* flag = (int*)lds;  // the parked copies are no longer needed
+  if (threadIdx.x == 0) {
+    int old = __hip_atomic_fetch_add(sp.tickets + pair, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (old == nz - 1)
+      __hip_atomic_store(sp.tickets + pair, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *flag = (old == nz - 1);
+  }
+  __syncthreads();
+  if (*flag == 0 || !qvalid) return;
+  const float* base = sp.part + (size_t)pair * nz * PSLOT;
+  float m_fin = -INFINITY, l_fin = 0.f;
+  for (int z = 0; z < nz; ++z) m_fin = fmaxf(m_fin, ld_agent(base + (size_t)z * PSLOT + HT * 256 + lane * 2).x);
+  for (int h = wave; h < HT; h += NW) {
+    float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+    l_fin = 0.f;
+    for (int z = 0; z < nz; ++z) {
+      const float* pz = base + (size_t)z * PSLOT;
+      const float2 ml = ld_agent(pz + HT * 256 + lane * 2);
+      const float wz = ml.y > 0.f ? exp2f(ml.x - m_fin) : 0.f;
+      const float2 a = ld_agent(pz + (h * 64 + lane) * 4), b = ld_agent(pz + (h * 64 + lane) * 4 + 2);
+      l_fin += ml.y * wz;
+      o.x += a.x * wz; o.y += a.y * wz; o.z += b.x * wz; o.w += b.y * wz;
+    }
+    const float inv = 1.0f / l_fin;
     uint2 pk = make_uint2(pack2_bf16(o.x * inv, o.y * inv), pack2_bf16(o.z * inv, o.w * inv));
     *(uint2*)(out + packed_act_index(qrow, qhead * HD + h * 16 + grp * 4, MT)) = pk;
   }
@@ -313,7 +382,8 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_shared_kernel(
 
 template <int HD>
 static void launch_attn_mfma_hd(const bf16_t* q, const uint4* kp, const uint4* vp, int M, int T,
-                                int Tpad, int Hq, int Hkv, bf16_t* out, hipStream_t s) {
+                                int Tpad, int Hq, int Hkv, bf16_t* out, float* part,
+                                size_t part_floats, int* tickets, hipStream_t s) {
   const int G = Hq / Hkv, nQ = M * G, qtiles = (nQ + 15) / 16, MT = (M + 15) / 16;
   const float sc = 1.4426950408889634f / sqrtf((float)HD);
   if (qtiles * Hkv <= 256) {
@@ -326,8 +396,27 @@ static void launch_attn_mfma_hd(const bf16_t* q, const uint4* kp, const uint4* v
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
       attr_set = true;
     }
-    attn_mfma_split_kernel<HD><<<dim3(Hkv, qtiles), 512, smem, s>>>(
-        q, (const au32x4*)kp, (const au32x4*)vp, M, T, Tpad, Hq, Hkv, sc, out, MT);
+    // Key slices over blocks pay only for long contexts (the pieces go through write-through
+    // stores and a ticket, about 3 us): from 64 chunks on, two or more chunks per wave, and no
+    // more blocks than compute units.
+    const int nchunks = (T + 31) / 32, pairs = qtiles * Hkv;
+    constexpr size_t PSLOT = (HD / 16) * 256 + 128;
+    int nz = 1;
+    if (nchunks >= 64) {
+      nz = nchunks / 16;
+      if (nz > 256 / pairs) nz = 256 / pairs;
+      if (nz > 8) nz = 8;
+      if (nz < 1) nz = 1;
+    }
+    while (nz > 1 && (size_t)pairs * nz * PSLOT > part_floats) --nz;
+    if (!part || !tickets) nz = 1;
+    AttnSplit sp;
+    sp.part = part;
+    sp.tickets = tickets;
+    sp.chunks_per_block = (nchunks + nz - 1) / nz;
+    nz = (nchunks + sp.chunks_per_block - 1) / sp.chunks_per_block;  // no empty slice
+    attn_mfma_split_kernel<HD><<<dim3(Hkv, qtiles, nz), 512, smem, s>>>(
+        q, (const au32x4*)kp, (const au32x4*)vp, M, T, Tpad, Hq, Hkv, sc, out, MT, sp);
   } else {
     // two query tiles per wave halve the LDS reads per MFMA, but only pay once the grid still
     // covers the chip's 256 compute units
@@ -345,12 +434,15 @@ static void launch_attn_mfma_hd(const bf16_t* q, const uint4* kp, const uint4* v
 }
 
 void launch_attention_mfma(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int M, int T,
-                           int Tpad, int Hq, int Hkv, int hd, bf16_t* out, hipStream_t s) {
+                           int Tpad, int Hq, int Hkv, int hd, bf16_t* out, float* part,
+                           size_t part_floats, int* tickets, hipStream_t s) {
   if (M <= 0) return;
   if (hd == 64)
-    launch_attn_mfma_hd<64>(q, (const uint4*)kc, (const uint4*)vc, M, T, Tpad, Hq, Hkv, out, s);
+    launch_attn_mfma_hd<64>(q, (const uint4*)kc, (const uint4*)vc, M, T, Tpad, Hq, Hkv, out, part,
+                            part_floats, tickets, s);
   else
-    launch_attn_mfma_hd<128>(q, (const uint4*)kc, (const uint4*)vc, M, T, Tpad, Hq, Hkv, out, s);
+    launch_attn_mfma_hd<128>(q, (const uint4*)kc, (const uint4*)vc, M, T, Tpad, Hq, Hkv, out, part,
+                             part_floats, tickets, s);
 }
 
 }  // namespace ec

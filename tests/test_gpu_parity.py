@@ -51,6 +51,19 @@ def test_small_models_whole_generation(dtype, hq, hkv, hd, P, N, block, k, n, ta
     assert s["modes"][eco.PARTIAL] >= 1
 
 
+@pytest.mark.parametrize("hq,hkv,hd", [(4, 4, 64), (4, 2, 128)])
+def test_long_context_partial_steps(hq, hkv, hd):
+    """More than 2048 keys: the partial-step attention cuts the keys into slices that different
+    blocks reduce and the last one to finish adds up."""
+    cfg = small_cfg("bf16", hq, hkv, hd, d=hq * hd if hq * hd >= 256 else 256)
+    w = ec_inputs.make_weights(cfg, 11, gain_jitter=0.1)
+    dec = ec_inputs.DecodeCfg(gen_len=40, block=32, k_recent=3, tokens_per_step=2, tau=1e9)
+    prompt = ec_inputs.make_prompt(cfg.vocab, 2100, 5)
+    s = run_teacher_forced(cfg, w, dec, prompt, TOL["bf16"], max_steps=8)
+    print(s)
+    assert s["modes"][eco.PARTIAL] >= 6
+
+
 def test_free_running_generation_matches_oracle_f32():
     """Without forcing: the GPU's own decisions reproduce the oracle's generation (float32 model,
     margins far above 1e-4 at every step of this seed)."""
