@@ -23,7 +23,12 @@
  *    The context owns only small host-side state and one pinned host buffer.
  *  - All device work is enqueued on the HIP stream given to ec_init.  ec_step synchronises that
  *    stream once, for the read-back of its small result.
- *  - A context is not thread-safe.  batch must be 1.
+ *  - A context is not thread-safe.
+ *  - batch sequences generate side by side and independently (own prompt, mask set, history,
+ *    flag, block, cache): a step concatenates the rows each sequence recomputes, so the weights
+ *    stream once for all of them; the results equal those of running each sequence alone.
+ *    batch > 1 needs the bfloat16 path.  Per-sequence arguments and results are arrays of
+ *    batch entries in sequence order.
  *  - All matrices are row-major [out_features, in_features] in the model's storage type
  *    (float32 or bfloat16).  Norm gains are vectors of the same type.
  */
@@ -39,6 +44,7 @@ extern "C" {
 
 #define EC_MAX_N 32        /* most tokens one step may unmask (tokens_per_step <= EC_MAX_N)   */
 #define EC_MAX_BLOCK 128   /* largest block (window) size                                     */
+#define EC_MAX_BATCH 64    /* most sequences of one context                                   */
 
 typedef struct ec_ctx ec_ctx; /* opaque */
 
@@ -145,19 +151,21 @@ size_t ec_workspace_bytes(const ec_model_cfg *model, const ec_decode_cfg *decode
 /* Creates a context: validates the configuration, carves the workspace, uploads the prompt,
  * fills the generation slots with mask_id, clears the history (t = 1, flag = recompute).
  * No forward pass runs here; the first step is FULL (appendix algorithm, t == 1 branch).
- *  prompt_ids  HOST, concatenated prompts, prompt_lens[b] ids each, none equal to ... any id in
- *              [0, vocab) is accepted
+ *  prompt_ids  HOST, the batch's prompts one after the other, prompt_lens[b] ids each; any id
+ *              in [0, vocab) is accepted
  *  workspace   DEVICE, 256-byte aligned, >= ec_workspace_bytes(); BORROWED
  *  hip_stream  hipStream_t to enqueue on (NULL = the default stream)                          */
 int ec_init(ec_ctx **out, const ec_model_cfg *model, const ec_weights *weights,
             const ec_decode_cfg *decode, const int32_t *prompt_ids, const int32_t *prompt_lens,
             void *workspace, size_t workspace_bytes, void *hip_stream);
 
-/* Restarts the generation of an existing context with a new prompt of the SAME length. */
+/* Restarts the generation of an existing context with new prompts of the SAME lengths. */
 int ec_reset(ec_ctx *ctx, const int32_t *prompt_ids /*HOST*/);
 
-/* One denoising step (Algorithm 1 loop body).  mode = EC_AUTO follows the entropy flag;
- * EC_FULL / EC_PARTIAL override it.  out: HOST, one ec_step_result. */
+/* One denoising step (Algorithm 1 loop body) of every unfinished sequence.  mode = EC_AUTO
+ * follows each sequence's entropy flag; EC_FULL / EC_PARTIAL override it for all of them.
+ * out: HOST, batch ec_step_result; a sequence that had finished earlier reports done = 1 and
+ * zeros. */
 int ec_step(ec_ctx *ctx, int mode, ec_step_result *out);
 
 /* Teacher forcing: runs the forward pass and the vocabulary reduction in `mode`, reports the
@@ -165,9 +173,14 @@ int ec_step(ec_ctx *ctx, int mode, ec_step_result *out);
  * n may be 0) to x, the mask set and the history. */
 int ec_step_forced(ec_ctx *ctx, int mode, int32_t n, const int32_t *positions,
                    const int32_t *tokens, ec_step_result *out);
+/* The same for a batch: modes[b] and n[b] per sequence (entries of finished sequences are
+ * ignored), the pairs of all sequences one after the other in positions / tokens. */
+int ec_step_forced_batch(ec_ctx *ctx, const int32_t *modes, const int32_t *n,
+                         const int32_t *positions, const int32_t *tokens, ec_step_result *out);
 
-/* Runs EC_AUTO steps until no masked position is left (Algorithm 1).  out_tokens: HOST
- * [gen_len] final ids of the generation slots.  stats may be NULL. */
+/* Runs EC_AUTO steps until no masked position is left in any sequence (Algorithm 1).
+ * out_tokens: HOST [batch, gen_len] final ids of the generation slots.  stats may be NULL; its
+ * full_steps / partial_steps count sequence-steps. */
 int ec_generate(ec_ctx *ctx, int32_t *out_tokens, ec_gen_stats *stats);
 
 /* Per-kernel-class device timing with HIP events on the context's stream.  While enabled every
@@ -178,7 +191,8 @@ int ec_profile_read(ec_ctx *ctx, ec_profile *out);
 
 /* Copies internal state to the host (synchronises the stream).  bytes must not exceed the
  * size of the item; the copy is truncated to bytes. */
-int ec_debug_read(ec_ctx *ctx, int what, int layer, void *host_dst, size_t bytes);
+int ec_debug_read(ec_ctx *ctx, int what, int layer, void *host_dst, size_t bytes); /* sequence 0 */
+int ec_debug_read_seq(ec_ctx *ctx, int seq, int what, int layer, void *host_dst, size_t bytes);
 
 /* Frees host-side state only; never frees weights or workspace.  NULL is allowed. */
 void ec_destroy(ec_ctx *ctx);

@@ -14,6 +14,7 @@ LIB_PATH = os.path.join(HERE, "libec.so")
 
 EC_MAX_N = 32
 EC_MAX_BLOCK = 128
+EC_MAX_BATCH = 64
 EC_F32, EC_BF16 = 0, 1
 EC_FULL, EC_PARTIAL, EC_AUTO = 0, 1, 2
 EC_OK, EC_ERR_ARG, EC_ERR_CONFIG, EC_ERR_WORKSPACE, EC_ERR_STATE, EC_ERR_HIP = 0, -1, -2, -3, -4, -5
@@ -25,8 +26,8 @@ KERNEL_CLASS_NAMES = ["embed", "norm", "qkv", "rope_kv", "attn", "oproj", "gateu
  EC_DBG_ROW_STATS) = range(8)
 
 EXPORTS = ["ec_workspace_bytes", "ec_init", "ec_reset", "ec_step", "ec_step_forced",
-           "ec_generate", "ec_profile_enable", "ec_profile_read", "ec_debug_read", "ec_destroy",
-           "ec_strerror", "ec_last_error"]
+           "ec_step_forced_batch", "ec_generate", "ec_profile_enable", "ec_profile_read",
+           "ec_debug_read", "ec_debug_read_seq", "ec_destroy", "ec_strerror", "ec_last_error"]
 
 
 class ec_model_cfg(C.Structure):
@@ -99,6 +100,8 @@ def load_library() -> C.CDLL:
     lib.ec_step.argtypes = [vp, C.c_int, C.POINTER(ec_step_result)]
     lib.ec_step_forced.restype = C.c_int
     lib.ec_step_forced.argtypes = [vp, C.c_int, C.c_int32, i32p, i32p, C.POINTER(ec_step_result)]
+    lib.ec_step_forced_batch.restype = C.c_int
+    lib.ec_step_forced_batch.argtypes = [vp, i32p, i32p, i32p, i32p, C.POINTER(ec_step_result)]
     lib.ec_generate.restype = C.c_int
     lib.ec_generate.argtypes = [vp, i32p, C.POINTER(ec_gen_stats)]
     lib.ec_profile_enable.restype = C.c_int
@@ -107,6 +110,8 @@ def load_library() -> C.CDLL:
     lib.ec_profile_read.argtypes = [vp, C.POINTER(ec_profile)]
     lib.ec_debug_read.restype = C.c_int
     lib.ec_debug_read.argtypes = [vp, C.c_int, C.c_int, vp, C.c_size_t]
+    lib.ec_debug_read_seq.restype = C.c_int
+    lib.ec_debug_read_seq.argtypes = [vp, C.c_int, C.c_int, C.c_int, vp, C.c_size_t]
     lib.ec_destroy.restype = None
     lib.ec_destroy.argtypes = [vp]
     lib.ec_strerror.restype = C.c_char_p
@@ -158,15 +163,21 @@ def weights_to_device(cfg, w: Dict[str, object], device="cuda:0") -> Dict[str, o
 
 
 class EntropyCache:
-    """One context: holds the torch tensors the library borrows (weights, workspace)."""
+    """One context: holds the torch tensors the library borrows (weights, workspace).
+    With dec.batch > 1, `prompt` is a list of dec.batch prompts and the per-sequence results
+    come back as lists in sequence order."""
 
-    def __init__(self, cfg, dev_weights: Dict[str, object], dec, prompt: Sequence[int],
-                 stream=None):
+    def __init__(self, cfg, dev_weights: Dict[str, object], dec, prompt, stream=None):
         import torch
         self.lib = load_library()
         self.cfg, self.dec = cfg, dec
-        self.P, self.N = len(prompt), dec.gen_len
-        self.T = self.P + self.N
+        self.B = dec.batch
+        prompts = [list(prompt)] if self.B == 1 else [list(p) for p in prompt]
+        assert len(prompts) == self.B
+        self.Ps = [len(p) for p in prompts]
+        self.N = dec.gen_len
+        self.Ts = [p + self.N for p in self.Ps]
+        self.P, self.T = self.Ps[0], self.Ts[0]
         self._w = dev_weights  # keep alive
         self._mc, self._dc = model_cfg_struct(cfg), decode_cfg_struct(dec)
         L = cfg.n_layers
@@ -180,7 +191,7 @@ class EntropyCache:
             self._ptr_arrays[name] = arr
             setattr(ws, name, C.cast(arr, C.POINTER(C.c_void_p)))
         self._ws = ws
-        plen = _i32([self.P])
+        plen = _i32(self.Ps)
         need = self.lib.ec_workspace_bytes(C.byref(self._mc), C.byref(self._dc), _i32p(plen))
         if need == 0:
             # let ec_init produce the message
@@ -189,7 +200,7 @@ class EntropyCache:
         self._workspace = torch.empty(need, dtype=torch.uint8, device=dev_weights["tok_emb"].device)
         self._stream = stream if stream is not None else torch.cuda.current_stream()
         ctx = C.c_void_p()
-        pr = _i32(prompt)
+        pr = _i32([t for p in prompts for t in p])
         rc = self.lib.ec_init(C.byref(ctx), C.byref(self._mc), C.byref(self._ws),
                               C.byref(self._dc), _i32p(pr), _i32p(plen),
                               C.c_void_p(self._workspace.data_ptr()), need,
@@ -202,15 +213,26 @@ class EntropyCache:
         if rc != EC_OK:
             raise EcError(rc, self.lib.ec_last_error(self.ctx).decode())
 
-    def reset(self, prompt: Sequence[int]):
-        pr = _i32(prompt)
-        assert len(pr) == self.P
+    def reset(self, prompt):
+        prompts = [list(prompt)] if self.B == 1 else [list(p) for p in prompt]
+        assert [len(p) for p in prompts] == self.Ps
+        pr = _i32([t for p in prompts for t in p])
         self._check(self.lib.ec_reset(self.ctx, _i32p(pr)))
 
-    def step(self, mode: int = EC_AUTO) -> dict:
-        r = ec_step_result()
-        self._check(self.lib.ec_step(self.ctx, mode, C.byref(r)))
-        return r.as_dict()
+    def step(self, mode: int = EC_AUTO):
+        r = (ec_step_result * self.B)()
+        self._check(self.lib.ec_step(self.ctx, mode, r))
+        return r[0].as_dict() if self.B == 1 else [x.as_dict() for x in r]
+
+    def step_forced_batch(self, modes: Sequence[int], positions, tokens) -> List[dict]:
+        """positions / tokens: one list per sequence (ignored for finished sequences)."""
+        r = (ec_step_result * self.B)()
+        n = _i32([len(p) for p in positions])
+        p = _i32([v for q in positions for v in q] or [0])
+        t = _i32([v for q in tokens for v in q] or [0])
+        self._check(self.lib.ec_step_forced_batch(self.ctx, _i32p(_i32(modes)), _i32p(n), _i32p(p),
+                                                  _i32p(t), r))
+        return [x.as_dict() for x in r]
 
     def step_forced(self, mode: int, positions: Sequence[int], tokens: Sequence[int]) -> dict:
         r = ec_step_result()
@@ -219,11 +241,11 @@ class EntropyCache:
         return r.as_dict()
 
     def generate(self):
-        out = np.zeros(self.N, dtype=np.int32)
+        out = np.zeros(self.B * self.N, dtype=np.int32)
         st = ec_gen_stats()
         self._check(self.lib.ec_generate(self.ctx, _i32p(out), C.byref(st)))
         stats = {k: getattr(st, k) for k, _ in ec_gen_stats._fields_}
-        return out, stats
+        return (out if self.B == 1 else out.reshape(self.B, self.N)), stats
 
     def profile_enable(self, on: bool):
         self._check(self.lib.ec_profile_enable(self.ctx, int(on)))
@@ -235,19 +257,21 @@ class EntropyCache:
                 "ms": {n: p.ms[i] for i, n in enumerate(KERNEL_CLASS_NAMES)},
                 "launches": {n: p.launches[i] for i, n in enumerate(KERNEL_CLASS_NAMES)}}
 
-    def debug_read(self, what: int, layer: int = 0, count: Optional[int] = None) -> np.ndarray:
+    def debug_read(self, what: int, layer: int = 0, count: Optional[int] = None,
+                   seq: int = 0) -> np.ndarray:
         cfg = self.cfg
+        T = self.Ts[seq]
         kvw = cfg.n_kv_heads * cfg.head_dim
         if what == EC_DBG_LOGITS:
             n = self.dec.block if count is None else count
             out = np.empty((n, cfg.vocab), dtype=np.float32)
         elif what in (EC_DBG_KCACHE, EC_DBG_VCACHE):
-            out = np.empty((self.T, cfg.n_kv_heads, cfg.head_dim),
+            out = np.empty((T, cfg.n_kv_heads, cfg.head_dim),
                            dtype=np.uint16 if cfg.dtype == "bf16" else np.float32)
         elif what == EC_DBG_X:
-            out = np.empty(self.T, dtype=np.int32)
+            out = np.empty(T, dtype=np.int32)
         elif what == EC_DBG_MASKED:
-            out = np.empty(self.T, dtype=np.uint8)
+            out = np.empty(T, dtype=np.uint8)
         elif what == EC_DBG_HIST:
             out = np.empty(self.N, dtype=np.int32)
         elif what == EC_DBG_ROWS:
@@ -257,8 +281,8 @@ class EntropyCache:
             out = np.empty((n, 4), dtype=np.float32)
         else:
             raise ValueError("unknown debug item")
-        self._check(self.lib.ec_debug_read(self.ctx, what, layer, out.ctypes.data_as(C.c_void_p),
-                                           out.nbytes))
+        self._check(self.lib.ec_debug_read_seq(self.ctx, seq, what, layer,
+                                               out.ctypes.data_as(C.c_void_p), out.nbytes))
         return out
 
     def close(self):

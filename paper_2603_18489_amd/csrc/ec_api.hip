@@ -38,11 +38,15 @@ struct PackedLayer {
 };
 
 struct Buffers {
-  // sequence state
+  // sequence state, sequence after sequence: x / masked / rows_partial / prompt by positions,
+  // the others with the fixed stride named in DecideArgs
   int* x; uint8_t* masked; int* hist; DevState* st; int* mb_pos; int* rows_partial; int* mb_idx;
   float* row_stats; StepOut* out; int* forced_pos; int* forced_tok; int* prompt;
+  // the step's row list (bf16 path)
+  SeqDesc* seqs; int4* rowinfo; int4* tileinfo; int* lm_sel;
   float2* rope_cs;
-  char* kv;  // [L][2][T][Hkv*hd] storage type
+  char* kv;  // [L][2] planes; a plane holds every sequence's [Hkv][keys][hd] slabs, storage type
+  size_t kv_plane;  // elements per plane
   // activations
   float* h; void* u; float* qkv; void* q; void* attn; float* gu; void* act; void* u_lm;
   float* logits; float4* partials;
@@ -65,36 +69,71 @@ size_t packed_elems(int epi, size_t N, size_t K) {
   return (nt + g - 1) / g * g * 16 * K;
 }
 
-void carve(Carver& c, const ec_model_cfg& m, const ec_decode_cfg& d, int P, Buffers& b) {
-  const int T = P + d.gen_len, N = d.gen_len;
-  const size_t T16 = (size_t)(T + 15) / 16 * 16, B16 = (size_t)(d.block + 15) / 16 * 16;
+// Sizes that depend on the prompt lengths.
+struct Geometry {
+  int B = 0;
+  std::vector<int> P, T, tpad, x_off, kv_off;
+  size_t xtot = 0, ptot = 0;  // positions / prompt ids over all sequences
+  size_t kv_plane = 0;        // elements of one layer's K (or V) plane
+  size_t rmax = 0;            // most rows a step can have, with the padding of the row list
+  int tmax = 0;
+};
+
+// rows a sequence's segment of the row list takes
+int seg_rows_of(int n_rows) {
+  return n_rows > kSmallRows ? (n_rows + 255) / 256 * 256 : (n_rows + 15) / 16 * 16;
+}
+
+Geometry geometry(const ec_model_cfg& m, const ec_decode_cfg& d, const int32_t* prompt_lens) {
+  Geometry g;
+  g.B = d.batch;
+  const size_t nkv = (size_t)m.n_kv_heads * m.head_dim;
+  for (int b = 0; b < g.B; ++b) {
+    const int P = prompt_lens[b], T = P + d.gen_len;
+    g.P.push_back(P); g.T.push_back(T); g.tpad.push_back(kv_keys(m.dtype, T));
+    g.x_off.push_back((int)g.xtot); g.kv_off.push_back((int)g.kv_plane);
+    g.xtot += T; g.ptot += P;
+    g.kv_plane += (size_t)kv_keys(m.dtype, T) * nkv;
+    g.rmax += seg_rows_of(T);
+    g.tmax = T > g.tmax ? T : g.tmax;
+  }
+  return g;
+}
+
+void carve(Carver& c, const ec_model_cfg& m, const ec_decode_cfg& d, const Geometry& g,
+           Buffers& b) {
+  const int N = d.gen_len, B = g.B;
+  const size_t R = g.rmax, BL = (size_t)B * d.block, BL16 = (BL + 15) / 16 * 16;
   const size_t es = esize(m.dtype);
   const size_t nq = (size_t)m.n_heads * m.head_dim, nkv = (size_t)m.n_kv_heads * m.head_dim;
-  b.x = c.take<int>(T); b.masked = c.take<uint8_t>(T); b.hist = c.take<int>(N);
-  b.st = c.take<DevState>(1); b.mb_pos = c.take<int>(d.block); b.rows_partial = c.take<int>(T);
-  b.mb_idx = c.take<int>(d.block); b.row_stats = c.take<float>((size_t)d.block * 4);
-  b.out = c.take<StepOut>(1); b.forced_pos = c.take<int>(EC_MAX_N);
-  b.forced_tok = c.take<int>(EC_MAX_N); b.prompt = c.take<int>(P);
-  b.rope_cs = c.take<float2>((size_t)T * (m.head_dim / 2));
-  b.kv = c.take<char>((size_t)m.n_layers * 2 * kv_keys(m.dtype, T) * nkv * es);
-  b.h = c.take<float>((size_t)T * m.d_model);
-  b.u = c.take<char>(T16 * m.d_model * es);
-  b.qkv = c.take<float>((size_t)T * (nq + 2 * nkv));
-  b.q = c.take<char>(T16 * nq * es);
-  b.attn = c.take<char>(T16 * nq * es);
-  b.gu = c.take<float>((size_t)T * 2 * m.d_ffn);
-  b.act = c.take<char>(T16 * m.d_ffn * es);
-  b.u_lm = c.take<char>(B16 * m.d_model * es);
-  b.logits = c.take<float>((size_t)d.block * m.vocab);
-  b.partials = c.take<float4>((size_t)d.block * vocab_reduce_parts(m.vocab));
+  b.x = c.take<int>(g.xtot); b.masked = c.take<uint8_t>(g.xtot); b.hist = c.take<int>((size_t)B * N);
+  b.st = c.take<DevState>(B); b.mb_pos = c.take<int>(BL); b.rows_partial = c.take<int>(g.xtot);
+  b.mb_idx = c.take<int>(BL); b.row_stats = c.take<float>(BL * 4);
+  b.out = c.take<StepOut>(B); b.forced_pos = c.take<int>((size_t)B * EC_MAX_N);
+  b.forced_tok = c.take<int>((size_t)B * EC_MAX_N); b.prompt = c.take<int>(g.ptot);
+  b.seqs = c.take<SeqDesc>(B); b.rowinfo = c.take<int4>(R); b.tileinfo = c.take<int4>(R / 16);
+  b.lm_sel = c.take<int>(BL);
+  b.rope_cs = c.take<float2>((size_t)g.tmax * (m.head_dim / 2));
+  b.kv_plane = g.kv_plane;
+  b.kv = c.take<char>((size_t)m.n_layers * 2 * g.kv_plane * es);
+  b.h = c.take<float>(R * m.d_model);
+  b.u = c.take<char>(R * m.d_model * es);
+  b.qkv = c.take<float>(R * (nq + 2 * nkv));
+  b.q = c.take<char>(R * nq * es);
+  b.attn = c.take<char>(R * nq * es);
+  b.gu = c.take<float>(m.dtype == EC_F32 ? R * 2 * m.d_ffn : 1);
+  b.act = c.take<char>(R * m.d_ffn * es);
+  b.u_lm = c.take<char>(BL16 * m.d_model * es);
+  b.logits = c.take<float>(BL * m.vocab);
+  b.partials = c.take<float4>(BL * vocab_reduce_parts(m.vocab));
   b.pl.clear();
   b.lm_head_p = nullptr;
   b.sumsq = nullptr;
   b.ksplit_part = nullptr; b.ksplit_floats = 0; b.attn_tickets = nullptr;
-  b.sumsq_stride = (int)T16;
+  b.sumsq_stride = (int)R;
   if (m.dtype == EC_BF16) {
-    b.sumsq = c.take<unsigned long long>((size_t)(2 * m.n_layers + 1) * kSumSlots * T16);
-    b.ksplit_floats = (size_t)kMaxKSplit * T * m.d_model;
+    b.sumsq = c.take<unsigned long long>((size_t)(2 * m.n_layers + 1) * kSumSlots * R);
+    b.ksplit_floats = (size_t)kMaxKSplit * R * m.d_model;
     b.ksplit_part = c.take<float>(b.ksplit_floats);
     b.attn_tickets = c.take<int>(256);
     b.pl.resize(m.n_layers);
@@ -109,7 +148,7 @@ void carve(Carver& c, const ec_model_cfg& m, const ec_decode_cfg& d, int P, Buff
   }
 }
 
-const char* check_config(const ec_model_cfg* m, const ec_decode_cfg* d, int P) {
+const char* check_config(const ec_model_cfg* m, const ec_decode_cfg* d, const int32_t* prompt_lens) {
   if (m->dtype != EC_F32 && m->dtype != EC_BF16) return "dtype must be EC_F32 or EC_BF16";
   if (m->n_layers < 1 || m->d_model < 1 || m->n_heads < 1 || m->n_kv_heads < 1 || m->d_ffn < 1 ||
       m->vocab < 2)
@@ -124,15 +163,21 @@ const char* check_config(const ec_model_cfg* m, const ec_decode_cfg* d, int P) {
     if (m->d_model % 32 || m->d_ffn % 32 || m->vocab % 16)
       return "bf16 path: d_model, d_ffn must be multiples of 32 and vocab a multiple of 16";
   }
-  if (d->batch != 1) return "batch must be 1";
+  if (d->batch < 1 || d->batch > EC_MAX_BATCH) return "batch must be in [1, EC_MAX_BATCH]";
+  if (d->batch > 1 && m->dtype != EC_BF16) return "batch > 1 needs the bfloat16 path";
   if (d->gen_len < 1) return "gen_len must be positive";
   if (d->block < 1 || d->block > EC_MAX_BLOCK) return "block must be in [1, EC_MAX_BLOCK]";
   if (d->tokens_per_step < 1 || d->tokens_per_step > EC_MAX_N)
     return "tokens_per_step must be in [1, EC_MAX_N]";
   if (d->k_recent < 0) return "k_recent must be >= 0";
   if (!(d->tau == d->tau)) return "tau is NaN";
-  if (P < 0) return "negative prompt length";
-  if ((long)P + d->gen_len > 15000) return "context longer than 15000 positions";
+  long total = 0;
+  for (int b = 0; b < d->batch; ++b) {
+    if (prompt_lens[b] < 0) return "negative prompt length";
+    if ((long)prompt_lens[b] + d->gen_len > 15000) return "context longer than 15000 positions";
+    total += (long)prompt_lens[b] + d->gen_len + 256;
+  }
+  if (total > 200000) return "more than 200000 positions over the batch";
   return nullptr;
 }
 
@@ -145,14 +190,18 @@ struct ec_ctx {
   ec_decode_cfg d;
   ec_weights w;  // device pointers; per-layer arrays copied into the vectors below
   std::vector<const void*> attn_norm, wq, wk, wv, wo, mlp_norm, w_gate, w_up, w_down;
-  int P, N, T;
+  Geometry g;
+  int B, N;
   hipStream_t stream;
   Buffers b;
-  StepOut* host_out = nullptr;   // pinned
-  int* host_stage = nullptr;     // pinned: prompt / forced lists on their way to the device
-  // host mirror of the scalar state
-  int steps_run = 0, next_mode = EC_FULL, has_full = 0, done = 0, n_mb = 0, n_rows_partial = 0;
-  std::vector<uint8_t> masked_host;
+  StepOut* host_out = nullptr;   // pinned [B]
+  int* host_stage = nullptr;     // pinned: prompts / forced lists on their way to the device
+  SeqDesc* host_seqs = nullptr;  // pinned [B]
+  // host mirror of the scalar state, per sequence
+  int steps_run = 0;
+  std::vector<int> next_mode, has_full, done, n_mb, n_rows_partial;
+  int all_done = 0;
+  std::vector<uint8_t> masked_host;  // concatenated by x_off
   int64_t rows_recomputed = 0;
   int full_steps = 0, partial_steps = 0, tokens = 0;
   // profiling
@@ -207,44 +256,85 @@ void prof_collect(ec_ctx* c) {  // stream must be idle
 }
 
 char* kv_ptr(ec_ctx* c, int layer, int which) {
-  size_t row = (size_t)c->m.n_kv_heads * c->m.head_dim * esize(c->m.dtype);
-  return c->b.kv + ((size_t)layer * 2 + which) * kv_keys(c->m.dtype, c->T) * row;
+  return c->b.kv + ((size_t)layer * 2 + which) * c->b.kv_plane * esize(c->m.dtype);
 }
 
-int upload_and_init_state(ec_ctx* c, const int32_t* prompt_ids) {
-  if (c->P > 0) {
-    memcpy(c->host_stage, prompt_ids, (size_t)c->P * sizeof(int));
-    EC_HIP(c, hipMemcpyAsync(c->b.prompt, c->host_stage, (size_t)c->P * sizeof(int),
-                             hipMemcpyHostToDevice, c->stream));
-  }
-  launch_init_state(c->b.x, c->b.masked, c->b.hist, c->b.st, c->b.prompt, c->P, c->N,
-                    c->m.mask_id, c->stream);
-  DecideArgs a{};
-  a.init_only = 1; a.forced_n = -1;
+void fill_decide_args(ec_ctx* c, DecideArgs& a) {
+  a.seqs = c->b.seqs;
+  a.partials = c->b.partials; a.nparts = vocab_reduce_parts(c->m.vocab);
+  a.forced_pos = c->b.forced_pos; a.forced_tok = c->b.forced_tok;
   a.x = c->b.x; a.masked = c->b.masked; a.hist = c->b.hist; a.st = c->b.st;
   a.mb_pos = c->b.mb_pos; a.rows_partial = c->b.rows_partial; a.mb_idx = c->b.mb_idx;
   a.row_stats = c->b.row_stats; a.out = c->b.out;
-  a.P = c->P; a.N = c->N; a.T = c->T; a.block = c->d.block; a.k_recent = c->d.k_recent;
+  a.N = c->N; a.block = c->d.block; a.k_recent = c->d.k_recent;
   a.n_tok = c->d.tokens_per_step; a.tau = c->d.tau;
-  launch_decide(a, c->stream);
+}
+
+// static part of a sequence's descriptor
+SeqDesc base_desc(const ec_ctx* c, int b) {
+  SeqDesc sd{};
+  sd.P = c->g.P[b]; sd.T = c->g.T[b]; sd.tpad = c->g.tpad[b];
+  sd.x_off = c->g.x_off[b]; sd.kv_off = c->g.kv_off[b];
+  sd.mode = -1; sd.forced_n = -1;
+  return sd;
+}
+
+int upload_and_init_state(ec_ctx* c, const int32_t* prompt_ids) {
+  const int B = c->B;
+  if (c->g.ptot > 0) {
+    memcpy(c->host_stage, prompt_ids, c->g.ptot * sizeof(int));
+    EC_HIP(c, hipMemcpyAsync(c->b.prompt, c->host_stage, c->g.ptot * sizeof(int),
+                             hipMemcpyHostToDevice, c->stream));
+  }
+  size_t poff = 0;
+  for (int b = 0; b < B; ++b) {
+    launch_init_state(c->b.x + c->g.x_off[b], c->b.masked + c->g.x_off[b],
+                      c->b.hist + (size_t)b * c->N, c->b.st + b, c->b.prompt + poff, c->g.P[b],
+                      c->N, c->m.mask_id, c->stream);
+    poff += c->g.P[b];
+    c->host_seqs[b] = base_desc(c, b);
+    c->host_seqs[b].mode = EC_FULL;  // takes part in the list building below
+  }
+  EC_HIP(c, hipMemcpyAsync(c->b.seqs, c->host_seqs, (size_t)B * sizeof(SeqDesc),
+                           hipMemcpyHostToDevice, c->stream));
+  DecideArgs a{};
+  fill_decide_args(c, a);
+  a.init_only = 1;
+  launch_decide(a, B, c->stream);
   EC_HIP(c, hipGetLastError());
-  EC_HIP(c, hipMemcpyAsync(c->host_out, c->b.out, sizeof(StepOut), hipMemcpyDeviceToHost,
-                           c->stream));
+  EC_HIP(c, hipMemcpyAsync(c->host_out, c->b.out, (size_t)B * sizeof(StepOut),
+                           hipMemcpyDeviceToHost, c->stream));
   EC_HIP(c, hipStreamSynchronize(c->stream));
-  c->steps_run = 0; c->next_mode = EC_FULL; c->has_full = 0; c->done = 0;
-  c->n_mb = c->host_out->next_n_mb; c->n_rows_partial = c->host_out->next_n_rows_partial;
-  c->masked_host.assign(c->T, 0);
-  for (int i = c->P; i < c->T; ++i) c->masked_host[i] = 1;
+  c->steps_run = 0; c->all_done = 0;
+  c->next_mode.assign(B, EC_FULL); c->has_full.assign(B, 0); c->done.assign(B, 0);
+  c->n_mb.assign(B, 0); c->n_rows_partial.assign(B, 0);
+  c->masked_host.assign(c->g.xtot, 0);
+  for (int b = 0; b < B; ++b) {
+    c->n_mb[b] = c->host_out[b].next_n_mb;
+    c->n_rows_partial[b] = c->host_out[b].next_n_rows_partial;
+    for (int i = c->g.P[b]; i < c->g.T[b]; ++i) c->masked_host[c->g.x_off[b] + i] = 1;
+  }
   c->rows_recomputed = 0; c->full_steps = c->partial_steps = c->tokens = 0;
   return EC_OK;
 }
 
-// ---- the forward pass of one step over M rows -------------------------------------------------
+// What the host worked out for one step.
+struct StepPlan {
+  int R = 0, n_lm = 0;                      // rows of the list (with padding), masked block rows
+  bool has_small = false, has_large = false;
+  int max_T_small = 1;
+  bool single = false;                      // one sequence takes part: one_seq is its tile entry
+  int4 one_seq = make_int4(0, 0, 32, 0);
+  int64_t rows = 0;                         // sum of the sequences' own row counts
+  int n_full = 0, n_partial = 0;            // sequences running in each mode
+};
+
+// ---- the forward pass of one step (float32: batch 1, the sequence's M rows) --------------------
 int forward_f32(ec_ctx* c, int mode, int M, int n_mb) {
   const ec_model_cfg& m = c->m;
   Buffers& b = c->b;
   hipStream_t s = c->stream;
-  const int d = m.d_model, F = m.d_ffn, hd = m.head_dim;
+  const int d = m.d_model, F = m.d_ffn, hd = m.head_dim, T = c->g.T[0];
   const int nq = m.n_heads * hd, nkv = m.n_kv_heads * hd, nqkv = nq + 2 * nkv;
   const int* rows = (mode == EC_FULL) ? nullptr : b.rows_partial;
   const int* lm_sel = (mode == EC_FULL) ? b.mb_pos : b.mb_idx;
@@ -264,7 +354,7 @@ int forward_f32(ec_ctx* c, int mode, int M, int n_mb) {
     { Scope p(c, EC_K_ROPE_KV);
       launch_rope_scatter_f32(b.qkv, rows, M, m.n_heads, m.n_kv_heads, hd, b.rope_cs, q, kc, vc, s); }
     { Scope p(c, EC_K_ATTN);
-      launch_attention_f32(q, kc, vc, M, c->T, m.n_heads, m.n_kv_heads, hd, attn, s); }
+      launch_attention_f32(q, kc, vc, M, T, m.n_heads, m.n_kv_heads, hd, attn, s); }
     { Scope p(c, EC_K_OPROJ); launch_gemm_f32(attn, W(c->wo[l]), b.h, d, M, d, nq, 1, 1.f, s); }
     { Scope p(c, EC_K_NORM);
       launch_rmsnorm_f32(b.h, nullptr, M, d, W(c->mlp_norm[l]), m.rms_eps, u, s); }
@@ -282,145 +372,209 @@ int forward_f32(ec_ctx* c, int mode, int M, int n_mb) {
   return EC_OK;
 }
 
-// bf16: five launches per layer.  Norms, RoPE, the KV scatter, SwiGLU and the residual adds run
-// in the GEMM epilogues; `u` always holds the next GEMM's operand bf16(h * gain).
-int forward_bf16(ec_ctx* c, int mode, int M, int n_mb) {
+// bf16: the rows of all sequences in one list; five launches per layer.  Norms, RoPE, the KV
+// scatter, SwiGLU and the residual adds run in the GEMM epilogues; `u` always holds the next
+// GEMM's operand bf16(h * gain).
+int forward_bf16(ec_ctx* c, const StepPlan& sp) {
   const ec_model_cfg& m = c->m;
   Buffers& b = c->b;
   hipStream_t s = c->stream;
   const int d = m.d_model, F = m.d_ffn, hd = m.head_dim, L = m.n_layers;
   const int nq = m.n_heads * hd, nkv = m.n_kv_heads * hd, nqkv = nq + 2 * nkv;
-  const int Tpad = kv_keys(EC_BF16, c->T), MT = (M + 15) / 16;
-  const int* rows = (mode == EC_FULL) ? nullptr : b.rows_partial;
-  const int* lm_sel = (mode == EC_FULL) ? b.mb_pos : b.mb_idx;
+  // R rows in the list; the GEMMs work on M of them: all, or with a single sequence only its own
+  // rows (the tail of the last tile is padding: skipping it saves the activation reads)
+  const int R = sp.R, MT = (R + 15) / 16, M = sp.single ? (int)sp.rows : R;
   bf16_t* u = (bf16_t*)b.u; bf16_t* q = (bf16_t*)b.q; bf16_t* attn = (bf16_t*)b.attn;
   bf16_t* act = (bf16_t*)b.act;
   auto G = [](const void* p) { return (const bf16_t*)p; };
   auto sums = [&](int i) { return b.sumsq + (size_t)i * kSumSlots * b.sumsq_stride; };
 
   { Scope p(c, EC_K_EMBED);
-    launch_embed_bf16(G(c->w.tok_emb), b.x, rows, M, d, G(c->attn_norm[0]), b.h, u, b.sumsq,
-                      (2 * L + 1) * kSumSlots, b.sumsq_stride, s); }
+    StepLists sl{};
+    sl.seqs = b.seqs; sl.B = c->B; sl.R = R; sl.n_lm = sp.n_lm; sl.x = b.x;
+    sl.rows_partial = b.rows_partial; sl.mb_pos = b.mb_pos; sl.mb_idx = b.mb_idx;
+    sl.block = c->d.block; sl.rowinfo = b.rowinfo; sl.tileinfo = b.tileinfo; sl.lm_sel = b.lm_sel;
+    launch_step_prologue_bf16(sl, G(c->w.tok_emb), d, G(c->attn_norm[0]), b.h, u, b.sumsq,
+                              (2 * L + 1) * kSumSlots, b.sumsq_stride, s); }
   for (int l = 0; l < L; ++l) {
     bf16_t* kc = (bf16_t*)kv_ptr(c, l, 0); bf16_t* vc = (bf16_t*)kv_ptr(c, l, 1);
     { Scope p(c, EC_K_QKV);
-      GemmEpi e{}; e.M = M; e.MT = MT; e.sumsq_in = sums(2 * l); e.d_in = d; e.eps = m.rms_eps; e.sum_stride = b.sumsq_stride;
-      e.rows = rows; e.cs = b.rope_cs; e.Hq = m.n_heads; e.Hkv = m.n_kv_heads; e.hd = hd;
-      e.Tpad = Tpad; e.q_out = q; e.kc = kc; e.vc = vc;
+      GemmEpi e{}; e.M = M; e.MT = MT; e.sumsq_in = sums(2 * l); e.d_in = d; e.eps = m.rms_eps;
+      e.sum_stride = b.sumsq_stride; e.rowinfo = b.rowinfo; e.cs = b.rope_cs; e.Hq = m.n_heads;
+      e.Hkv = m.n_kv_heads; e.hd = hd; e.q_out = q; e.kc = kc; e.vc = vc;
       e.w_grp = skinny_tiles_per_block(EPI_QKV, nqkv / 16);
-      launch_gemm_bf16(EPI_QKV, u, M, b.pl[l].wqkv, nqkv, d, e, s); }
+      launch_gemm_bf16(EPI_QKV, u, R, b.pl[l].wqkv, nqkv, d, e, s); }
     { Scope p(c, EC_K_ATTN);
-      launch_attention_mfma(q, kc, vc, M, c->T, Tpad, m.n_heads, m.n_kv_heads, hd, attn,
-                            b.ksplit_part, b.ksplit_floats, b.attn_tickets, s); }
+      launch_attention_mfma(q, kc, vc, R, b.rowinfo, sp.single ? nullptr : b.tileinfo, sp.one_seq,
+                            sp.has_small, sp.has_large, sp.max_T_small, m.n_heads, m.n_kv_heads,
+                            hd, attn, b.ksplit_part, b.ksplit_floats, b.attn_tickets, s); }
     { Scope p(c, EC_K_OPROJ);
       GemmEpi e{}; e.M = M; e.MT = MT; e.h = b.h; e.d = d; e.gain_next = G(c->mlp_norm[l]);
-      e.a_next = u; e.sumsq_out = sums(2 * l + 1); e.sum_stride = b.sumsq_stride; e.partial = b.ksplit_part;
-      e.max_ksplit = kMaxKSplit;
+      e.a_next = u; e.sumsq_out = sums(2 * l + 1); e.sum_stride = b.sumsq_stride;
+      e.partial = b.ksplit_part; e.max_ksplit = kMaxKSplit;
       e.w_grp = skinny_tiles_per_block(EPI_RESID, d / 16);
-      launch_gemm_bf16(EPI_RESID, attn, M, b.pl[l].wo, d, nq, e, s); }
+      launch_gemm_bf16(EPI_RESID, attn, R, b.pl[l].wo, d, nq, e, s); }
     { Scope p(c, EC_K_GATEUP);
-      GemmEpi e{}; e.M = M; e.MT = MT; e.sumsq_in = sums(2 * l + 1); e.d_in = d; e.eps = m.rms_eps; e.sum_stride = b.sumsq_stride;
-      e.act = act;
+      GemmEpi e{}; e.M = M; e.MT = MT; e.sumsq_in = sums(2 * l + 1); e.d_in = d; e.eps = m.rms_eps;
+      e.sum_stride = b.sumsq_stride; e.act = act;
       e.w_grp = skinny_tiles_per_block(EPI_SWIGLU, 2 * F / 16);
-      launch_gemm_bf16(EPI_SWIGLU, u, M, b.pl[l].wgu, 2 * F, d, e, s); }
+      launch_gemm_bf16(EPI_SWIGLU, u, R, b.pl[l].wgu, 2 * F, d, e, s); }
     { Scope p(c, EC_K_DOWN);
       GemmEpi e{}; e.M = M; e.MT = MT; e.h = b.h; e.d = d;
       e.gain_next = G(l + 1 < L ? c->attn_norm[l + 1] : c->w.final_norm);
-      e.a_next = u; e.sumsq_out = sums(2 * l + 2); e.sum_stride = b.sumsq_stride; e.partial = b.ksplit_part;
-      e.max_ksplit = kMaxKSplit;
+      e.a_next = u; e.sumsq_out = sums(2 * l + 2); e.sum_stride = b.sumsq_stride;
+      e.partial = b.ksplit_part; e.max_ksplit = kMaxKSplit;
       e.w_grp = skinny_tiles_per_block(EPI_RESID, d / 16);
-      launch_gemm_bf16(EPI_RESID, act, M, b.pl[l].wd, d, F, e, s); }
+      launch_gemm_bf16(EPI_RESID, act, R, b.pl[l].wd, d, F, e, s); }
   }
-  // logits only for the block's masked rows: the LM head gathers them from `u`
+  // logits only for the blocks' masked rows: the LM head gathers them from `u`
   { Scope p(c, EC_K_LMHEAD);
-    GemmEpi e{}; e.M = n_mb; e.MT = (n_mb + 15) / 16; e.row_sel = lm_sel; e.sumsq_in = sums(2 * L);
-    e.d_in = d; e.eps = m.rms_eps; e.sum_stride = b.sumsq_stride; e.scale = m.logit_scale; e.logits = b.logits; e.ldc = m.vocab;
+    GemmEpi e{}; e.M = sp.n_lm; e.MT = (sp.n_lm + 15) / 16; e.row_sel = b.lm_sel;
+    e.sumsq_in = sums(2 * L); e.d_in = d; e.eps = m.rms_eps; e.sum_stride = b.sumsq_stride;
+    e.scale = m.logit_scale; e.logits = b.logits; e.ldc = m.vocab;
     e.w_grp = skinny_tiles_per_block(EPI_LOGITS, m.vocab / 16);
-    launch_gemm_bf16(EPI_LOGITS, u, M, b.lm_head_p, m.vocab, d, e, s); }
+    launch_gemm_bf16(EPI_LOGITS, u, R, b.lm_head_p, m.vocab, d, e, s); }
   return EC_OK;
 }
 
-int forward(ec_ctx* c, int mode, int M, int n_mb) {
-  int rc = (c->m.dtype == EC_F32) ? forward_f32(c, mode, M, n_mb) : forward_bf16(c, mode, M, n_mb);
-  if (rc != EC_OK) return rc;
-  { Scope p(c, EC_K_VOCAB_REDUCE);
-    launch_vocab_reduce(c->b.logits, n_mb, c->m.vocab, c->b.partials, c->stream); }
-  EC_HIP(c, hipGetLastError());
-  return EC_OK;
-}
-
-int run_step(ec_ctx* c, int mode, int forced_n, const int32_t* fpos, const int32_t* ftok,
-             ec_step_result* out) {
+// One step for every unfinished sequence.  modes: one entry per sequence or a single shared one
+// (modes_n == 1).  forced_n: NULL, or per sequence the number of (position, token) pairs to
+// commit, the pairs concatenated in fpos / ftok.
+int run_step(ec_ctx* c, const int32_t* modes, int modes_n, const int32_t* forced_n,
+             const int32_t* fpos, const int32_t* ftok, ec_step_result* out) {
   if (!c) return fail(nullptr, EC_ERR_ARG, "ctx is NULL");
   if (!out) return fail(c, EC_ERR_ARG, "out is NULL");
-  if (mode != EC_FULL && mode != EC_PARTIAL && mode != EC_AUTO)
-    return fail(c, EC_ERR_ARG, "mode must be EC_FULL, EC_PARTIAL or EC_AUTO");
-  if (c->done) return fail(c, EC_ERR_STATE, "generation is finished: no masked position left");
-  if (mode == EC_AUTO) mode = (c->steps_run == 0) ? EC_FULL : c->next_mode;
-  if (mode == EC_PARTIAL && !c->has_full)
-    return fail(c, EC_ERR_STATE, "PARTIAL step before any FULL step: the KV cache is empty");
-  if (forced_n >= 0) {
-    if (forced_n > EC_MAX_N) return fail(c, EC_ERR_ARG, "more than EC_MAX_N forced tokens");
-    if (forced_n > 0 && (!fpos || !ftok)) return fail(c, EC_ERR_ARG, "forced lists are NULL");
-    for (int i = 0; i < forced_n; ++i) {
-      if (fpos[i] < c->P || fpos[i] >= c->T || !c->masked_host[fpos[i]])
-        return fail(c, EC_ERR_ARG, "forced position is not a masked generation slot");
-      if (ftok[i] < 0 || ftok[i] >= c->m.vocab)
-        return fail(c, EC_ERR_ARG, "forced token outside the vocabulary");
-      for (int j = 0; j < i; ++j)
-        if (fpos[j] == fpos[i]) return fail(c, EC_ERR_ARG, "forced position listed twice");
-    }
-    if (forced_n > 0) {
-      memcpy(c->host_stage, fpos, forced_n * sizeof(int));
-      memcpy(c->host_stage + EC_MAX_N, ftok, forced_n * sizeof(int));
-      EC_HIP(c, hipMemcpyAsync(c->b.forced_pos, c->host_stage, forced_n * sizeof(int),
-                               hipMemcpyHostToDevice, c->stream));
-      EC_HIP(c, hipMemcpyAsync(c->b.forced_tok, c->host_stage + EC_MAX_N, forced_n * sizeof(int),
-                               hipMemcpyHostToDevice, c->stream));
+  if (!modes) return fail(c, EC_ERR_ARG, "modes is NULL");
+  if (c->all_done) return fail(c, EC_ERR_STATE, "generation is finished: no masked position left");
+  const int B = c->B;
+  // ---- validate, resolve the modes -------------------------------------------------------------
+  std::vector<int> mode(B, -1);
+  size_t foff = 0;
+  for (int b = 0; b < B; ++b) {
+    int mb = modes[modes_n == 1 ? 0 : b];
+    if (mb != EC_FULL && mb != EC_PARTIAL && mb != EC_AUTO)
+      return fail(c, EC_ERR_ARG, "mode must be EC_FULL, EC_PARTIAL or EC_AUTO");
+    const int fn = forced_n ? forced_n[b] : -1;
+    if (forced_n && fn < 0) return fail(c, EC_ERR_ARG, "n must be >= 0");
+    if (c->done[b]) { foff += fn > 0 ? fn : 0; continue; }
+    if (mb == EC_AUTO) mb = (c->steps_run == 0) ? EC_FULL : c->next_mode[b];
+    if (mb == EC_PARTIAL && !c->has_full[b])
+      return fail(c, EC_ERR_STATE, "PARTIAL step before any FULL step: the KV cache is empty");
+    mode[b] = mb;
+    if (fn >= 0) {
+      if (fn > EC_MAX_N) return fail(c, EC_ERR_ARG, "more than EC_MAX_N forced tokens");
+      if (fn > 0 && (!fpos || !ftok)) return fail(c, EC_ERR_ARG, "forced lists are NULL");
+      for (int i = 0; i < fn; ++i) {
+        const int p = fpos[foff + i];
+        if (p < c->g.P[b] || p >= c->g.T[b] || !c->masked_host[c->g.x_off[b] + p])
+          return fail(c, EC_ERR_ARG, "forced position is not a masked generation slot");
+        if (ftok[foff + i] < 0 || ftok[foff + i] >= c->m.vocab)
+          return fail(c, EC_ERR_ARG, "forced token outside the vocabulary");
+        for (int j = 0; j < i; ++j)
+          if (fpos[foff + j] == p) return fail(c, EC_ERR_ARG, "forced position listed twice");
+      }
+      foff += fn;
     }
   }
-  const int M = (mode == EC_FULL) ? c->T : c->n_rows_partial;
-  const int n_mb = c->n_mb;
-  int rc = forward(c, mode, M, n_mb);
+  // ---- the step's row list: many-row sequences first -------------------------------------------
+  StepPlan sp;
+  for (int pass = 0; pass < 2; ++pass) {
+    foff = 0;
+    for (int b = 0; b < B; ++b) {
+      const int fn = forced_n ? forced_n[b] : -1;
+      const size_t f0 = foff;
+      foff += fn > 0 ? fn : 0;
+      if (pass == 0) c->host_seqs[b] = base_desc(c, b);
+      if (mode[b] < 0) continue;
+      const int n_rows = mode[b] == EC_FULL ? c->g.T[b] : c->n_rows_partial[b];
+      const bool large = n_rows > kSmallRows;
+      if (large != (pass == 0)) continue;
+      SeqDesc& sd = c->host_seqs[b];
+      sd.mode = mode[b]; sd.n_rows = n_rows; sd.row0 = sp.R; sd.seg_rows = seg_rows_of(n_rows);
+      sd.n_mb = c->n_mb[b]; sd.forced_n = fn;
+      sp.R += sd.seg_rows; sp.rows += n_rows;
+      (large ? sp.has_large : sp.has_small) = true;
+      if (!large && c->g.T[b] > sp.max_T_small) sp.max_T_small = c->g.T[b];
+      (mode[b] == EC_FULL ? sp.n_full : sp.n_partial) += 1;
+      if (fn > 0) {
+        memcpy(c->host_stage + (size_t)b * EC_MAX_N, fpos + f0, fn * sizeof(int));
+        memcpy(c->host_stage + (size_t)(B + b) * EC_MAX_N, ftok + f0, fn * sizeof(int));
+      }
+    }
+  }
+  for (int b = 0; b < B; ++b)
+    if (mode[b] >= 0) {
+      SeqDesc& sd = c->host_seqs[b];
+      sd.lm0 = sp.n_lm;
+      sp.n_lm += c->n_mb[b];
+      sp.one_seq = make_int4(sd.kv_off, sd.T, sd.tpad, sd.n_rows > kSmallRows ? 1 : 0);
+    }
+  sp.single = sp.n_full + sp.n_partial == 1;
+  EC_HIP(c, hipMemcpyAsync(c->b.seqs, c->host_seqs, (size_t)B * sizeof(SeqDesc),
+                           hipMemcpyHostToDevice, c->stream));
+  if (forced_n) {
+    EC_HIP(c, hipMemcpyAsync(c->b.forced_pos, c->host_stage, (size_t)B * EC_MAX_N * sizeof(int),
+                             hipMemcpyHostToDevice, c->stream));
+    EC_HIP(c, hipMemcpyAsync(c->b.forced_tok, c->host_stage + (size_t)B * EC_MAX_N,
+                             (size_t)B * EC_MAX_N * sizeof(int), hipMemcpyHostToDevice, c->stream));
+  }
+  // ---- forward, vocabulary reduction, decision ---------------------------------------------------
+  int rc = (c->m.dtype == EC_F32) ? forward_f32(c, mode[0], c->host_seqs[0].n_rows, c->n_mb[0])
+                                  : forward_bf16(c, sp);
   if (rc != EC_OK) return rc;
-
-  DecideArgs a{};
-  a.partials = c->b.partials; a.nparts = vocab_reduce_parts(c->m.vocab); a.n_mb = n_mb;
-  a.mode_run = mode; a.n_rows_run = M; a.forced_n = forced_n;
-  a.forced_pos = c->b.forced_pos; a.forced_tok = c->b.forced_tok; a.init_only = 0;
-  a.x = c->b.x; a.masked = c->b.masked; a.hist = c->b.hist; a.st = c->b.st;
-  a.mb_pos = c->b.mb_pos; a.rows_partial = c->b.rows_partial; a.mb_idx = c->b.mb_idx;
-  a.row_stats = c->b.row_stats; a.out = c->b.out;
-  a.P = c->P; a.N = c->N; a.T = c->T; a.block = c->d.block; a.k_recent = c->d.k_recent;
-  a.n_tok = c->d.tokens_per_step; a.tau = c->d.tau;
-  { Scope p(c, EC_K_DECIDE); launch_decide(a, c->stream); }
+  { Scope p(c, EC_K_VOCAB_REDUCE);
+    launch_vocab_reduce(c->b.logits, sp.n_lm, c->m.vocab, c->b.partials, c->stream); }
   EC_HIP(c, hipGetLastError());
-  EC_HIP(c, hipMemcpyAsync(c->host_out, c->b.out, sizeof(StepOut), hipMemcpyDeviceToHost,
-                           c->stream));
+  DecideArgs a{};
+  fill_decide_args(c, a);
+  { Scope p(c, EC_K_DECIDE); launch_decide(a, B, c->stream); }
+  EC_HIP(c, hipGetLastError());
+  EC_HIP(c, hipMemcpyAsync(c->host_out, c->b.out, (size_t)B * sizeof(StepOut),
+                           hipMemcpyDeviceToHost, c->stream));
   EC_HIP(c, hipStreamSynchronize(c->stream));
   if (c->prof_on) prof_collect(c);
 
-  const StepOut& o = *c->host_out;
+  // ---- mirror the new state ------------------------------------------------------------------------
   c->steps_run += 1;
-  c->has_full |= (mode == EC_FULL);
-  c->done = o.r.done;
-  c->n_mb = o.next_n_mb;
-  c->n_rows_partial = o.next_n_rows_partial;
-  c->rows_recomputed += M;
-  (mode == EC_FULL ? c->full_steps : c->partial_steps) += 1;
-  if (forced_n >= 0) {
-    for (int i = 0; i < forced_n; ++i) c->masked_host[fpos[i]] = 0;
-    c->tokens += forced_n;
-    // the flag follows the committed tokens; the device computed it, mirror it from the state
-    DevState st;
-    EC_HIP(c, hipMemcpy(&st, c->b.st, sizeof(st), hipMemcpyDeviceToHost));
-    c->next_mode = st.skip ? EC_PARTIAL : EC_FULL;
-  } else {
-    for (int i = 0; i < o.r.n_unmasked; ++i) c->masked_host[o.r.positions[i]] = 0;
-    c->tokens += o.r.n_unmasked;
-    c->next_mode = o.r.next_mode;
+  c->rows_recomputed += sp.rows;
+  c->full_steps += sp.n_full;
+  c->partial_steps += sp.n_partial;
+  std::vector<DevState> st;
+  if (forced_n) {
+    // the flags follow the committed tokens; the device computed them, mirror them from its state
+    st.resize(B);
+    EC_HIP(c, hipMemcpy(st.data(), c->b.st, (size_t)B * sizeof(DevState), hipMemcpyDeviceToHost));
   }
-  *out = o.r;
+  int all_done = 1;
+  foff = 0;
+  for (int b = 0; b < B; ++b) {
+    const int fn = forced_n ? forced_n[b] : -1;
+    const size_t f0 = foff;
+    foff += fn > 0 ? fn : 0;
+    if (mode[b] < 0) {  // finished before this step
+      memset(&out[b], 0, sizeof(ec_step_result));
+      out[b].done = 1;
+      continue;
+    }
+    const StepOut& o = c->host_out[b];
+    c->has_full[b] |= (mode[b] == EC_FULL);
+    c->done[b] = o.r.done;
+    c->n_mb[b] = o.next_n_mb;
+    c->n_rows_partial[b] = o.next_n_rows_partial;
+    uint8_t* mh = c->masked_host.data() + c->g.x_off[b];
+    if (fn >= 0) {
+      for (int i = 0; i < fn; ++i) mh[fpos[f0 + i]] = 0;
+      c->tokens += fn;
+      c->next_mode[b] = st[b].skip ? EC_PARTIAL : EC_FULL;
+    } else {
+      for (int i = 0; i < o.r.n_unmasked; ++i) mh[o.r.positions[i]] = 0;
+      c->tokens += o.r.n_unmasked;
+      c->next_mode[b] = o.r.next_mode;
+    }
+    out[b] = o.r;
+    all_done &= c->done[b];
+  }
+  c->all_done = all_done;
   return EC_OK;
 }
 
@@ -434,10 +588,11 @@ extern "C" {
 size_t ec_workspace_bytes(const ec_model_cfg* model, const ec_decode_cfg* decode,
                           const int32_t* prompt_lens) {
   if (!model || !decode || !prompt_lens) return 0;
-  if (check_config(model, decode, prompt_lens[0]) != nullptr) return 0;
+  if (decode->batch < 1 || decode->batch > EC_MAX_BATCH) return 0;
+  if (check_config(model, decode, prompt_lens) != nullptr) return 0;
   Carver c(nullptr);
   Buffers b;
-  carve(c, *model, *decode, prompt_lens[0], b);
+  carve(c, *model, *decode, geometry(*model, *decode, prompt_lens), b);
   return c.off;
 }
 
@@ -448,10 +603,13 @@ int ec_init(ec_ctx** out, const ec_model_cfg* model, const ec_weights* weights,
   *out = nullptr;
   if (!model || !weights || !decode || !prompt_lens)
     return fail(nullptr, EC_ERR_ARG, "model, weights, decode and prompt_lens must not be NULL");
-  const int P = prompt_lens[0];
-  if (const char* msg = check_config(model, decode, P)) return fail(nullptr, EC_ERR_CONFIG, msg);
-  if (P > 0 && !prompt_ids) return fail(nullptr, EC_ERR_ARG, "prompt_ids is NULL");
-  for (int i = 0; i < P; ++i)
+  if (decode->batch < 1 || decode->batch > EC_MAX_BATCH)
+    return fail(nullptr, EC_ERR_CONFIG, "batch must be in [1, EC_MAX_BATCH]");
+  if (const char* msg = check_config(model, decode, prompt_lens))
+    return fail(nullptr, EC_ERR_CONFIG, msg);
+  Geometry g = geometry(*model, *decode, prompt_lens);
+  if (g.ptot > 0 && !prompt_ids) return fail(nullptr, EC_ERR_ARG, "prompt_ids is NULL");
+  for (size_t i = 0; i < g.ptot; ++i)
     if (prompt_ids[i] < 0 || prompt_ids[i] >= model->vocab)
       return fail(nullptr, EC_ERR_ARG, "prompt id outside the vocabulary");
   if (!weights->tok_emb || !weights->lm_head || !weights->final_norm || !weights->attn_norm ||
@@ -475,7 +633,7 @@ int ec_init(ec_ctx** out, const ec_model_cfg* model, const ec_weights* weights,
   ec_ctx* c = new (std::nothrow) ec_ctx();
   if (!c) return fail(nullptr, EC_ERR_ARG, "out of host memory");
   c->m = *model; c->d = *decode; c->w = *weights;
-  const int L = model->n_layers;
+  const int L = model->n_layers, B = decode->batch;
   c->attn_norm.assign(weights->attn_norm, weights->attn_norm + L);
   c->wq.assign(weights->wq, weights->wq + L); c->wk.assign(weights->wk, weights->wk + L);
   c->wv.assign(weights->wv, weights->wv + L); c->wo.assign(weights->wo, weights->wo + L);
@@ -483,48 +641,51 @@ int ec_init(ec_ctx** out, const ec_model_cfg* model, const ec_weights* weights,
   c->w_gate.assign(weights->w_gate, weights->w_gate + L);
   c->w_up.assign(weights->w_up, weights->w_up + L);
   c->w_down.assign(weights->w_down, weights->w_down + L);
-  c->P = P; c->N = decode->gen_len; c->T = P + decode->gen_len;
+  c->g = g; c->B = B; c->N = decode->gen_len;
   c->stream = (hipStream_t)hip_stream;
   Carver cv(workspace);
-  carve(cv, c->m, c->d, P, c->b);
+  carve(cv, c->m, c->d, c->g, c->b);
 
   auto bail = [&](int code, const std::string& msg) {
     if (c->host_out) (void)hipHostFree(c->host_out);
     if (c->host_stage) (void)hipHostFree(c->host_stage);
+    if (c->host_seqs) (void)hipHostFree(c->host_seqs);
     delete c;
     return fail(nullptr, code, msg);
   };
-  hipError_t e = hipHostMalloc((void**)&c->host_out, sizeof(StepOut), hipHostMallocDefault);
+  hipError_t e = hipHostMalloc((void**)&c->host_out, (size_t)B * sizeof(StepOut), hipHostMallocDefault);
   if (e != hipSuccess) return bail(EC_ERR_HIP, std::string("hipHostMalloc: ") + hipGetErrorString(e));
-  size_t stage = (size_t)(P > 2 * EC_MAX_N ? P : 2 * EC_MAX_N) * sizeof(int);
+  size_t stage = (g.ptot > (size_t)2 * B * EC_MAX_N ? g.ptot : (size_t)2 * B * EC_MAX_N) * sizeof(int);
   e = hipHostMalloc((void**)&c->host_stage, stage, hipHostMallocDefault);
+  if (e != hipSuccess) return bail(EC_ERR_HIP, std::string("hipHostMalloc: ") + hipGetErrorString(e));
+  e = hipHostMalloc((void**)&c->host_seqs, (size_t)B * sizeof(SeqDesc), hipHostMallocDefault);
   if (e != hipSuccess) return bail(EC_ERR_HIP, std::string("hipHostMalloc: ") + hipGetErrorString(e));
 
   // one-time device set-up: RoPE table, re-tiled bf16 matrices, finite padding keys
-  launch_rope_table(c->b.rope_cs, c->T, c->m.head_dim, c->m.rope_base, c->stream);
+  launch_rope_table(c->b.rope_cs, g.tmax, c->m.head_dim, c->m.rope_base, c->stream);
   if (c->m.dtype == EC_BF16) {
-    size_t kvbytes = (size_t)L * 2 * kv_keys(EC_BF16, c->T) * c->m.n_kv_heads * c->m.head_dim * 2;
+    size_t kvbytes = (size_t)L * 2 * c->b.kv_plane * 2;
     e = hipMemsetAsync(c->b.kv, 0, kvbytes, c->stream);
     if (e == hipSuccess) e = hipMemsetAsync(c->b.attn_tickets, 0, 256 * sizeof(int), c->stream);
     if (e != hipSuccess) return bail(EC_ERR_HIP, std::string("hipMemsetAsync: ") + hipGetErrorString(e));
     const int d = c->m.d_model, F = c->m.d_ffn;
     const int nq = c->m.n_heads * c->m.head_dim, nkv = c->m.n_kv_heads * c->m.head_dim;
     const int hd = c->m.head_dim;
-    auto B = [](const void* p) { return (const bf16_t*)p; };
+    auto Bp = [](const void* p) { return (const bf16_t*)p; };
     for (int l = 0; l < L; ++l) {
       PackedLayer& p = c->b.pl[l];
       const int gq = skinny_tiles_per_block(EPI_QKV, (nq + 2 * nkv) / 16);
       const int go = skinny_tiles_per_block(EPI_RESID, d / 16);
       const int gg = skinny_tiles_per_block(EPI_SWIGLU, 2 * F / 16);
-      launch_repack_weight(B(c->wq[l]), nq, d, p.wqkv, REPACK_ROPE_HALVES, hd, gq, 0, c->stream);
-      launch_repack_weight(B(c->wk[l]), nkv, d, p.wqkv, REPACK_ROPE_HALVES, hd, gq, nq, c->stream);
-      launch_repack_weight(B(c->wv[l]), nkv, d, p.wqkv, REPACK_PLAIN, hd, gq, nq + nkv, c->stream);
-      launch_repack_weight(B(c->wo[l]), d, nq, p.wo, REPACK_PLAIN, hd, go, 0, c->stream);
-      launch_repack_weight(B(c->w_gate[l]), F, d, p.wgu, REPACK_LO8, hd, gg, 0, c->stream);
-      launch_repack_weight(B(c->w_up[l]), F, d, p.wgu, REPACK_HI8, hd, gg, 0, c->stream);
-      launch_repack_weight(B(c->w_down[l]), d, F, p.wd, REPACK_PLAIN, hd, go, 0, c->stream);
+      launch_repack_weight(Bp(c->wq[l]), nq, d, p.wqkv, REPACK_ROPE_HALVES, hd, gq, 0, c->stream);
+      launch_repack_weight(Bp(c->wk[l]), nkv, d, p.wqkv, REPACK_ROPE_HALVES, hd, gq, nq, c->stream);
+      launch_repack_weight(Bp(c->wv[l]), nkv, d, p.wqkv, REPACK_PLAIN, hd, gq, nq + nkv, c->stream);
+      launch_repack_weight(Bp(c->wo[l]), d, nq, p.wo, REPACK_PLAIN, hd, go, 0, c->stream);
+      launch_repack_weight(Bp(c->w_gate[l]), F, d, p.wgu, REPACK_LO8, hd, gg, 0, c->stream);
+      launch_repack_weight(Bp(c->w_up[l]), F, d, p.wgu, REPACK_HI8, hd, gg, 0, c->stream);
+      launch_repack_weight(Bp(c->w_down[l]), d, F, p.wd, REPACK_PLAIN, hd, go, 0, c->stream);
     }
-    launch_repack_weight(B(c->w.lm_head), c->m.vocab, d, c->b.lm_head_p, REPACK_PLAIN, hd,
+    launch_repack_weight(Bp(c->w.lm_head), c->m.vocab, d, c->b.lm_head_p, REPACK_PLAIN, hd,
                          skinny_tiles_per_block(EPI_LOGITS, c->m.vocab / 16), 0, c->stream);
   }
   e = hipGetLastError();
@@ -537,34 +698,47 @@ int ec_init(ec_ctx** out, const ec_model_cfg* model, const ec_weights* weights,
 
 int ec_reset(ec_ctx* ctx, const int32_t* prompt_ids) {
   if (!ctx) return fail(nullptr, EC_ERR_ARG, "ctx is NULL");
-  if (ctx->P > 0 && !prompt_ids) return fail(ctx, EC_ERR_ARG, "prompt_ids is NULL");
-  for (int i = 0; i < ctx->P; ++i)
+  if (ctx->g.ptot > 0 && !prompt_ids) return fail(ctx, EC_ERR_ARG, "prompt_ids is NULL");
+  for (size_t i = 0; i < ctx->g.ptot; ++i)
     if (prompt_ids[i] < 0 || prompt_ids[i] >= ctx->m.vocab)
       return fail(ctx, EC_ERR_ARG, "prompt id outside the vocabulary");
   return upload_and_init_state(ctx, prompt_ids);
 }
 
 int ec_step(ec_ctx* ctx, int mode, ec_step_result* out) {
-  return run_step(ctx, mode, -1, nullptr, nullptr, out);
+  const int32_t m = mode;
+  return run_step(ctx, &m, 1, nullptr, nullptr, nullptr, out);
 }
 
 int ec_step_forced(ec_ctx* ctx, int mode, int32_t n, const int32_t* positions,
                    const int32_t* tokens, ec_step_result* out) {
+  if (ctx && ctx->B != 1)
+    return fail(ctx, EC_ERR_ARG, "ec_step_forced is for batch 1; use ec_step_forced_batch");
   if (n < 0) return fail(ctx, EC_ERR_ARG, "n must be >= 0");
-  return run_step(ctx, mode, n, positions, tokens, out);
+  const int32_t m = mode;
+  return run_step(ctx, &m, 1, &n, positions, tokens, out);
+}
+
+int ec_step_forced_batch(ec_ctx* ctx, const int32_t* modes, const int32_t* n,
+                         const int32_t* positions, const int32_t* tokens, ec_step_result* out) {
+  if (!ctx) return fail(nullptr, EC_ERR_ARG, "ctx is NULL");
+  if (!n) return fail(ctx, EC_ERR_ARG, "n is NULL");
+  return run_step(ctx, modes, ctx->B, n, positions, tokens, out);
 }
 
 int ec_generate(ec_ctx* ctx, int32_t* out_tokens, ec_gen_stats* stats) {
   if (!ctx) return fail(nullptr, EC_ERR_ARG, "ctx is NULL");
   if (!out_tokens) return fail(ctx, EC_ERR_ARG, "out_tokens is NULL");
   auto t0 = std::chrono::steady_clock::now();
-  ec_step_result r;
-  while (!ctx->done) {
-    int rc = run_step(ctx, EC_AUTO, -1, nullptr, nullptr, &r);
+  std::vector<ec_step_result> r(ctx->B);
+  const int32_t m = EC_AUTO;
+  while (!ctx->all_done) {
+    int rc = run_step(ctx, &m, 1, nullptr, nullptr, nullptr, r.data());
     if (rc != EC_OK) return rc;
   }
-  EC_HIP(ctx, hipMemcpy(out_tokens, ctx->b.x + ctx->P, (size_t)ctx->N * sizeof(int),
-                        hipMemcpyDeviceToHost));
+  for (int b = 0; b < ctx->B; ++b)
+    EC_HIP(ctx, hipMemcpy(out_tokens + (size_t)b * ctx->N, ctx->b.x + ctx->g.x_off[b] + ctx->g.P[b],
+                          (size_t)ctx->N * sizeof(int), hipMemcpyDeviceToHost));
   if (stats) {
     stats->steps = ctx->steps_run; stats->full_steps = ctx->full_steps;
     stats->partial_steps = ctx->partial_steps; stats->tokens = ctx->tokens;
@@ -590,31 +764,39 @@ int ec_profile_read(ec_ctx* ctx, ec_profile* out) {
   return EC_OK;
 }
 
-int ec_debug_read(ec_ctx* ctx, int what, int layer, void* host_dst, size_t bytes) {
+int ec_debug_read_seq(ec_ctx* ctx, int seq, int what, int layer, void* host_dst, size_t bytes) {
   if (!ctx) return fail(nullptr, EC_ERR_ARG, "ctx is NULL");
   if (!host_dst) return fail(ctx, EC_ERR_ARG, "host_dst is NULL");
+  if (seq < 0 || seq >= ctx->B) return fail(ctx, EC_ERR_ARG, "sequence index out of range");
   const void* src = nullptr;
   size_t avail = 0;
-  const size_t kvrow = (size_t)ctx->m.n_kv_heads * ctx->m.head_dim * esize(ctx->m.dtype);
+  const size_t es = esize(ctx->m.dtype);
+  const size_t kvrow = (size_t)ctx->m.n_kv_heads * ctx->m.head_dim * es;
+  const int T = ctx->g.T[seq], xo = ctx->g.x_off[seq], blk = ctx->d.block;
   switch (what) {
-    case EC_DBG_LOGITS: src = ctx->b.logits; avail = (size_t)ctx->d.block * ctx->m.vocab * 4; break;
+    case EC_DBG_LOGITS:
+      // rows of the last step, at the place the step gave them in the logits buffer
+      src = ctx->b.logits + (size_t)ctx->host_seqs[seq].lm0 * ctx->m.vocab;
+      avail = (size_t)blk * ctx->m.vocab * 4;
+      if (ctx->host_seqs[seq].mode < 0) avail = 0;
+      break;
     case EC_DBG_KCACHE:
     case EC_DBG_VCACHE:
       if (layer < 0 || layer >= ctx->m.n_layers) return fail(ctx, EC_ERR_ARG, "layer out of range");
-      src = kv_ptr(ctx, layer, what == EC_DBG_VCACHE); avail = (size_t)ctx->T * kvrow;
+      src = kv_ptr(ctx, layer, what == EC_DBG_VCACHE) + (size_t)ctx->g.kv_off[seq] * es;
+      avail = (size_t)T * kvrow;
       if (ctx->m.dtype == EC_BF16) {
         // the packed cache is put back into [T, Hkv, hd] order in a scratch activation buffer
-        launch_unpack_cache((const bf16_t*)src, what == EC_DBG_VCACHE, ctx->T,
-                            kv_keys(EC_BF16, ctx->T), ctx->m.n_kv_heads, ctx->m.head_dim,
-                            (bf16_t*)ctx->b.qkv, ctx->stream);
+        launch_unpack_cache((const bf16_t*)src, what == EC_DBG_VCACHE, T, ctx->g.tpad[seq],
+                            ctx->m.n_kv_heads, ctx->m.head_dim, (bf16_t*)ctx->b.qkv, ctx->stream);
         src = ctx->b.qkv;
       }
       break;
-    case EC_DBG_X: src = ctx->b.x; avail = (size_t)ctx->T * 4; break;
-    case EC_DBG_MASKED: src = ctx->b.masked; avail = (size_t)ctx->T; break;
-    case EC_DBG_HIST: src = ctx->b.hist; avail = (size_t)ctx->N * 4; break;
-    case EC_DBG_ROWS: src = ctx->b.rows_partial; avail = (size_t)ctx->n_rows_partial * 4; break;
-    case EC_DBG_ROW_STATS: src = ctx->b.row_stats; avail = (size_t)ctx->d.block * 16; break;
+    case EC_DBG_X: src = ctx->b.x + xo; avail = (size_t)T * 4; break;
+    case EC_DBG_MASKED: src = ctx->b.masked + xo; avail = (size_t)T; break;
+    case EC_DBG_HIST: src = ctx->b.hist + (size_t)seq * ctx->N; avail = (size_t)ctx->N * 4; break;
+    case EC_DBG_ROWS: src = ctx->b.rows_partial + xo; avail = (size_t)ctx->n_rows_partial[seq] * 4; break;
+    case EC_DBG_ROW_STATS: src = ctx->b.row_stats + (size_t)seq * blk * 4; avail = (size_t)blk * 16; break;
     default: return fail(ctx, EC_ERR_ARG, "unknown debug item");
   }
   if (bytes > avail) return fail(ctx, EC_ERR_ARG, "bytes exceeds the size of the item");
@@ -623,12 +805,17 @@ int ec_debug_read(ec_ctx* ctx, int what, int layer, void* host_dst, size_t bytes
   return EC_OK;
 }
 
+int ec_debug_read(ec_ctx* ctx, int what, int layer, void* host_dst, size_t bytes) {
+  return ec_debug_read_seq(ctx, 0, what, layer, host_dst, bytes);
+}
+
 void ec_destroy(ec_ctx* ctx) {
   if (!ctx) return;
   (void)hipStreamSynchronize(ctx->stream);
   for (auto& e : ctx->prof_pool) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
   if (ctx->host_out) (void)hipHostFree(ctx->host_out);
   if (ctx->host_stage) (void)hipHostFree(ctx->host_stage);
+  if (ctx->host_seqs) (void)hipHostFree(ctx->host_seqs);
   delete ctx;
 }
 

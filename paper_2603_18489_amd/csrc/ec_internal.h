@@ -22,6 +22,23 @@ struct DevState {
   int pad[7];
 };
 
+// One sequence of the batch as a step sees it; the host rewrites the table before every step.
+// A step's rows are the sequences' row sets one after the other, each padded to whole 16-row
+// tiles (to 256 rows once it has more than kSmallRows, so that an attention block's query tiles
+// never straddle two sequences); sequences with many rows come first.
+struct SeqDesc {
+  int P, T, tpad;   // prompt length, positions, keys per cache slab (padded to 32)
+  int x_off;        // first element of the sequence in x / masked / rows_partial
+  int kv_off;       // first element of the sequence's slabs inside one layer's K (or V) plane
+  int mode;         // EC_FULL / EC_PARTIAL this step, -1 = takes no part (finished)
+  int n_rows;       // rows it contributes: T or |M u R|
+  int row0;         // its first row in the step's row list
+  int seg_rows;     // rows of its segment including the padding
+  int n_mb, lm0;    // masked rows of its block; the first of them in the logits buffer
+  int forced_n;     // teacher forcing: tokens to commit, -1 = the step's own choice
+};
+constexpr int kSmallRows = 64;
+
 // What the decision kernel hands back to the host after each step.
 struct StepOut {
   ec_step_result r;
@@ -30,27 +47,31 @@ struct StepOut {
   int pad[6];
 };
 
+// Arguments of the decision kernel: one block per sequence.  The pointers are those of sequence
+// 0; block b moves them by its SeqDesc (x_off) or by b times the per-sequence stride given in the
+// comment, and takes P, T, n_mb, mode_run, n_rows_run, forced_n from its SeqDesc.
 struct DecideArgs {
+  const SeqDesc* seqs;
   // this step
-  const float4* partials;  // [n_mb][nparts] (max, argmax as float bits, sum e, sum e*(z-max))
+  const float4* partials;  // [lm0 + row][nparts] (max, argmax as float bits, sum e, sum e*(z-max))
   int nparts;
   int n_mb;
   int mode_run;
   int n_rows_run;
   int forced_n;            // -1: commit the step's own choice
-  const int* forced_pos;   // device
-  const int* forced_tok;   // device
+  const int* forced_pos;   // device, stride EC_MAX_N
+  const int* forced_tok;   // device, stride EC_MAX_N
   int init_only;           // 1: no decode, only build the lists of the first step
   // sequence state
-  int* x;                  // [T]
-  uint8_t* masked;         // [T]
-  int* hist;               // [N], INT32_MIN = never decoded
-  DevState* st;
-  int* mb_pos;             // [block] positions of the block's masked rows, ascending
-  int* rows_partial;       // [T] ascending positions of M u R
-  int* mb_idx;             // [block] index of each block row inside rows_partial
-  float* row_stats;        // [block][4] token, confidence, entropy, max logit
-  StepOut* out;
+  int* x;                  // [T] (x_off)
+  uint8_t* masked;         // [T] (x_off)
+  int* hist;               // [N], INT32_MIN = never decoded (stride N)
+  DevState* st;            // (stride 1)
+  int* mb_pos;             // [block] positions of the block's masked rows, ascending (stride block)
+  int* rows_partial;       // [T] ascending positions of M u R (x_off)
+  int* mb_idx;             // [block] index of each block row inside rows_partial (stride block)
+  float* row_stats;        // [block][4] token, confidence, entropy, max logit (stride 4*block)
+  StepOut* out;            // (stride 1)
   // configuration
   int P, N, T, block, k_recent, n_tok;
   float tau;
@@ -103,18 +124,33 @@ struct GemmEpi {
   bf16_t* a_next;                 // packed bf16(h * gain_next)
   unsigned long long* sumsq_out;  // [kSumSlots][sum_stride], accumulated with integer atomics
   bf16_t* act;                    // EPI_SWIGLU: packed activations, K = d_ffn
-  const int* rows;                // EPI_QKV: position of each row (nullable = identity)
-  const float2* cs;               // RoPE table [T][hd/2]
-  int Hq, Hkv, hd, Tpad;
+  const int4* rowinfo;            // EPI_QKV: per row (position or -1 for a padding row, index
+                                  // into x, offset and keys per slab of its sequence's cache)
+  const float2* cs;               // RoPE table [max T][hd/2]
+  int Hq, Hkv, hd;
   bf16_t* q_out;                  // [M, Hq*hd] row-major
   bf16_t* kc; bf16_t* vc;         // the layer's packed caches
 };
 
-// h = Emb[x[pos]], packed bf16(h * gain) for the first GEMM, the rows' sums of squares into
-// sumsq[0..M), and zeroes the nbuf-1 further sum buffers (stride sumsq_stride) of the step.
-void launch_embed_bf16(const bf16_t* emb, const int* x, const int* rows, int M, int d,
-                       const bf16_t* gain, float* h, bf16_t* a_out, unsigned long long* sumsq,
-                       int nbuf, int sumsq_stride, hipStream_t s);
+// First kernel of a step.  From the sequence table it writes the step's row list (rowinfo, one
+// int4 per row as GemmEpi describes; tileinfo, one int4 per 16 rows: cache offset, positions,
+// keys per slab, 1 if the sequence has more than kSmallRows rows) and lm_sel (for each masked
+// row of a current block, its row in the list); then, per row, h = Emb[x], packed bf16(h * gain)
+// for the first GEMM, the row's sum of squares into sumsq[0..R) and zeros into the nbuf-1
+// further sum buffers (stride sumsq_stride) of the step.  Padding rows get zeros.
+struct StepLists {
+  const SeqDesc* seqs; int B;
+  int R, n_lm;                  // rows of the step (with padding); masked block rows
+  const int* x;                 // concatenated by x_off, like rows_partial
+  const int* rows_partial;
+  const int* mb_pos;            // stride block
+  const int* mb_idx;            // stride block
+  int block;
+  int4* rowinfo; int4* tileinfo; int* lm_sel;
+};
+void launch_step_prologue_bf16(const StepLists& L, const bf16_t* emb, int d, const bf16_t* gain,
+                               float* h, bf16_t* a_out, unsigned long long* sumsq, int nbuf,
+                               int sumsq_stride, hipStream_t s);
 // Re-tiles W[N,K] (row-major) into fragment order inside a packed matrix whose tiles are
 // grouped by `grp`.  mode picks the destination row of each source row (row0 = first destination
 // row of this source matrix): plain; rotary halves (a head's tile t holds its columns 8t..8t+7
@@ -133,14 +169,20 @@ void launch_gemm_bf16(int epi, const bf16_t* Ap, int M_src, const bf16_t* Wp, in
 // q row-major [M, Hq*hd]; packed caches of one layer; out packed bf16 (K = Hq*hd).
 // part / tickets: scratch for splitting the keys over blocks when there are few query rows
 // (part_floats floats; 256 counters, zero on entry and again on exit); null = never split.
-void launch_attention_mfma(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int M, int T,
-                           int Tpad, int Hq, int Hkv, int hd, bf16_t* out, float* part,
-                           size_t part_floats, int* tickets, hipStream_t s);
+// R rows (rowinfo / tileinfo as the step prologue wrote them), kc / vc: one layer's planes.
+// tileinfo may be NULL when the step has a single sequence: then one_seq is every tile's entry.
+// has_small / has_large: whether any sequence of the step has at most / more than kSmallRows
+// rows; max_T: most positions of any few-row sequence taking part.
+void launch_attention_mfma(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int R,
+                           const int4* rowinfo, const int4* tileinfo, int4 one_seq,
+                           bool has_small, bool has_large, int max_T, int Hq, int Hkv, int hd,
+                           bf16_t* out, float* part, size_t part_floats, int* tickets,
+                           hipStream_t s);
 
 // decision
 int vocab_reduce_parts(int V);
 void launch_vocab_reduce(const float* logits, int n_rows, int V, float4* partials, hipStream_t s);
-void launch_decide(const DecideArgs& a, hipStream_t s);
+void launch_decide(const DecideArgs& a, int B, hipStream_t s);
 void launch_init_state(int* x, uint8_t* masked, int* hist, DevState* st, const int* prompt_dev,
                        int P, int N, int mask_id, hipStream_t s);
 

@@ -1,7 +1,10 @@
 // bf16 non-causal attention on MFMA with an online softmax, for the packed KV cache.
 //
-// For one kv head the "queries" are all (row, head-in-group) pairs, so grouped-query attention
-// reads each K/V fragment once for all heads of the group.  Per 32-key chunk and 16-query tile:
+// The step's rows come as a list (sequence after sequence, each padded to whole 16-row tiles);
+// a query tile is one 16-row tile of that list for one query head, tile number g * MT + mt for
+// head g of the kv head's group, so the tiles of a group share the K/V fragments in cache.
+// tileinfo tells each row tile which sequence's cache it attends to (offset, positions, padded
+// keys) and whether that sequence has many rows in this step.  Per 32-key chunk and query tile:
 //   S^T[keys x queries] = K . Q^T          (2 key tiles x HD/32 MFMAs, K fragments straight from
 //                                            the cache, Q fragments held in registers)
 //   online softmax down the key axis        (a lane owns 8 consecutive keys of one query; the
@@ -107,7 +110,6 @@ __device__ __forceinline__ void attn_chunk_tile(const bf16x8 (&kf)[2][HB], const
 struct AttnSplit {
   float* part;    // [pairs][gridDim.z][HT*64*4 + 64*2] floats
   int* tickets;   // [pairs], zero between launches (the last block of a pair resets its own)
-  int chunks_per_block;
 };
 
 __device__ __forceinline__ void st_agent(float* p, float a, float b) {
@@ -124,27 +126,35 @@ __device__ __forceinline__ float2 ld_agent(const float* p) {
 template <int HD>
 __global__ __launch_bounds__(512) void attn_mfma_split_kernel(
     const bf16_t* __restrict__ q, const au32x4* __restrict__ kp, const au32x4* __restrict__ vp,
-    int M, int T, int Tpad, int Hq, int Hkv, float scale_log2e, bf16_t* __restrict__ out,
-    int MT, AttnSplit sp) {
+    int R, const int4* __restrict__ rowinfo, const int4* __restrict__ tileinfo, int4 one_seq,
+    int Hq, int Hkv, float scale_log2e, bf16_t* __restrict__ out, AttnSplit sp) {
   constexpr int HB = HD / 32, HT = HD / 16, NW = 8;
   extern __shared__ float4 lds[];
   // scalar wave index: no MFMA may sit under a condition the compiler could treat as divergent
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int kvh = blockIdx.x, G = Hq / Hkv, nQ = M * G;
+  const int kvh = blockIdx.x, G = Hq / Hkv, MT = (R + 15) >> 4;
+  const int mt = blockIdx.y % MT, gq = blockIdx.y / MT;
+  // cache offset, positions, keys per slab, many-rows flag: from the table, or (tileinfo ==
+  // NULL: a single sequence) from the arguments, which saves a dependent load
+  const int4 ti = tileinfo ? tileinfo[mt] : one_seq;
+  if (ti.w != 0) return;         // that sequence's tiles belong to the other kernel
+  const int T = ti.y, Tpad = ti.z;
   const int nchunks = (T + 31) >> 5, KB32 = Tpad >> 5;
   const int qcol = lane & 15, grp = lane >> 4;
-  // this block's chunks: [c_lo, c_hi), never empty
-  const int c_lo = blockIdx.z * sp.chunks_per_block;
-  const int c_hi = min(c_lo + sp.chunks_per_block, nchunks);
+  // this block's chunks: [c_lo, c_hi), empty if the sequence is short
+  const int cpb = (nchunks + gridDim.z - 1) / gridDim.z;
+  const int c_lo = min((int)blockIdx.z * cpb, nchunks);
+  const int c_hi = min(c_lo + cpb, nchunks);
 
   // ---- Q fragments (B operand): lane (query qcol, group grp) holds 8 hd columns -------------
-  const int qi = blockIdx.y * 16 + qcol;
-  const bool qvalid = qi < nQ;
-  const int qrow = qvalid ? qi / G : 0, qhead = kvh * G + (qvalid ? qi % G : 0);
+  const int qrow = mt * 16 + qcol, qhead = kvh * G + gq;
+  const int qr = qrow < R ? qrow : 0;
+  const bool qvalid = qrow < R && rowinfo[qr].x >= 0;
   bf16x8 qf[HB];
 #pragma unroll
   for (int hb = 0; hb < HB; ++hb) {
-    au32x4 v = *(const au32x4*)(q + (size_t)qrow * Hq * HD + qhead * HD + hb * 32 + grp * 8);
+    // loaded regardless of validity (row qr exists), so that it does not wait for rowinfo
+    au32x4 v = *(const au32x4*)(q + (size_t)qr * Hq * HD + qhead * HD + hb * 32 + grp * 8);
     qf[hb] = av4_as_bf16x8(qvalid ? v : (au32x4){0u, 0u, 0u, 0u});
   }
 
@@ -153,8 +163,9 @@ __global__ __launch_bounds__(512) void attn_mfma_split_kernel(
 #pragma unroll
   for (int h = 0; h < HT; ++h) acc[h] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  const au32x4* kbase = kp + (size_t)kvh * KB32 * 2 * HB * 64 + lane;
-  const au32x4* vbase = vp + (size_t)kvh * HT * KB32 * 64 + lane;
+  const size_t slab = ((size_t)ti.x + (size_t)kvh * Tpad * HD) >> 3;  // in 16-byte units
+  const au32x4* kbase = kp + slab + lane;
+  const au32x4* vbase = vp + slab + lane;
   // the wave's chunks are c_lo + wave, + NW, ...: n_my of them.  Loads are unconditional (a
   // chunk past the end re-reads the last one, which is in cache); a chunk past the end is
   // computed with every key masked, which changes nothing once the wave has seen one real chunk.
@@ -162,7 +173,7 @@ __global__ __launch_bounds__(512) void attn_mfma_split_kernel(
   bf16x8 kfa[2][HB], vfa[HT], kfb[2][HB], vfb[HT];
 #define EC_AT_LOAD(KF, VF, I)                                                               \
   {                                                                                         \
-    const int c_ = min(c_lo + wave + NW * (I), c_hi - 1);                                   \
+    const int c_ = max(min(c_lo + wave + NW * (I), c_hi - 1), 0);                           \
     _Pragma("unroll") for (int t2 = 0; t2 < 2; ++t2)                                        \
       _Pragma("unroll") for (int hb = 0; hb < HB; ++hb)                                     \
         KF[t2][hb] = av4_as_bf16x8(kbase[((size_t)(c_ * 2 + t2) * HB + hb) * 64]);          \
@@ -232,7 +243,8 @@ __global__ __launch_bounds__(512) void attn_mfma_split_kernel(
       // lane holds hd rows h*16 + grp*4 .. +3 of query qcol
       const float inv = 1.0f / l_all;
       uint2 pk = make_uint2(pack2_bf16(o.x * inv, o.y * inv), pack2_bf16(o.z * inv, o.w * inv));
-      if (qvalid) *(uint2*)(out + packed_act_index(qrow, qhead * HD + h * 16 + grp * 4, MT)) = pk;
+      if (!qvalid) pk = make_uint2(0u, 0u);  // padding rows of the list read as zeros downstream
+      if (qrow < R) *(uint2*)(out + packed_act_index(qrow, qhead * HD + h * 16 + grp * 4, MT)) = pk;
     } else {
       st_agent(mine + (h * 64 + lane) * 4, o.x, o.y);
       st_agent(mine + (h * 64 + lane) * 4 + 2, o.z, o.w);
@@ -252,7 +264,7 @@ __global__ __launch_bounds__(512) void attn_mfma_split_kernel(
     *flag = (old == nz - 1);
   }
   __syncthreads();
-  if (*flag == 0 || !qvalid) return;
+  if (*flag == 0 || qrow >= R) return;
   const float* base = sp.part + (size_t)pair * nz * PSLOT;
   float m_fin = -INFINITY, l_fin = 0.f;
   for (int z = 0; z < nz; ++z) m_fin = fmaxf(m_fin, ld_agent(base + (size_t)z * PSLOT + HT * 256 + lane * 2).x);
@@ -269,6 +281,7 @@ __global__ __launch_bounds__(512) void attn_mfma_split_kernel(
     }
     const float inv = 1.0f / l_fin;
     uint2 pk = make_uint2(pack2_bf16(o.x * inv, o.y * inv), pack2_bf16(o.z * inv, o.w * inv));
+    if (!qvalid) pk = make_uint2(0u, 0u);
     *(uint2*)(out + packed_act_index(qrow, qhead * HD + h * 16 + grp * 4, MT)) = pk;
   }
 }
@@ -287,21 +300,30 @@ template <int N> __device__ __forceinline__ void attn_wait_vmcnt() {
 template <int HD, int QT, int NW>
 __global__ __launch_bounds__(NW * 64) void attn_mfma_shared_kernel(
     const bf16_t* __restrict__ q, const au32x4* __restrict__ kp, const au32x4* __restrict__ vp,
-    int M, int T, int Tpad, int Hq, int Hkv, float scale_log2e, bf16_t* __restrict__ out,
-    int MT) {
+    int R, const int4* __restrict__ rowinfo, const int4* __restrict__ tileinfo, int4 one_seq,
+    int Hq, int Hkv, float scale_log2e, bf16_t* __restrict__ out) {
   constexpr int HB = HD / 32, HT = HD / 16, NSTAGE = 3;
   constexpr int NFRAG = 2 * HB + HT, LF = NFRAG / NW;
   static_assert(NFRAG % NW == 0, "fragments per chunk must divide over the waves");
   extern __shared__ au32x4 ring[];  // [NSTAGE][NFRAG][64]
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int kvh = blockIdx.y, G = Hq / Hkv, nQ = M * G;
+  const int kvh = blockIdx.y, G = Hq / Hkv, MT = (R + 15) >> 4, MTp = (MT + 15) & ~15;
+  // the block's NW*QT query tiles: one head of the group, consecutive row tiles that all lie in
+  // one many-row sequence (such sequences come first and are padded to 16 row tiles) or in none
+  const int t_first = blockIdx.x * NW * QT;
+  const int gq = t_first / MTp, mt_first = t_first - gq * MTp;
+  if (mt_first >= MT) return;
+  const int4 ti = tileinfo ? tileinfo[mt_first] : one_seq;
+  if (ti.w == 0) return;  // few-row sequences belong to the other kernel
+  const int T = ti.y, Tpad = ti.z;
   const int nchunks = (T + 31) >> 5, KB32 = Tpad >> 5;
-  const int tile0 = (blockIdx.x * NW + wave) * QT;
+  const int mt0 = mt_first + wave * QT;
   const int qcol = lane & 15, grp = lane >> 4;
 
   // fragment f of a chunk: f < 2*HB is K tile f / HB, hd block f % HB; the rest are V^T hd tiles
-  const au32x4* kbase = kp + (size_t)kvh * KB32 * 2 * HB * 64 + lane;
-  const au32x4* vbase = vp + (size_t)kvh * HT * KB32 * 64 + lane;
+  const size_t slab = ((size_t)ti.x + (size_t)kvh * Tpad * HD) >> 3;  // in 16-byte units
+  const au32x4* kbase = kp + slab + lane;
+  const au32x4* vbase = vp + slab + lane;
   auto issue = [&](int c) {
     const int cc = min(c, nchunks - 1), stage = c % NSTAGE;
 #pragma unroll
@@ -317,18 +339,18 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_shared_kernel(
   };
 
   bf16x8 qf[QT][HB];
-  int qrow[QT], qhead[QT];
+  int qrow[QT];
+  bool qvalid[QT];
+  const int qhead = kvh * G + gq;
 #pragma unroll
   for (int t = 0; t < QT; ++t) {
-    int qi = (tile0 + t) * 16 + qcol;
-    bool valid = qi < nQ;
-    qrow[t] = valid ? qi / G : -1;
-    qhead[t] = kvh * G + (valid ? qi % G : 0);
+    qrow[t] = (mt0 + t) * 16 + qcol;
+    qvalid[t] = qrow[t] < R && rowinfo[qrow[t] < R ? qrow[t] : 0].x >= 0;
 #pragma unroll
     for (int hb = 0; hb < HB; ++hb) {
       uint4 v = make_uint4(0, 0, 0, 0);
-      if (valid)
-        v = *(const uint4*)(q + (size_t)qrow[t] * Hq * HD + qhead[t] * HD + hb * 32 + grp * 8);
+      if (qvalid[t])
+        v = *(const uint4*)(q + (size_t)qrow[t] * Hq * HD + qhead * HD + hb * 32 + grp * 8);
       qf[t][hb] = u4_as_bf16x8(v);
     }
   }
@@ -368,26 +390,29 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_shared_kernel(
 
 #pragma unroll
   for (int t = 0; t < QT; ++t) {
-    if (qrow[t] < 0) continue;
+    if (qrow[t] >= R) continue;
     float inv = 1.0f / l_run[t];
 #pragma unroll
     for (int h = 0; h < HT; ++h) {
       f32x4 a = acc[t][h];
       uint2 pk = make_uint2(pack2_bf16(a[0] * inv, a[1] * inv), pack2_bf16(a[2] * inv, a[3] * inv));
-      int k = qhead[t] * HD + h * 16 + grp * 4;
+      if (!qvalid[t]) pk = make_uint2(0u, 0u);  // padding rows read as zeros downstream
+      int k = qhead * HD + h * 16 + grp * 4;
       *(uint2*)(out + packed_act_index(qrow[t], k, MT)) = pk;
     }
   }
 }
 
 template <int HD>
-static void launch_attn_mfma_hd(const bf16_t* q, const uint4* kp, const uint4* vp, int M, int T,
-                                int Tpad, int Hq, int Hkv, bf16_t* out, float* part,
-                                size_t part_floats, int* tickets, hipStream_t s) {
-  const int G = Hq / Hkv, nQ = M * G, qtiles = (nQ + 15) / 16, MT = (M + 15) / 16;
+static void launch_attn_mfma_hd(const bf16_t* q, const uint4* kp, const uint4* vp, int R,
+                                const int4* rowinfo, const int4* tileinfo, int4 one_seq,
+                                bool has_small, bool has_large, int max_T, int Hq, int Hkv,
+                                bf16_t* out, float* part, size_t part_floats, int* tickets,
+                                hipStream_t s) {
+  const int G = Hq / Hkv, MT = (R + 15) / 16;
   const float sc = 1.4426950408889634f / sqrtf((float)HD);
-  if (qtiles * Hkv <= 256) {
-    // few (query tile, kv head) pairs: one block each, the keys split over its waves
+  if (has_small) {
+    // sequences with few rows: one block per query tile, the keys split over its waves
     constexpr int SLOT = (HD / 16) * 64 + 32;
     constexpr size_t smem = 8 * SLOT * sizeof(float4);
     static bool attr_set = false;
@@ -399,10 +424,10 @@ static void launch_attn_mfma_hd(const bf16_t* q, const uint4* kp, const uint4* v
     // Key slices over blocks pay only for long contexts (the pieces go through write-through
     // stores and a ticket, about 3 us): from 64 chunks on, two or more chunks per wave, and no
     // more blocks than compute units.
-    const int nchunks = (T + 31) / 32, pairs = qtiles * Hkv;
+    const int nchunks = (max_T + 31) / 32, pairs = G * MT * Hkv;
     constexpr size_t PSLOT = (HD / 16) * 256 + 128;
     int nz = 1;
-    if (nchunks >= 64) {
+    if (nchunks >= 64 && pairs <= 256) {
       nz = nchunks / 16;
       if (nz > 256 / pairs) nz = 256 / pairs;
       if (nz > 8) nz = 8;
@@ -413,36 +438,42 @@ static void launch_attn_mfma_hd(const bf16_t* q, const uint4* kp, const uint4* v
     AttnSplit sp;
     sp.part = part;
     sp.tickets = tickets;
-    sp.chunks_per_block = (nchunks + nz - 1) / nz;
-    nz = (nchunks + sp.chunks_per_block - 1) / sp.chunks_per_block;  // no empty slice
-    attn_mfma_split_kernel<HD><<<dim3(Hkv, qtiles, nz), 512, smem, s>>>(
-        q, (const au32x4*)kp, (const au32x4*)vp, M, T, Tpad, Hq, Hkv, sc, out, MT, sp);
-  } else {
+    attn_mfma_split_kernel<HD><<<dim3(Hkv, G * MT, nz), 512, smem, s>>>(
+        q, (const au32x4*)kp, (const au32x4*)vp, R, rowinfo, tileinfo, one_seq, Hq, Hkv, sc, out,
+        sp);
+  }
+  if (has_large) {
     // two query tiles per wave halve the LDS reads per MFMA, but only pay once the grid still
     // covers the chip's 256 compute units
     constexpr int NW = 8, NFRAG = 2 * (HD / 32) + HD / 16;
-    if (((qtiles + 2 * NW - 1) / (2 * NW)) * Hkv >= 256) {
-      dim3 grid((qtiles + 2 * NW - 1) / (2 * NW), Hkv);
+    const int tiles = G * ((MT + 15) & ~15);
+    if ((tiles / (2 * NW)) * Hkv >= 256) {
+      dim3 grid(tiles / (2 * NW), Hkv);
       attn_mfma_shared_kernel<HD, 2, NW><<<grid, NW * 64, 3 * NFRAG * 1024, s>>>(
-          q, (const au32x4*)kp, (const au32x4*)vp, M, T, Tpad, Hq, Hkv, sc, out, MT);
+          q, (const au32x4*)kp, (const au32x4*)vp, R, rowinfo, tileinfo, one_seq, Hq, Hkv, sc,
+          out);
     } else {
-      dim3 grid((qtiles + NW - 1) / NW, Hkv);
+      dim3 grid(tiles / NW, Hkv);
       attn_mfma_shared_kernel<HD, 1, NW><<<grid, NW * 64, 3 * NFRAG * 1024, s>>>(
-          q, (const au32x4*)kp, (const au32x4*)vp, M, T, Tpad, Hq, Hkv, sc, out, MT);
+          q, (const au32x4*)kp, (const au32x4*)vp, R, rowinfo, tileinfo, one_seq, Hq, Hkv, sc,
+          out);
     }
   }
 }
 
-void launch_attention_mfma(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int M, int T,
-                           int Tpad, int Hq, int Hkv, int hd, bf16_t* out, float* part,
-                           size_t part_floats, int* tickets, hipStream_t s) {
-  if (M <= 0) return;
+void launch_attention_mfma(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int R,
+                           const int4* rowinfo, const int4* tileinfo, int4 one_seq,
+                           bool has_small, bool has_large, int max_T, int Hq, int Hkv, int hd,
+                           bf16_t* out, float* part, size_t part_floats, int* tickets,
+                           hipStream_t s) {
+  if (R <= 0) return;
   if (hd == 64)
-    launch_attn_mfma_hd<64>(q, (const uint4*)kc, (const uint4*)vc, M, T, Tpad, Hq, Hkv, out, part,
-                            part_floats, tickets, s);
+    launch_attn_mfma_hd<64>(q, (const uint4*)kc, (const uint4*)vc, R, rowinfo, tileinfo, one_seq,
+                            has_small, has_large, max_T, Hq, Hkv, out, part, part_floats, tickets, s);
   else
-    launch_attn_mfma_hd<128>(q, (const uint4*)kc, (const uint4*)vc, M, T, Tpad, Hq, Hkv, out, part,
-                             part_floats, tickets, s);
+    launch_attn_mfma_hd<128>(q, (const uint4*)kc, (const uint4*)vc, R, rowinfo, tileinfo, one_seq,
+                             has_small, has_large, max_T, Hq, Hkv, out, part, part_floats, tickets,
+                             s);
 }
 
 }  // namespace ec

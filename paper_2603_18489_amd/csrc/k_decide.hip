@@ -125,6 +125,18 @@ __device__ __forceinline__ int block_excl_scan_flag(int flag, int* scratch, int*
 // decide: one block of 256 threads per sequence.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void decide_kernel(DecideArgs a) {
+  {  // this block's sequence: move the pointers, take the per-sequence scalars
+    const int b = blockIdx.x;
+    const SeqDesc sd = a.seqs[b];
+    if (sd.mode < 0) return;  // finished earlier: no rows in this step, nothing to decide
+    a.partials += (size_t)sd.lm0 * a.nparts;
+    a.n_mb = sd.n_mb; a.mode_run = sd.mode; a.n_rows_run = sd.n_rows; a.forced_n = sd.forced_n;
+    a.forced_pos += b * EC_MAX_N; a.forced_tok += b * EC_MAX_N;
+    a.x += sd.x_off; a.masked += sd.x_off; a.rows_partial += sd.x_off;
+    a.hist += (size_t)b * a.N; a.st += b; a.out += b;
+    a.mb_pos += b * a.block; a.mb_idx += b * a.block; a.row_stats += b * a.block * 4;
+    a.P = sd.P; a.T = sd.T;
+  }
   __shared__ int s_tok[EC_MAX_BLOCK];
   __shared__ float s_conf[EC_MAX_BLOCK], s_H[EC_MAX_BLOCK];
   __shared__ int s_taken[EC_MAX_BLOCK];
@@ -293,7 +305,9 @@ __global__ __launch_bounds__(256) void decide_kernel(DecideArgs a) {
   }
 }
 
-void launch_decide(const DecideArgs& a, hipStream_t s) { decide_kernel<<<1, 256, 0, s>>>(a); }
+void launch_decide(const DecideArgs& a, int B, hipStream_t s) {
+  decide_kernel<<<B, 256, 0, s>>>(a);
+}
 
 // ---------------------------------------------------------------------------------------------
 // init_state: x = [prompt ; mask_id ...], mask set = generation slots, history = never,

@@ -92,7 +92,8 @@ __device__ __forceinline__ void epi_add_sumsq(const GemmEpi& e, int m, bool vali
   if (valid && (threadIdx.x & 63) < 16) {
     unsigned long long fx = (unsigned long long)((double)part * 4294967296.0 + 0.5);
     const int slot = (blockIdx.x + blockIdx.y) & (kSumSlots - 1);
-    atomicAdd((unsigned long long*)(e.sumsq_out + (size_t)slot * e.sum_stride + m), fx);
+    // (the padding rows of the row list are all zeros: nothing to add)
+    if (fx) atomicAdd((unsigned long long*)(e.sumsq_out + (size_t)slot * e.sum_stride + m), fx);
   }
 }
 
@@ -138,11 +139,13 @@ __device__ __forceinline__ void epi_qkv(const GemmEpi& e, int m, int vt, int q4,
                                         float rs) {
   const int hd = e.hd, tph = hd >> 4;  // tiles per head
   const int nqt = e.Hq * tph, nkt = e.Hkv * tph;
-  const int pos = e.rows ? e.rows[m] : m;
+  const int4 ri = e.rowinfo[m];  // position, -, cache offset, keys per slab
+  const int pos = ri.x;
   if (vt < nqt + nkt) {
     float o[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) o[r] = other_half(v[r]);
+    if (pos < 0) return;  // padding row (its partner lane has the same row)
     const bool is_q = vt < nqt, hi = q4 >= 2;
     const int t = is_q ? vt : vt - nqt;
     const int head = t / tph, j = (t % tph) * 8 + (q4 & 1) * 4;  // column within the half head
@@ -160,15 +163,15 @@ __device__ __forceinline__ void epi_qkv(const GemmEpi& e, int m, int vt, int q4,
     if (is_q) {
       *(u32x2*)(e.q_out + (size_t)m * (e.Hq * hd) + head * hd + col) = pk;
     } else {
-      bf16_t* slab = e.kc + (size_t)head * e.Tpad * hd;
+      bf16_t* slab = e.kc + ri.z + (size_t)head * ri.w * hd;
       *(u32x2*)(slab + kcache_index(pos, col, hd)) = pk;
     }
-  } else {
+  } else if (pos >= 0) {
     const int t = vt - nqt - nkt;
     const int head = t / tph, c0 = (t % tph) * 16 + q4 * 4;
-    bf16_t* slab = e.vc + (size_t)head * e.Tpad * hd;
+    bf16_t* slab = e.vc + ri.z + (size_t)head * ri.w * hd;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) slab[vcache_index(pos, c0 + r, e.Tpad)] = f32_to_bf16(v[r] * rs);
+    for (int r = 0; r < 4; ++r) slab[vcache_index(pos, c0 + r, ri.w)] = f32_to_bf16(v[r] * rs);
   }
 }
 
@@ -397,15 +400,18 @@ __device__ __forceinline__ void tiled_epilogue_qkv(const GemmEpi& e, f32x4 (&acc
     head[i] = t / tph;
     w[i] = t - head[i] * tph;
   }
-  int pos[WTM];
+  int pos[WTM], kvoff[WTM], tpad[WTM];
   float rs[WTM];
   bool mvalid[WTM];
 #pragma unroll
   for (int j = 0; j < WTM; ++j) {
     const int m = (mt_base + j) * 16 + (lane & 15);
-    mvalid[j] = m < e.M;
-    const int mm = mvalid[j] ? m : 0;
-    pos[j] = e.rows ? e.rows[mm] : mm;
+    const int mm = m < e.M ? m : 0;
+    const int4 ri = e.rowinfo[mm];
+    mvalid[j] = m < e.M && ri.x >= 0;  // not a padding row
+    pos[j] = ri.x >= 0 ? ri.x : 0;
+    kvoff[j] = ri.z;
+    tpad[j] = ri.w;
     rs[j] = rstd_of(e, mm);
   }
   float4 ca[WTN][2], cb[WTN][2];  // (cos, sin) x 4 columns for each rotary tile of one m-tile
@@ -436,12 +442,13 @@ __device__ __forceinline__ void tiled_epilogue_qkv(const GemmEpi& e, f32x4 (&acc
         if (kind[i] == 0)                                                                    \
           *(u32x2*)(e.q_out + (size_t)m_ * (e.Hq * hd) + head[i] * hd + col_) = pk_;          \
         else                                                                                 \
-          *(u32x2*)(e.kc + (size_t)head[i] * e.Tpad * hd + kcache_index(pos[J], col_, hd)) = pk_; \
+          *(u32x2*)(e.kc + kvoff[J] + (size_t)head[i] * tpad[J] * hd +                        \
+                    kcache_index(pos[J], col_, hd)) = pk_;                                   \
       }                                                                                      \
     } else if (kind[i] == 2 && mvalid[J]) {                                                  \
-      bf16_t* slab_ = e.vc + (size_t)head[i] * e.Tpad * hd;                                   \
+      bf16_t* slab_ = e.vc + kvoff[J] + (size_t)head[i] * tpad[J] * hd;                       \
       _Pragma("unroll") for (int r = 0; r < 4; ++r)                                            \
-          slab_[vcache_index(pos[J], w[i] * 16 + q4 * 4 + r, e.Tpad)] = f32_to_bf16(v[r] * rs[J]); \
+          slab_[vcache_index(pos[J], w[i] * 16 + q4 * 4 + r, tpad[J])] = f32_to_bf16(v[r] * rs[J]); \
     }                                                                                        \
   }
   EC_QKV_LOADC(ca, 0)
@@ -776,7 +783,7 @@ __global__ __launch_bounds__(256) void resid_finish_kernel(GemmEpi e, int ksplit
   part = block_sum<4>(part, red);
   if (threadIdx.x == 0) {
     unsigned long long fx = (unsigned long long)((double)part * 4294967296.0 + 0.5);
-    atomicAdd((unsigned long long*)(e.sumsq_out + (size_t)(blockIdx.x & (kSumSlots - 1)) * e.sum_stride + m), fx);
+    if (fx) atomicAdd((unsigned long long*)(e.sumsq_out + (size_t)(blockIdx.x & (kSumSlots - 1)) * e.sum_stride + m), fx);
   }
 }
 
@@ -835,14 +842,15 @@ static void launch_epi(const bf16_t* Ap, int M_src, const bf16_t* Wp, int N, int
       default: launch_skinny_mt<EPI, 4>(Ap, MT_src, Wp, total_nt, KB, e, s); break;
     }
   } else {
-    // the tiled kernel reads its activation rows in place (no gather): M_src == M
+    // the tiled kernel reads its activation rows in place (no gather) and walks every m-tile of
+    // the buffer; rows from e.M on are dropped in the epilogue
     const int max_ks = (EPI == EPI_RESID && e.partial) ? e.max_ksplit : 1;
-    TilePick tp = pick_tile(MT, total_nt, KB, max_ks, e.M, N);
+    TilePick tp = pick_tile(MT_src, total_nt, KB, max_ks, e.M, N);
     if (tp.ksplit > 1) {
-      launch_tiled_pick<EPI_PARTIAL>(Ap, MT, Wp, total_nt, KB, e, s, tp.tile, tp.ksplit);
+      launch_tiled_pick<EPI_PARTIAL>(Ap, MT_src, Wp, total_nt, KB, e, s, tp.tile, tp.ksplit);
       resid_finish_kernel<<<dim3((N + 1023) / 1024, e.M), 256, 0, s>>>(e, tp.ksplit);
     } else {
-      launch_tiled_pick<EPI>(Ap, MT, Wp, total_nt, KB, e, s, tp.tile, 1);
+      launch_tiled_pick<EPI>(Ap, MT_src, Wp, total_nt, KB, e, s, tp.tile, 1);
     }
   }
 }

@@ -1,8 +1,9 @@
 // Small memory-bound kernels around the GEMMs.
 //  float32 path: embedding gather, RMSNorm, RoPE + KV-cache scatter, SwiGLU (row-major tensors).
-//  bf16 path:    embedding gather fused with the first norm's operand, the one-time re-tiling of
-//                the matrices, and the un-tiling of a cache layer for debug read-back.  Everything
-//                else of that path lives in the GEMM epilogues.
+//  bf16 path:    the step prologue (row list, embedding gather fused with the first norm's
+//                operand), the one-time re-tiling of the matrices, and the un-tiling of a cache
+//                layer for debug read-back.  Everything else of that path lives in the GEMM
+//                epilogues.
 #include "ec_internal.h"
 
 namespace ec {
@@ -27,21 +28,49 @@ void launch_embed_f32(const float* emb, const int* x, const int* rows, int M, in
   embed_f32_kernel<<<M, 256, 0, s>>>(emb, x, rows, d, h);
 }
 
-// bf16: also emits the first GEMM's operand bf16(h * gain) in fragment order, the row's sum of
-// squares (32.32 fixed point), and clears the step's other sum buffers for this row.
-__global__ __launch_bounds__(256) void embed_bf16_kernel(
-    const bf16_t* __restrict__ emb, const int* __restrict__ x, const int* __restrict__ rows, int M,
-    int d, const bf16_t* __restrict__ gain, float* __restrict__ h, bf16_t* __restrict__ a_out,
-    unsigned long long* __restrict__ sumsq, int nbuf, int sumsq_stride, int MT) {
+// bf16: the step's first kernel, one block per row of the step's row list.  It derives the
+// row's sequence and position from the sequence table (and records them for the later kernels),
+// gathers the embedding, emits the first GEMM's operand bf16(h * gain) in fragment order and the
+// row's sum of squares (32.32 fixed point), and clears the step's other sum buffers for the row.
+__global__ __launch_bounds__(256) void step_prologue_bf16_kernel(
+    StepLists L, const bf16_t* __restrict__ emb, int d, const bf16_t* __restrict__ gain,
+    float* __restrict__ h, bf16_t* __restrict__ a_out, unsigned long long* __restrict__ sumsq,
+    int nbuf, int sumsq_stride, int MT) {
   __shared__ float red[4];
-  int r = blockIdx.x;
-  int pos = rows ? rows[r] : r;
-  const bf16_t* src = emb + (size_t)x[pos] * d;
+  __shared__ int sh_xidx;
+  const int r = blockIdx.x;
+  if (threadIdx.x == 0) {
+    int4 ri = make_int4(-1, -1, 0, 32);
+    int4 ti = make_int4(0, 0, 32, 0);
+    for (int b = 0; b < L.B; ++b) {
+      const SeqDesc sd = L.seqs[b];
+      if (sd.mode < 0 || r < sd.row0 || r >= sd.row0 + sd.seg_rows) continue;
+      const int i = r - sd.row0;
+      int pos = -1;
+      if (i < sd.n_rows) pos = sd.mode == EC_FULL ? i : L.rows_partial[sd.x_off + i];
+      ri = make_int4(pos, pos >= 0 ? sd.x_off + pos : -1, sd.kv_off, sd.tpad);
+      ti = make_int4(sd.kv_off, sd.T, sd.tpad, sd.n_rows > kSmallRows ? 1 : 0);
+    }
+    L.rowinfo[r] = ri;
+    if ((r & 15) == 0) L.tileinfo[r >> 4] = ti;
+    sh_xidx = ri.y;
+    if (r < L.n_lm) {
+      for (int b = 0; b < L.B; ++b) {
+        const SeqDesc sd = L.seqs[b];
+        if (sd.mode < 0 || r < sd.lm0 || r >= sd.lm0 + sd.n_mb) continue;
+        const int i = b * L.block + (r - sd.lm0);
+        L.lm_sel[r] = sd.row0 + (sd.mode == EC_FULL ? L.mb_pos[i] : L.mb_idx[i]);
+      }
+    }
+  }
+  __syncthreads();
+  const int xidx = sh_xidx;
+  const bf16_t* src = emb + (size_t)(xidx >= 0 ? L.x[xidx] : 0) * d;
   float* dst = h + (size_t)r * d;
   float ss = 0.f;
   for (int c8 = threadIdx.x * 8; c8 < d; c8 += 256 * 8) {
     union { uint4 v; bf16_t e[8]; } in, out;
-    in.v = *(const uint4*)(src + c8);
+    in.v = xidx >= 0 ? *(const uint4*)(src + c8) : make_uint4(0, 0, 0, 0);
     float f[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -59,12 +88,12 @@ __global__ __launch_bounds__(256) void embed_bf16_kernel(
   for (int b = 1 + threadIdx.x; b < nbuf; b += 256) sumsq[(size_t)b * sumsq_stride + r] = 0ull;
 }
 
-void launch_embed_bf16(const bf16_t* emb, const int* x, const int* rows, int M, int d,
-                       const bf16_t* gain, float* h, bf16_t* a_out, unsigned long long* sumsq,
-                       int nbuf, int sumsq_stride, hipStream_t s) {
-  if (M <= 0) return;
-  embed_bf16_kernel<<<M, 256, 0, s>>>(emb, x, rows, M, d, gain, h, a_out, sumsq, nbuf,
-                                      sumsq_stride, (M + 15) / 16);
+void launch_step_prologue_bf16(const StepLists& L, const bf16_t* emb, int d, const bf16_t* gain,
+                               float* h, bf16_t* a_out, unsigned long long* sumsq, int nbuf,
+                               int sumsq_stride, hipStream_t s) {
+  if (L.R <= 0) return;
+  step_prologue_bf16_kernel<<<L.R, 256, 0, s>>>(L, emb, d, gain, h, a_out, sumsq, nbuf,
+                                                sumsq_stride, (L.R + 15) / 16);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -108,3 +108,78 @@ def run_teacher_forced(cfg, w, dec, prompt, tol, max_steps=None, check_cache_eve
     finally:
         g.close()
     return {"steps": steps, "modes": modes, "worst": worst, "exact_checked": n_exact_checked}
+
+
+def run_teacher_forced_batch(cfg, w, dec, prompts, tol, max_steps=None, fast_seq=None,
+                             check_cache_every=4):
+    """The batched HIP path against one oracle run per sequence (sequences are independent, so
+    the batch must reproduce each of them).  fast_seq: that sequence commits every masked token
+    of its block at each step (with the oracle's argmax tokens), so it finishes early while the
+    others go on.  Returns a summary; raises AssertionError on any parity violation."""
+    B = len(prompts)
+    model = eco.OracleModel(cfg, w)
+    sts = [eco.eco_init(model, dec, p) for p in prompts]
+    g = ec.EntropyCache(cfg, ec.weights_to_device(cfg, w), dec, prompts)
+    worst = {"logits": 0.0, "K": 0.0, "V": 0.0}
+    steps, modes = 0, {eco.FULL: 0, eco.PARTIAL: 0}
+    finished_early = 0
+    try:
+        while not all(st.done for st in sts) and (max_steps is None or steps < max_steps):
+            res = [None] * B
+            for b, st in enumerate(sts):
+                if st.done:
+                    continue
+                Mb = eco.current_block_masked(st)
+                exp_rows = sorted(set(Mb.tolist()) | set(st.R))
+                if steps > 0:
+                    rows = g.debug_read(ec.EC_DBG_ROWS, count=len(exp_rows), seq=b)
+                    assert rows.tolist() == exp_rows, f"seq {b} step {st.t}: row set differs"
+                if b == fast_seq:
+                    # look at the step's own tokens first, then commit the whole block
+                    import copy
+                    probe = eco.eco_step(copy.deepcopy(st), eco.AUTO)
+                    forced = {"positions": [int(p) for p in probe["Mb"]],
+                              "tokens": [int(v) for v in probe["tok"]]}
+                    res[b] = eco.eco_step(st, probe["mode"], forced=forced)
+                else:
+                    res[b] = eco.eco_step(st, eco.AUTO)
+            mlist = [r["mode"] if r else ec.EC_AUTO for r in res]
+            plist = [r["positions"] if r else [] for r in res]
+            tlist = [r["tokens"] if r else [] for r in res]
+            q = g.step_forced_batch(mlist, plist, tlist)
+            steps += 1
+            for b, r in enumerate(res):
+                if r is None:
+                    assert q[b]["done"], f"seq {b}: finished sequence must report done"
+                    finished_early += 1
+                    continue
+                modes[r["mode"]] += 1
+                nmb = len(r["Mb"])
+                assert q[b]["mode_run"] == r["mode"] and q[b]["n_query_rows"] == len(r["S"])
+                assert q[b]["n_block_rows"] == nmb and q[b]["step_index"] == r["t"]
+                assert q[b]["done"] == r["done"] and q[b]["n_recent_next"] == len(r["R"])
+                logits = g.debug_read(ec.EC_DBG_LOGITS, count=nmb, seq=b)
+                e = relerr(logits, r["logits"])
+                worst["logits"] = max(worst["logits"], e)
+                assert e <= tol, f"seq {b} step {r['t']} mode {r['mode']}: logits rel err {e:.3e}"
+                stats = g.debug_read(ec.EC_DBG_ROW_STATS, count=nmb, seq=b)
+                zrange = float(np.ptp(r["logits"]))
+                stat_tol = max(tol, 4 * tol * max(zrange, 1.0))
+                assert float(np.abs(stats[:, 2] - r["H"]).max() / np.log(cfg.vocab)) <= stat_tol
+                if steps % check_cache_every == 0 or sts[b].done:
+                    for l in range(cfg.n_layers):
+                        for name, which, oc in (("K", ec.EC_DBG_KCACHE, sts[b].Kc),
+                                                ("V", ec.EC_DBG_VCACHE, sts[b].Vc)):
+                            c = g.debug_read(which, l, seq=b)
+                            e = relerr(bf16_bits_to_f32(c) if c.dtype == np.uint16 else c, oc[l])
+                            worst[name] = max(worst[name], e)
+                            assert e <= tol, f"seq {b} step {r['t']} layer {l}: {name} cache {e:.3e}"
+        for b, st in enumerate(sts):
+            assert np.array_equal(g.debug_read(ec.EC_DBG_X, seq=b), st.x.astype(np.int32))
+            assert np.array_equal(g.debug_read(ec.EC_DBG_MASKED, seq=b).astype(bool), st.masked)
+            hist = np.array([np.iinfo(np.int32).min if h == -np.inf else int(h) for h in st.hist],
+                            dtype=np.int32)
+            assert np.array_equal(g.debug_read(ec.EC_DBG_HIST, seq=b), hist)
+    finally:
+        g.close()
+    return {"steps": steps, "modes": modes, "worst": worst, "finished_early": finished_early}

@@ -10,7 +10,7 @@ import pytest
 import ec_inputs
 import paper_2603_18489_amd as ec
 from oracle import entropycache as eco
-from tests.gpu_harness import run_teacher_forced, relerr
+from tests.gpu_harness import run_teacher_forced, run_teacher_forced_batch, relerr
 
 pytestmark = pytest.mark.gpu
 
@@ -62,6 +62,26 @@ def test_long_context_partial_steps(hq, hkv, hd):
     s = run_teacher_forced(cfg, w, dec, prompt, TOL["bf16"], max_steps=8)
     print(s)
     assert s["modes"][eco.PARTIAL] >= 6
+
+
+@pytest.mark.parametrize("hq,hkv,hd,plens,N,block,k,n,tau,fast", [
+    (4, 4, 64, [40, 100, 7], 40, 16, 2, 2, 3.0, None),      # ragged prompts, mixed modes
+    (4, 2, 128, [70, 9, 33, 150], 36, 32, 3, 1, 2.5, 1),    # GQA; sequence 1 finishes early;
+                                                             # 150 + 36 rows: a many-row sequence
+])
+def test_batched_sequences_match_their_own_oracle_runs(hq, hkv, hd, plens, N, block, k, n, tau, fast):
+    """Sequences of a batch are independent: each must reproduce the oracle run on it alone,
+    whatever modes the others are in and after some of them have finished."""
+    cfg = small_cfg("bf16", hq, hkv, hd, d=hq * hd if hq * hd >= 256 else 256)
+    w = ec_inputs.make_weights(cfg, 13, gain_jitter=0.1)
+    dec = ec_inputs.DecodeCfg(gen_len=N, block=block, k_recent=k, tokens_per_step=n, tau=tau,
+                              batch=len(plens))
+    prompts = [ec_inputs.make_prompt(cfg.vocab, P, 20 + i) for i, P in enumerate(plens)]
+    s = run_teacher_forced_batch(cfg, w, dec, prompts, TOL["bf16"], fast_seq=fast)
+    print(s)
+    assert s["modes"][eco.PARTIAL] >= 1 and s["modes"][eco.FULL] >= len(plens)
+    if fast is not None:
+        assert s["finished_early"] >= 1
 
 
 def test_free_running_generation_matches_oracle_f32():
