@@ -223,7 +223,7 @@ def main():
     gu_full_ms = pf["gateup"] / cfg.n_layers
     gu_flops = 2.0 * T * cfg.d_model * 2 * cfg.d_ffn
     ach_f = gu_flops / (gu_full_ms * 1e-3) / 1e12
-    roofline_full = {"kernel": "gemm_bf16_tiled (gate/up projection, full step)", "bound": "mfma",
+    roofline_full = {"kernel": "gemm_bf16_tiled8 (gate/up projection, full step)", "bound": "mfma",
                      "achieved": ach_f, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": ach_f / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
                      "launch_ms": gu_full_ms, "flops_per_launch": gu_flops}
