@@ -16,7 +16,7 @@ import pytest
 import ec_inputs
 import paper_2603_18489_amd as ec
 from oracle import entropycache as eco
-from tests.gpu_harness import bf16_bits_to_f32, run_teacher_forced
+from tests.gpu_harness import bf16_bits_to_f32, run_teacher_forced, run_teacher_forced_batch
 
 pytestmark = pytest.mark.gpu
 TOL = 2e-2
@@ -65,6 +65,25 @@ def test_long_cot_shape_two_layers():
         eco.enable_f64_cache(False)
     print(s)
     assert s["steps"] == 40
+
+
+@pytest.mark.timeout(900)
+def test_batch_of_ragged_sequences_two_layers():
+    """The many-sequence shape (ragged prompts, one row list per step) on a 2-layer LLaDA twin:
+    every sequence against its own oracle run; free-running modes, so FULL and PARTIAL sequences
+    share steps."""
+    wl = ec_inputs.WORKLOADS["llada8b_l2"]
+    cfg = wl.model.replace(logit_scale=8.0)
+    w = ec_inputs.make_weights(cfg, wl.seed, threads=16)
+    dec = wl.decode.replace(gen_len=64, batch=3)
+    prompts = [ec_inputs.make_prompt(cfg.vocab, P, 40 + i) for i, P in enumerate((300, 77, 160))]
+    eco.enable_f64_cache(True)
+    try:
+        s = run_teacher_forced_batch(cfg, w, dec, prompts, TOL, max_steps=10, check_cache_every=5)
+    finally:
+        eco.enable_f64_cache(False)
+    print(s)
+    assert s["steps"] == 10 and s["modes"][eco.FULL] >= 3 and s["modes"][eco.PARTIAL] >= 3
 
 
 @pytest.mark.timeout(900)
