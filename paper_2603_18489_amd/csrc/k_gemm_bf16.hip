@@ -576,7 +576,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_tiled4_kernel(const u32x4* __re
                                                               GemmEpi e) {
   constexpr int BMT = 2 * WTM, BNT = 2 * WTN, NF = BMT + BNT;  // fragments per k-step
   constexpr int LF = (NF + 3) / 4;                             // fragments loaded per wave
-  static_assert(WTN % 2 == 0, "pair epilogues need an even number of weight tiles per wave");
   __shared__ u32x4 lds[2][NF][64];
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int mt0 = blockIdx.y * BMT, nt0 = blockIdx.x * BNT;
@@ -666,13 +665,16 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+// (Blocks of at most 192 x 192 are meant to run two to a CU: their register use is capped at
+// the 128 VGPRs that allows, which only the epilogues would exceed.)
 template <int EPI, int WM, int WN, int WTM, int WTN, int NSTAGE>
-__global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_tiled8_kernel(
+__global__ __launch_bounds__(WM * WN * 64)
+__attribute__((amdgpu_waves_per_eu(WTM * WTN <= 18 ? 4 : 2, WTM * WTN <= 18 ? 4 : 2)))
+void gemm_bf16_tiled8_kernel(
     const u32x4* __restrict__ Ap, const u32x4* __restrict__ Wp, int total_nt, int KB_all, int MT,
     GemmEpi e) {
   constexpr int NW = WM * WN, BMT = WM * WTM, BNT = WN * WTN, NF = BMT + BNT;
   constexpr int LF = (NF + NW - 1) / NW;  // loads per wave and stage (all waves issue LF)
-  static_assert(WTN % 2 == 0, "pair epilogues need an even number of weight tiles per wave");
   static_assert(LF * (NSTAGE - 1) <= 63, "vmcnt counts at most 63 outstanding loads");
   extern __shared__ u32x4 lds[];  // [NSTAGE][NF][64] + one dump fragment
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -787,19 +789,23 @@ __global__ __launch_bounds__(256) void resid_finish_kernel(GemmEpi e, int ksplit
   }
 }
 
-// Block shapes of the tiled kernel (rows x weight rows, waves) and what one k-step of a block
-// costs on MI355X (us, measured with all 256 CUs busy):
-//   0: 192 x 384, 8 waves   1: 192 x 256, 8 waves   2: 192 x 192   3: 192 x 128   4: 128 x 128
-//   5: 96 x 128 (4 waves each)
-// Eight waves (two per SIMD) overlap one wave's LDS reads and barrier waits with the other's
-// MFMAs, and the wider the block the fewer operand bytes per flop cross the L2, which is what
-// bounds these kernels.  A grid that does not fill the 256 CUs in whole rounds wastes the
-// remainder, so narrow outputs (N = d_model) are also split along K into partial products that
-// a small second kernel sums.
+// Block shapes of the tiled kernels (rows x weight rows) and what one k-step costs on MI355X
+// with all 256 CUs busy (us, measured): alone on its CU, and - for the shapes small enough that
+// two blocks share a CU's LDS and registers - per k-step of such a pair.
+//   8 waves: 0: 192 x 384   1: 192 x 256   2: 192 x 192   3: 192 x 128
+//   4 waves: 4: 192 x 192   5: 192 x 128   6: 128 x 128   7: 96 x 128
+// Two waves per SIMD overlap one wave's LDS reads and barrier waits with the other's MFMAs, four
+// (two 8-wave blocks) do so better still: 512 blocks of 192 x 192 beat 256 of 192 x 384.  The
+// wider the block the fewer operand bytes per flop cross L2 and LDS, which is what bounds these
+// kernels.  A grid that does not fill the 256 CUs in whole rounds wastes the remainder, so
+// narrow outputs (N = d_model) are also split along K into partial products that a small second
+// kernel sums.
 struct TilePick { int tile, ksplit; };
-constexpr int kNumTiles = 6;
-static const int kTileM[kNumTiles] = {12, 12, 12, 12, 8, 6}, kTileN[kNumTiles] = {24, 16, 12, 8, 8, 8};
-static const float kTileUsPerKstep[kNumTiles] = {1.03f, 0.86f, 0.68f, 0.53f, 0.53f, 0.50f};
+constexpr int kNumTiles = 8;
+static const int kTileM[kNumTiles] = {12, 12, 12, 12, 12, 12, 8, 6};
+static const int kTileN[kNumTiles] = {24, 16, 12, 8, 12, 8, 8, 8};
+static const float kTileUsAlone[kNumTiles] = {1.00f, 0.88f, 0.81f, 0.72f, 0.68f, 0.53f, 0.53f, 0.50f};
+static const float kTileUsPair[kNumTiles] = {0.f, 0.f, 0.914f, 0.83f, 0.f, 0.f, 0.f, 0.f};
 
 static TilePick pick_tile(int MT, int total_nt, int KB, int max_ksplit, int M, int N) {
   TilePick best{1, 1};
@@ -807,9 +813,13 @@ static TilePick pick_tile(int MT, int total_nt, int KB, int max_ksplit, int M, i
   for (int i = 0; i < kNumTiles; ++i) {
     long gm = (MT + kTileM[i] - 1) / kTileM[i], gn = (total_nt + kTileN[i] - 1) / kTileN[i];
     for (int ks = 1; ks <= max_ksplit; ++ks) {
-      long blocks = gm * gn * ks, rounds = (blocks + 255) / 256;
-      float ksteps = (float)((KB + ks - 1) / ks);
-      float t = rounds * (ksteps * kTileUsPerKstep[i] + 3.0f);
+      // the paired shapes only pay with the plain store epilogue of a K split: capped at 128
+      // registers, the fused epilogues spill and eat the gain (measured on gate/up)
+      if (kTileUsPair[i] > 0.f && ks == 1) continue;
+      const long blocks = gm * gn * ks, per_cu = (blocks + 255) / 256;
+      const float ksteps = (float)((KB + ks - 1) / ks);
+      const long pairs = kTileUsPair[i] > 0.f ? per_cu / 2 : 0, singles = per_cu - 2 * pairs;
+      float t = ksteps * (pairs * kTileUsPair[i] + singles * kTileUsAlone[i]) + 3.0f * per_cu;
       if (ks > 1) t += 2.5f + (float)M * N * (ks + 4) * 4.0f / 5.0e6f;  // finish kernel
       if (t < best_t) { best_t = t; best = TilePick{i, ks}; }
     }
@@ -823,9 +833,11 @@ static void launch_tiled_pick(const bf16_t* Ap, int MT, const bf16_t* Wp, int to
   switch (tile) {
     case 0: launch_tiled8_t<EPI, 2, 4, 6, 6, 3>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
     case 1: launch_tiled8_t<EPI, 2, 4, 6, 4, 3>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
-    case 2: launch_tiled4_t<EPI, 6, 6>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
-    case 3: launch_tiled4_t<EPI, 6, 4>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
-    case 4: launch_tiled4_t<EPI, 4, 4>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
+    case 2: launch_tiled8_t<EPI, 2, 4, 6, 3, 3>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
+    case 3: launch_tiled8_t<EPI, 2, 4, 6, 2, 3>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
+    case 4: launch_tiled4_t<EPI, 6, 6>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
+    case 5: launch_tiled4_t<EPI, 6, 4>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
+    case 6: launch_tiled4_t<EPI, 4, 4>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
     default: launch_tiled4_t<EPI, 3, 4>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
   }
 }
