@@ -368,7 +368,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_shared_kernel(
   for (int sg = 0; sg < NSTAGE - 1; ++sg) issue(sg);
   for (int c = 0; c < nchunks; ++c) {
     attn_wait_vmcnt<LF*(NSTAGE - 2)>();  // this wave's loads of chunk c have landed
-    __syncthreads();                     // ... everyone's have; the stage read last is free
+    block_barrier_nofence();             // ... everyone's have; the stage read last is free
     issue(c + NSTAGE - 1);
     const au32x4* st = ring + (size_t)(c % NSTAGE) * NFRAG * 64 + lane;
     bf16x8 kf[2][HB], vf[HT];

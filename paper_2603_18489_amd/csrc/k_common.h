@@ -34,6 +34,14 @@ __device__ __forceinline__ uint32_t pack2_bf16(float a, float b) {
   return c.u;
 }
 
+// Block barrier without the memory fence of __syncthreads().  That fence waits for every
+// outstanding global->LDS load of the wave (vmcnt(0)), which serialises a ring of such loads;
+// here the caller waits for exactly the loads it needs (s_waitcnt vmcnt(N)) beforehand.  The
+// wave's own LDS reads and writes are complete on return (lgkmcnt(0)).
+__device__ __forceinline__ void block_barrier_nofence() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // value held by the lane 32 positions away (one v_permlane32_swap, no LDS traffic)
 __device__ __forceinline__ float other_half(float x) {
   const unsigned u = __float_as_uint(x);

@@ -665,17 +665,25 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-// (Blocks of at most 192 x 192 are meant to run two to a CU: their register use is capped at
-// the 128 VGPRs that allows, which only the epilogues would exceed.)
-template <int EPI, int WM, int WN, int WTM, int WTN, int NSTAGE>
+// (With the plain store epilogue of a K split, blocks of at most 192 x 192 fit two to a CU: the
+// register count is pinned to the 128 VGPRs that allows.  The fused epilogues need more.)
+// PIPE: the fragments of k-step k+1 are read from LDS into a second register set while the
+// MFMAs of k-step k run.  Without it every k-step is a burst of LDS reads (all waves at once,
+// right after the barrier, matrix cores idle) followed by a burst of MFMAs.
+template <int EPI, int WM, int WN, int WTM, int WTN>
+constexpr int tiled8_waves_per_eu() {
+  return WM * WN == 4 ? 1 : (EPI == EPI_PARTIAL && WTM * WTN <= 18 ? 4 : 2);
+}
+template <int EPI, int WM, int WN, int WTM, int WTN, int NSTAGE, bool PIPE = false>
 __global__ __launch_bounds__(WM * WN * 64)
-__attribute__((amdgpu_waves_per_eu(WTM * WTN <= 18 ? 4 : 2, WTM * WTN <= 18 ? 4 : 2)))
+__attribute__((amdgpu_waves_per_eu(tiled8_waves_per_eu<EPI, WM, WN, WTM, WTN>(),
+                                   tiled8_waves_per_eu<EPI, WM, WN, WTM, WTN>())))
 void gemm_bf16_tiled8_kernel(
     const u32x4* __restrict__ Ap, const u32x4* __restrict__ Wp, int total_nt, int KB_all, int MT,
     GemmEpi e) {
   constexpr int NW = WM * WN, BMT = WM * WTM, BNT = WN * WTN, NF = BMT + BNT;
   constexpr int LF = (NF + NW - 1) / NW;  // loads per wave and stage (all waves issue LF)
-  static_assert(LF * (NSTAGE - 1) <= 63, "vmcnt counts at most 63 outstanding loads");
+  static_assert(LF * NSTAGE <= 63, "vmcnt counts at most 63 outstanding loads");
   extern __shared__ u32x4 lds[];  // [NSTAGE][NF][64] + one dump fragment
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int mt0 = blockIdx.y * BMT, nt0 = blockIdx.x * BNT;
@@ -727,36 +735,87 @@ void gemm_bf16_tiled8_kernel(
 #pragma unroll
     for (int j = 0; j < WTM; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
+  if constexpr (!PIPE) {
 #pragma unroll
-  for (int sgl = 0; sgl < NSTAGE - 1; ++sgl) issue(sgl);
-  for (int kb = 0; kb < KB; ++kb) {
-    // this wave's loads of k-step kb have landed once at most LF*(NSTAGE-2) newer ones remain
-    wait_vmcnt<LF*(NSTAGE - 2)>();
-    __syncthreads();  // ... and so have everyone else's; the stage read last iteration is free
-    issue(kb + NSTAGE - 1);
-    const u32x4* st = lds + (size_t)(kb % NSTAGE) * NF * 64;
-    bf16x8 af[WTM], wf[WTN];
+    for (int sgl = 0; sgl < NSTAGE - 1; ++sgl) issue(sgl);
+    for (int kb = 0; kb < KB; ++kb) {
+      // this wave's loads of k-step kb have landed once at most LF*(NSTAGE-2) newer ones remain
+      wait_vmcnt<LF*(NSTAGE - 2)>();
+      block_barrier_nofence();  // ... and so have everyone else's; the stage read last iteration is free
+      issue(kb + NSTAGE - 1);
+      const u32x4* st = lds + (size_t)(kb % NSTAGE) * NF * 64;
+      bf16x8 af[WTM], wf[WTN];
 #pragma unroll
-    for (int j = 0; j < WTM; ++j) af[j] = v4_as_bf16x8(st[(wm * WTM + j) * 64 + lane]);
+      for (int j = 0; j < WTM; ++j) af[j] = v4_as_bf16x8(st[(wm * WTM + j) * 64 + lane]);
 #pragma unroll
-    for (int i = 0; i < WTN; ++i) wf[i] = v4_as_bf16x8(st[(BMT + wn * WTN + i) * 64 + lane]);
+      for (int i = 0; i < WTN; ++i) wf[i] = v4_as_bf16x8(st[(BMT + wn * WTN + i) * 64 + lane]);
 #pragma unroll
-    for (int i = 0; i < WTN; ++i)
+      for (int i = 0; i < WTN; ++i)
 #pragma unroll
-      for (int j = 0; j < WTM; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[i], af[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < WTM; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[i], af[j], acc[i][j], 0, 0, 0);
+    }
+  } else {
+    // All NSTAGE slots are kept in flight.  Step k: this wave has finished reading slot k (its
+    // fragments sit in one register set) and its loads of k-step k+1 have landed; after the
+    // barrier that holds for every wave, so slot k is refilled with k-step k + NSTAGE, the
+    // fragments of k+1 go to the other register set, and the MFMAs of k run over those reads.
+    bf16x8 afa[WTM], wfa[WTN], afb[WTM], wfb[WTN];
+#define EC_T8_READ(AF, WF, KB_)                                                              \
+  {                                                                                          \
+    const u32x4* st_ = lds + (size_t)((KB_) % NSTAGE) * NF * 64;                             \
+    _Pragma("unroll") for (int j = 0; j < WTM; ++j)                                          \
+        AF[j] = v4_as_bf16x8(st_[(wm * WTM + j) * 64 + lane]);                               \
+    _Pragma("unroll") for (int i = 0; i < WTN; ++i)                                          \
+        WF[i] = v4_as_bf16x8(st_[(BMT + wn * WTN + i) * 64 + lane]);                         \
+  }
+#define EC_T8_MMA(AF, WF)                                                                    \
+  _Pragma("unroll") for (int i = 0; i < WTN; ++i)                                            \
+    _Pragma("unroll") for (int j = 0; j < WTM; ++j)                                          \
+      acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(WF[i], AF[j], acc[i][j], 0, 0, 0);
+#define EC_T8_STEP(AF, WF, AFN, WFN, KB_)                                                    \
+  {                                                                                          \
+    wait_vmcnt<LF*(NSTAGE - 2)>();  /* own loads of KB_+1 have landed */                     \
+    block_barrier_nofence();        /* and slot KB_ is in registers, for every wave */       \
+    issue((KB_) + NSTAGE);                                                                   \
+    EC_T8_READ(AFN, WFN, (KB_) + 1)                                                          \
+    __builtin_amdgcn_sched_barrier(0);                                                       \
+    EC_T8_MMA(AF, WF)                                                                        \
+    __builtin_amdgcn_sched_barrier(0);                                                       \
+  }
+#pragma unroll
+    for (int sgl = 0; sgl < NSTAGE; ++sgl) issue(sgl);
+    wait_vmcnt<LF*(NSTAGE - 1)>();
+    block_barrier_nofence();
+    EC_T8_READ(afa, wfa, 0)
+    for (int kb = 0; kb < KB; kb += 2) {
+      EC_T8_STEP(afa, wfa, afb, wfb, kb)
+      // an odd trip count runs one surplus step on a clamped (repeated) k-step: its activation
+      // fragments are zeroed so that it adds nothing
+      if (kb + 1 >= KB) {
+#pragma unroll
+        for (int j = 0; j < WTM; ++j) afb[j] = v4_as_bf16x8((u32x4){0u, 0u, 0u, 0u});
+      }
+      EC_T8_STEP(afb, wfb, afa, wfa, kb + 1)
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#undef EC_T8_STEP
+#undef EC_T8_MMA
+#undef EC_T8_READ
   }
   wait_vmcnt<0>();  // drain the clamped tail loads before the LDS goes away
 
-  tiled_epilogue<EPI, WTM, WTN, false>(e, acc, mt0 + wm * WTM, nt0 + wn * WTN, total_nt, lane, blockIdx.z);
+  // (the read-ahead QKV epilogue needs registers that only the smaller wave tiles leave free)
+  tiled_epilogue<EPI, WTM, WTN, (WTM * WTN <= 18)>(e, acc, mt0 + wm * WTM, nt0 + wn * WTN, total_nt, lane,
+                                                   blockIdx.z);
 }
 
-template <int EPI, int WM, int WN, int WTM, int WTN, int NSTAGE>
+template <int EPI, int WM, int WN, int WTM, int WTN, int NSTAGE, bool PIPE = false>
 static void launch_tiled8_t(const bf16_t* Ap, int MT, const bf16_t* Wp, int total_nt, int KB,
                             const GemmEpi& e, hipStream_t s, int ksplit) {
   constexpr int NF = WM * WTM + WN * WTN;
   const size_t smem = ((size_t)NSTAGE * NF + 1) * 1024;
-  auto kern = gemm_bf16_tiled8_kernel<EPI, WM, WN, WTM, WTN, NSTAGE>;
+  auto kern = gemm_bf16_tiled8_kernel<EPI, WM, WN, WTM, WTN, NSTAGE, PIPE>;
   static bool attr_set = false;
   if (!attr_set && smem > 48 * 1024) {
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -795,17 +854,17 @@ __global__ __launch_bounds__(256) void resid_finish_kernel(GemmEpi e, int ksplit
 //   8 waves: 0: 192 x 384   1: 192 x 256   2: 192 x 192   3: 192 x 128
 //   4 waves: 4: 192 x 192   5: 192 x 128   6: 128 x 128   7: 96 x 128
 // Two waves per SIMD overlap one wave's LDS reads and barrier waits with the other's MFMAs, four
-// (two 8-wave blocks) do so better still: 512 blocks of 192 x 192 beat 256 of 192 x 384.  The
-// wider the block the fewer operand bytes per flop cross L2 and LDS, which is what bounds these
-// kernels.  A grid that does not fill the 256 CUs in whole rounds wastes the remainder, so
-// narrow outputs (N = d_model) are also split along K into partial products that a small second
-// kernel sums.
+// (two 8-wave blocks) do so better still.  The wider the block the fewer operand bytes per flop
+// cross L2 and LDS.  A grid that does not fill the 256 CUs in whole rounds wastes the
+// remainder, so narrow outputs (N = d_model) are also split along K into partial products that
+// a small second kernel sums.  Two blocks to a CU need the 128-register kernels, which only the
+// plain store epilogue of a K split fits.
 struct TilePick { int tile, ksplit; };
 constexpr int kNumTiles = 8;
 static const int kTileM[kNumTiles] = {12, 12, 12, 12, 12, 12, 8, 6};
 static const int kTileN[kNumTiles] = {24, 16, 12, 8, 12, 8, 8, 8};
-static const float kTileUsAlone[kNumTiles] = {1.00f, 0.88f, 0.81f, 0.72f, 0.68f, 0.53f, 0.53f, 0.50f};
-static const float kTileUsPair[kNumTiles] = {0.f, 0.f, 0.914f, 0.83f, 0.f, 0.f, 0.f, 0.f};
+static const float kTileUsAlone[kNumTiles] = {0.98f, 0.71f, 0.54f, 0.46f, 0.64f, 0.55f, 0.53f, 0.41f};
+static const float kTileUsPair[kNumTiles] = {0.f, 0.f, 0.90f, 0.75f, 0.f, 0.f, 0.f, 0.f};
 
 static TilePick pick_tile(int MT, int total_nt, int KB, int max_ksplit, int M, int N) {
   TilePick best{1, 1};
@@ -813,13 +872,11 @@ static TilePick pick_tile(int MT, int total_nt, int KB, int max_ksplit, int M, i
   for (int i = 0; i < kNumTiles; ++i) {
     long gm = (MT + kTileM[i] - 1) / kTileM[i], gn = (total_nt + kTileN[i] - 1) / kTileN[i];
     for (int ks = 1; ks <= max_ksplit; ++ks) {
-      // the paired shapes only pay with the plain store epilogue of a K split: capped at 128
-      // registers, the fused epilogues spill and eat the gain (measured on gate/up)
-      if (kTileUsPair[i] > 0.f && ks == 1) continue;
       const long blocks = gm * gn * ks, per_cu = (blocks + 255) / 256;
       const float ksteps = (float)((KB + ks - 1) / ks);
-      const long pairs = kTileUsPair[i] > 0.f ? per_cu / 2 : 0, singles = per_cu - 2 * pairs;
-      float t = ksteps * (pairs * kTileUsPair[i] + singles * kTileUsAlone[i]) + 3.0f * per_cu;
+      const long pairs = (kTileUsPair[i] > 0.f && ks > 1) ? per_cu / 2 : 0;
+      const long singles = per_cu - 2 * pairs;
+      float t = ksteps * (pairs * kTileUsPair[i] + singles * kTileUsAlone[i]) + 5.0f * (pairs + singles);
       if (ks > 1) t += 2.5f + (float)M * N * (ks + 4) * 4.0f / 5.0e6f;  // finish kernel
       if (t < best_t) { best_t = t; best = TilePick{i, ks}; }
     }
