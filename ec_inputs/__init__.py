@@ -49,6 +49,8 @@ class DecodeCfg:
     tokens_per_step: int = 1
     tau: float = 1.0
     batch: int = 1
+    conf_threshold: float = 0.0   # > 0: unmask every block row whose confidence exceeds it
+    gate_metric: int = 0          # 0 max entropy, 1 entropy sum, 2 max confidence
 
     def replace(self, **kw) -> "DecodeCfg":
         return dataclasses.replace(self, **kw)

@@ -86,15 +86,27 @@ typedef struct {
 } ec_weights;
 
 /* Decoding parameters: generation length N, block (window) size w, recent-token budget k,
- * tokens unmasked per step n, entropy threshold tau in nats (Algorithm 1 inputs). */
+ * tokens unmasked per step n, entropy threshold tau in nats (Algorithm 1 inputs).
+ *  conf_threshold  0: a step unmasks the n most confident rows of the block.  > 0: confidence-
+ *                  based parallel decoding (the paper's experimental setup uses 0.9): every row
+ *                  whose confidence (maximum probability) exceeds it is unmasked, the n most
+ *                  confident ones in any case, at most EC_MAX_N.
+ *  gate_metric     what is compared with tau over the newly decoded tokens (the paper's
+ *                  ablation "Choice of thresholding variable"): EC_GATE_MAX_ENTROPY (Eq. 1, the
+ *                  method) and EC_GATE_ENTROPY_SUM skip the recomputation when the value is at
+ *                  most tau, EC_GATE_MAX_CONFIDENCE when it is at least tau. */
+enum { EC_GATE_MAX_ENTROPY = 0, EC_GATE_ENTROPY_SUM = 1, EC_GATE_MAX_CONFIDENCE = 2 };
 typedef struct {
   int32_t batch, gen_len, block, k_recent, tokens_per_step;
   float tau;
+  float conf_threshold;
+  int32_t gate_metric;
 } ec_decode_cfg;
 
 /* What one step did.  positions/tokens/entropy/confidence list the step's OWN decode() choice
  * (n_unmasked entries, most confident first); max_entropy is E of that choice (Eq. 1);
- * next_mode is EC_PARTIAL iff max_entropy <= tau.  Under ec_step_forced the caller's tokens are
+ * max_entropy holds the gate value (the maximum entropy unless gate_metric says otherwise);
+ * next_mode is EC_PARTIAL iff it passes the threshold (max entropy: <= tau).  Under ec_step_forced the caller's tokens are
  * committed instead, but these fields still report the step's own choice. */
 typedef struct {
   int32_t n_unmasked;

@@ -45,6 +45,7 @@ from typing import Dict, List, Optional, Sequence
 import numpy as np
 
 FULL, PARTIAL, AUTO = 0, 1, 2
+POS_INF = float("inf")
 NEG_INF = -math.inf
 
 
@@ -247,6 +248,30 @@ def forward_rows(st: OracleState, S: np.ndarray, want_rows: np.ndarray) -> np.nd
     return rmsnorm(h[sel], to_f64(w["final_norm"]), cfg.rms_eps)
 
 
+MAX_TOKENS_PER_STEP = 32   # what one step result of the C ABI can report
+
+
+def gate_value(H_dec, conf_dec, metric: int) -> float:
+    """The quantity compared with tau over the step's newly decoded tokens: 0 = their maximum
+    entropy (Eq. 1, the method's choice), 1 = the sum of their entropies, 2 = their maximum
+    confidence (the two alternatives of the ablation "Choice of thresholding variable").
+    No token decoded: the value that always skips."""
+    if len(H_dec) == 0:
+        return POS_INF if metric == 2 else NEG_INF
+    if metric == 0:
+        return float(max(H_dec))
+    if metric == 1:
+        return float(sum(H_dec))
+    return float(max(conf_dec))
+
+
+def gate_skips(value: float, tau: float, metric: int) -> bool:
+    """Skip the full recomputation iff the step was certain: entropy metrics at most tau (Eq. 1,
+    strict > recomputes); the confidence metric at least tau (reading: the paper does not say
+    which side of the threshold a confidence is compared on; high confidence = certain)."""
+    return value >= tau if metric == 2 else value <= tau
+
+
 def eco_step(st: OracleState, mode: int = AUTO, forced: Optional[dict] = None,
              keep_logits: bool = True, rows_override: Optional[np.ndarray] = None) -> dict:
     """One denoising step.
@@ -296,21 +321,27 @@ def eco_step(st: OracleState, mode: int = AUTO, forced: Optional[dict] = None,
     conf = np.array([s[1] for s in stats])
     H = np.array([s[2] for s in stats])
 
-    # decode(): the min(n, |Mb|) rows with largest confidence; ties -> lowest position
+    # decode(): the min(n, |Mb|) rows with largest confidence; ties -> lowest position.
+    # Confidence-based parallel decoding (experimental setup, threshold 0.9): every row of the
+    # block whose confidence exceeds the threshold is unmasked in the same step, the n most
+    # confident ones in any case; one step reports at most MAX_TOKENS_PER_STEP tokens.
     n = min(dec.tokens_per_step, len(Mb))
+    if dec.conf_threshold > 0:
+        n = min(max(n, int(np.sum(conf > dec.conf_threshold))), MAX_TOKENS_PER_STEP, len(Mb))
     order = sorted(range(len(Mb)), key=lambda i: (-conf[i], Mb[i]))[:n]
     own_pos = [int(Mb[i]) for i in order]
     own_tok = [int(tok[i]) for i in order]
     own_H = [float(H[i]) for i in order]
     own_conf = [float(conf[i]) for i in order]
-    E_own = max(own_H)
+    E_own = gate_value(own_H, own_conf, dec.gate_metric)
 
     if forced is not None:
         D_pos = [int(p) for p in forced["positions"]]
         D_tok = [int(v) for v in forced["tokens"]]
         rowof = {int(p): i for i, p in enumerate(Mb)}
-        # the maximum over an empty commit is -inf: nothing new entered the sequence
-        E = (max((float(H[rowof[p]]) for p in D_pos), default=NEG_INF)
+        # an empty commit never asks for a recomputation: nothing new entered the sequence
+        E = (gate_value([float(H[rowof[p]]) for p in D_pos], [float(conf[rowof[p]]) for p in D_pos],
+                        dec.gate_metric)
              if all(p in rowof for p in D_pos) else E_own)
     else:
         D_pos, D_tok, E = own_pos, own_tok, E_own
@@ -323,7 +354,7 @@ def eco_step(st: OracleState, mode: int = AUTO, forced: Optional[dict] = None,
     Ri = recent_set(st.hist, dec.k_recent, t, dt_eff)                    # Eq. 3, tau_R, R
     st.R = [st.P + i for i in Ri]
 
-    if E <= dec.tau:
+    if gate_skips(E, dec.tau, dec.gate_metric):
         st.skip = True
         st.dt = st.dt + 1
     else:

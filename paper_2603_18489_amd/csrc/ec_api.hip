@@ -171,6 +171,10 @@ const char* check_config(const ec_model_cfg* m, const ec_decode_cfg* d, const in
     return "tokens_per_step must be in [1, EC_MAX_N]";
   if (d->k_recent < 0) return "k_recent must be >= 0";
   if (!(d->tau == d->tau)) return "tau is NaN";
+  if (!(d->conf_threshold >= 0.f) || d->conf_threshold >= 1.f)
+    return "conf_threshold must be in [0, 1)";
+  if (d->gate_metric < EC_GATE_MAX_ENTROPY || d->gate_metric > EC_GATE_MAX_CONFIDENCE)
+    return "unknown gate_metric";
   long total = 0;
   for (int b = 0; b < d->batch; ++b) {
     if (prompt_lens[b] < 0) return "negative prompt length";
@@ -268,6 +272,7 @@ void fill_decide_args(ec_ctx* c, DecideArgs& a) {
   a.row_stats = c->b.row_stats; a.out = c->b.out;
   a.N = c->N; a.block = c->d.block; a.k_recent = c->d.k_recent;
   a.n_tok = c->d.tokens_per_step; a.tau = c->d.tau;
+  a.conf_threshold = c->d.conf_threshold; a.gate_metric = c->d.gate_metric;
 }
 
 // static part of a sequence's descriptor

@@ -75,6 +75,8 @@ struct DecideArgs {
   // configuration
   int P, N, T, block, k_recent, n_tok;
   float tau;
+  float conf_threshold;    // 0 = fixed n_tok per step
+  int gate_metric;         // EC_GATE_*
 };
 
 // ---- launchers (each enqueues on `s`; shapes are validated by the caller) --------------------

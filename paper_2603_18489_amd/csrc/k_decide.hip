@@ -121,6 +121,22 @@ __device__ __forceinline__ int block_excl_scan_flag(int flag, int* scratch, int*
   return off + pre;
 }
 
+// The quantity the threshold is applied to, accumulated over the newly decoded tokens: their
+// maximum entropy (Eq. 1), the sum of their entropies, or their maximum confidence (the
+// alternatives of the ablation on the thresholding variable).  Empty = the value that skips.
+struct GateAcc { float v; int metric; };
+__device__ __forceinline__ GateAcc gate_init(int metric) {
+  return GateAcc{metric == EC_GATE_MAX_CONFIDENCE ? INFINITY : -INFINITY, metric};
+}
+__device__ __forceinline__ void gate_add(GateAcc& g, float H, float conf) {
+  if (g.metric == EC_GATE_ENTROPY_SUM) g.v = (g.v == -INFINITY) ? H : g.v + H;
+  else if (g.metric == EC_GATE_MAX_CONFIDENCE) g.v = (g.v == INFINITY) ? conf : fmaxf(g.v, conf);
+  else g.v = fmaxf(g.v, H);
+}
+__device__ __forceinline__ bool gate_skips(float v, float tau, int metric) {
+  return metric == EC_GATE_MAX_CONFIDENCE ? v >= tau : v <= tau;
+}
+
 // ---------------------------------------------------------------------------------------------
 // decide: one block of 256 threads per sequence.
 // ---------------------------------------------------------------------------------------------
@@ -174,7 +190,14 @@ __global__ __launch_bounds__(256) void decide_kernel(DecideArgs a) {
     if (tid == 0) {
       ec_step_result& R = a.out->r;
       int n = min(a.n_tok, a.n_mb);
-      float E_own = -INFINITY;
+      if (a.conf_threshold > 0.f) {
+        // confidence-based parallel decoding: every row above the threshold, the n most
+        // confident ones in any case, no more than one result can report
+        int above = 0;
+        for (int r = 0; r < a.n_mb; ++r) above += (s_conf[r] > a.conf_threshold);
+        n = min(min(max(n, above), EC_MAX_N), a.n_mb);
+      }
+      GateAcc own = gate_init(a.gate_metric);
       for (int i = 0; i < n; ++i) {
         int best = -1;
         for (int r = 0; r < a.n_mb; ++r)
@@ -184,8 +207,9 @@ __global__ __launch_bounds__(256) void decide_kernel(DecideArgs a) {
         R.tokens[i] = s_tok[best];
         R.entropy[i] = s_H[best];
         R.confidence[i] = s_conf[best];
-        E_own = fmaxf(E_own, s_H[best]);
+        gate_add(own, s_H[best], s_conf[best]);
       }
+      const float E_own = own.v;
       for (int i = n; i < EC_MAX_N; ++i) {
         R.positions[i] = -1; R.tokens[i] = -1; R.entropy[i] = 0.f; R.confidence[i] = 0.f;
       }
@@ -195,17 +219,17 @@ __global__ __launch_bounds__(256) void decide_kernel(DecideArgs a) {
       float E = E_own;
       if (a.forced_n >= 0) {
         bool all_in_block = true;
-        float Ef = -INFINITY;
+        GateAcc fa = gate_init(a.gate_metric);
         for (int i = 0; i < a.forced_n; ++i) {
           int p = a.forced_pos[i], row = -1;
           for (int r = 0; r < a.n_mb; ++r)
             if (a.mb_pos[r] == p) row = r;
-          if (row < 0) all_in_block = false; else Ef = fmaxf(Ef, s_H[row]);
+          if (row < 0) all_in_block = false; else gate_add(fa, s_H[row], s_conf[row]);
           a.x[p] = a.forced_tok[i];
           a.masked[p] = 0;
           a.hist[p - P] = t;                              // Eq. 2
         }
-        if (all_in_block) E = Ef;                         // max over an empty set = -inf
+        if (all_in_block) E = fa.v;                       // nothing committed: always skips
       } else {
         for (int i = 0; i < n; ++i) {
           int p = R.positions[i];
@@ -247,7 +271,7 @@ __global__ __launch_bounds__(256) void decide_kernel(DecideArgs a) {
   // ---- flag for the next step, counters, block advance ---------------------------------------
   if (!a.init_only) {
     float E = sh_f[0];
-    if (E <= a.tau) { st.skip = 1; st.dt += 1; } else { st.skip = 0; st.dt = 0; }
+    if (gate_skips(E, a.tau, a.gate_metric)) { st.skip = 1; st.dt += 1; } else { st.skip = 0; st.dt = 0; }
     st.t_lastfull = t_lastfull;
     st.t = t + 1;
   }
@@ -296,7 +320,7 @@ __global__ __launch_bounds__(256) void decide_kernel(DecideArgs a) {
     if (!a.init_only) {
       o.r.done = st.done;
       o.r.mode_run = a.mode_run;
-      o.r.next_mode = (sh_f[1] <= a.tau) ? EC_PARTIAL : EC_FULL;
+      o.r.next_mode = gate_skips(sh_f[1], a.tau, a.gate_metric) ? EC_PARTIAL : EC_FULL;
       o.r.n_query_rows = a.n_rows_run;
       o.r.step_index = t;
       o.r.n_block_rows = a.n_mb;

@@ -83,13 +83,19 @@ def run_teacher_forced(cfg, w, dec, prompt, tol, max_steps=None, check_cache_eve
             if n > 1:
                 conf_margin_ok = conf_margin_ok and bool(
                     np.all(csort[:n - 1] - csort[1:n] > 8 * stat_tol * csort[:n - 1]))
+            thr = getattr(dec, "conf_threshold", 0.0)
+            if thr > 0:   # the number of tokens depends on which side of the threshold rows fall
+                conf_margin_ok = conf_margin_ok and bool(
+                    np.all(np.abs(r["conf"] - thr) > 8 * stat_tol * np.maximum(r["conf"], thr)))
             chosen_rows = [int(np.where(r["Mb"] == p)[0][0]) for p in r["own_positions"]]
             if conf_margin_ok and all(top2gap[i] > 4 * abs_tol for i in chosen_rows):
                 assert q["positions"] == r["own_positions"], f"step {r['t']}: positions"
                 assert q["tokens"] == r["own_tokens"], f"step {r['t']}: tokens"
                 n_exact_checked += 1
-                if abs(r["E_own"] - dec.tau) > 2 * stat_tol * lnV:
-                    assert q["next_mode"] == (eco.PARTIAL if r["E_own"] <= dec.tau else eco.FULL)
+                if abs(r["E_own"] - dec.tau) > 2 * stat_tol * lnV * max(1, len(r["own_positions"])):
+                    skips = eco.gate_skips(r["E_own"], dec.tau, getattr(dec, "gate_metric", 0))
+                    assert q["next_mode"] == (eco.PARTIAL if skips else eco.FULL)
+                    assert abs(q["max_entropy"] - r["E_own"]) <= 2 * stat_tol * lnV * len(r["own_positions"])
             if check_cache_every and (steps % check_cache_every == 0 or st.done):
                 for l in (range(cfg.n_layers) if cache_layers is None else cache_layers):
                     for name, which, oc in (("K", ec.EC_DBG_KCACHE, st.Kc), ("V", ec.EC_DBG_VCACHE, st.Vc)):

@@ -51,6 +51,27 @@ def test_small_models_whole_generation(dtype, hq, hkv, hd, P, N, block, k, n, ta
     assert s["modes"][eco.PARTIAL] >= 1
 
 
+@pytest.mark.parametrize("dtype,thr,metric,tau,scale", [
+    ("f32", 0.5, ec.EC_GATE_MAX_ENTROPY, 2.5, 13.0),
+    ("f32", 0.35, ec.EC_GATE_ENTROPY_SUM, 4.0, 13.0),
+    ("f32", 0.5, ec.EC_GATE_MAX_CONFIDENCE, 0.3, 13.0),
+    ("bf16", 0.5, ec.EC_GATE_MAX_ENTROPY, 2.5, 13.0),
+    ("bf16", 0.5, ec.EC_GATE_ENTROPY_SUM, 6.0, 13.0),
+])
+def test_confidence_threshold_decoding_and_gate_metrics(dtype, thr, metric, tau, scale):
+    """Confidence-based parallel decoding (several tokens per step, the recent set grows by ties)
+    and the alternative thresholding variables, against the oracle under teacher forcing."""
+    cfg = small_cfg(dtype, 4, 2, 64, scale=scale)
+    w = ec_inputs.make_weights(cfg, 17, gain_jitter=0.1)
+    dec = ec_inputs.DecodeCfg(gen_len=80, block=32, k_recent=4, tokens_per_step=1, tau=tau,
+                              conf_threshold=thr, gate_metric=metric)
+    prompt = ec_inputs.make_prompt(cfg.vocab, 45, 9)
+    s = run_teacher_forced(cfg, w, dec, prompt, TOL[dtype])
+    print(s)
+    assert s["modes"][eco.PARTIAL] >= 1 and s["modes"][eco.FULL] >= 1
+    assert s["steps"] < 80, "no step decoded several tokens: the threshold path did not run"
+
+
 @pytest.mark.parametrize("hq,hkv,hd", [(4, 4, 64), (4, 2, 128)])
 def test_long_context_partial_steps(hq, hkv, hd):
     """More than 2048 keys: the partial-step attention cuts the keys into slices that different
