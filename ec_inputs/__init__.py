@@ -51,6 +51,7 @@ class DecodeCfg:
     batch: int = 1
     conf_threshold: float = 0.0   # > 0: unmask every block row whose confidence exceeds it
     gate_metric: int = 0          # 0 max entropy, 1 entropy sum, 2 max confidence
+    schedule: int = 0             # 0 fixed blocks, 1 sliding window of `block` masked slots
 
     def replace(self, **kw) -> "DecodeCfg":
         return dataclasses.replace(self, **kw)

@@ -94,13 +94,19 @@ typedef struct {
  *  gate_metric     what is compared with tau over the newly decoded tokens (the paper's
  *                  ablation "Choice of thresholding variable"): EC_GATE_MAX_ENTROPY (Eq. 1, the
  *                  method) and EC_GATE_ENTROPY_SUM skip the recomputation when the value is at
- *                  most tau, EC_GATE_MAX_CONFIDENCE when it is at least tau. */
+ *                  most tau, EC_GATE_MAX_CONFIDENCE when it is at least tau.
+ *  schedule        EC_SCHED_BLOCKS: M^t = the masked positions of the current fixed block of
+ *                  `block` generation slots; the next block starts when it is empty.
+ *                  EC_SCHED_SLIDING: sliding-window decoding (the paper's experiments; it gives no
+ *                  advance rule): M^t = the leftmost `block` still-masked generation slots. */
 enum { EC_GATE_MAX_ENTROPY = 0, EC_GATE_ENTROPY_SUM = 1, EC_GATE_MAX_CONFIDENCE = 2 };
+enum { EC_SCHED_BLOCKS = 0, EC_SCHED_SLIDING = 1 };
 typedef struct {
   int32_t batch, gen_len, block, k_recent, tokens_per_step;
   float tau;
   float conf_threshold;
   int32_t gate_metric;
+  int32_t schedule;
 } ec_decode_cfg;
 
 /* What one step did.  positions/tokens/entropy/confidence list the step's OWN decode() choice

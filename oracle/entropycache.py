@@ -212,8 +212,14 @@ def eco_init(model: OracleModel, dec, prompt: np.ndarray) -> OracleState:
 
 
 def current_block_masked(st: OracleState) -> np.ndarray:
-    """Masked positions of the current block (the step's M^t)."""
+    """The step's M^t.  Blockwise decoding: the masked positions of the current fixed block.
+    Sliding-window decoding (the experiments' default, "window size = 32"; the paper states no
+    advance rule - reading: the window always holds the leftmost `block` still-masked
+    generation slots, so it slides on as its positions are decoded)."""
     w = st.dec.block
+    if getattr(st.dec, "schedule", 0) == 1:
+        idx = np.arange(st.P, st.T)
+        return idx[st.masked[st.P:]][:w]
     lo = st.P + st.blk * w
     hi = min(st.T, lo + w)
     idx = np.arange(lo, hi)

@@ -18,6 +18,7 @@ EC_MAX_BATCH = 64
 EC_F32, EC_BF16 = 0, 1
 EC_FULL, EC_PARTIAL, EC_AUTO = 0, 1, 2
 EC_GATE_MAX_ENTROPY, EC_GATE_ENTROPY_SUM, EC_GATE_MAX_CONFIDENCE = 0, 1, 2
+EC_SCHED_BLOCKS, EC_SCHED_SLIDING = 0, 1
 EC_OK, EC_ERR_ARG, EC_ERR_CONFIG, EC_ERR_WORKSPACE, EC_ERR_STATE, EC_ERR_HIP = 0, -1, -2, -3, -4, -5
 (EC_K_EMBED, EC_K_NORM, EC_K_QKV, EC_K_ROPE_KV, EC_K_ATTN, EC_K_OPROJ, EC_K_GATEUP, EC_K_SWIGLU,
  EC_K_DOWN, EC_K_LMHEAD, EC_K_VOCAB_REDUCE, EC_K_DECIDE, EC_K_COUNT) = range(13)
@@ -47,7 +48,8 @@ class ec_weights(C.Structure):
 class ec_decode_cfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("batch", "gen_len", "block", "k_recent",
                                          "tokens_per_step")] + \
-               [("tau", C.c_float), ("conf_threshold", C.c_float), ("gate_metric", C.c_int32)]
+               [("tau", C.c_float), ("conf_threshold", C.c_float), ("gate_metric", C.c_int32),
+                ("schedule", C.c_int32)]
 
 
 class ec_step_result(C.Structure):
@@ -139,7 +141,7 @@ def model_cfg_struct(cfg) -> ec_model_cfg:
 def decode_cfg_struct(dec) -> ec_decode_cfg:
     return ec_decode_cfg(dec.batch, dec.gen_len, dec.block, dec.k_recent, dec.tokens_per_step,
                          dec.tau, getattr(dec, "conf_threshold", 0.0),
-                         getattr(dec, "gate_metric", 0))
+                         getattr(dec, "gate_metric", 0), getattr(dec, "schedule", 0))
 
 
 def _i32(a) -> np.ndarray:

@@ -175,6 +175,7 @@ const char* check_config(const ec_model_cfg* m, const ec_decode_cfg* d, const in
     return "conf_threshold must be in [0, 1)";
   if (d->gate_metric < EC_GATE_MAX_ENTROPY || d->gate_metric > EC_GATE_MAX_CONFIDENCE)
     return "unknown gate_metric";
+  if (d->schedule != EC_SCHED_BLOCKS && d->schedule != EC_SCHED_SLIDING) return "unknown schedule";
   long total = 0;
   for (int b = 0; b < d->batch; ++b) {
     if (prompt_lens[b] < 0) return "negative prompt length";
@@ -273,6 +274,7 @@ void fill_decide_args(ec_ctx* c, DecideArgs& a) {
   a.N = c->N; a.block = c->d.block; a.k_recent = c->d.k_recent;
   a.n_tok = c->d.tokens_per_step; a.tau = c->d.tau;
   a.conf_threshold = c->d.conf_threshold; a.gate_metric = c->d.gate_metric;
+  a.schedule = c->d.schedule;
 }
 
 // static part of a sequence's descriptor

@@ -77,6 +77,7 @@ struct DecideArgs {
   float tau;
   float conf_threshold;    // 0 = fixed n_tok per step
   int gate_metric;         // EC_GATE_*
+  int schedule;            // EC_SCHED_*
 };
 
 // ---- launchers (each enqueues on `s`; shapes are validated by the caller) --------------------

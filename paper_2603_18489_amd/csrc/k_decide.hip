@@ -275,26 +275,37 @@ __global__ __launch_bounds__(256) void decide_kernel(DecideArgs a) {
     st.t_lastfull = t_lastfull;
     st.t = t + 1;
   }
+  const bool sliding = a.schedule == EC_SCHED_SLIDING;
   int blk = st.blk;
-  while (blk < nblocks) {  // uniform: every thread evaluates the same counts
-    int lo = P + blk * a.block, hi = min(T, lo + a.block), c = 0;
-    for (int i = lo + tid; i < hi; i += 256) c += a.masked[i];
-    c = block_sum_int(c, scratch);
-    if (c > 0) break;
-    ++blk;
+  if (!sliding) {
+    while (blk < nblocks) {  // uniform: every thread evaluates the same counts
+      int lo = P + blk * a.block, hi = min(T, lo + a.block), c = 0;
+      for (int i = lo + tid; i < hi; i += 256) c += a.masked[i];
+      c = block_sum_int(c, scratch);
+      if (c > 0) break;
+      ++blk;
+    }
+    st.blk = blk;
+    st.done = (blk >= nblocks);
   }
-  st.blk = blk;
-  st.done = (blk >= nblocks);
 
-  // ---- row lists of the next step: M (block's masked rows) and M u R, ascending -------------
+  // ---- row lists of the next step: M and M u R, ascending ---------------------------------------
+  // M = the masked rows of the current block, or (sliding window) the first `block` masked slots
   int blo = P + blk * a.block, bhi = min(T, blo + a.block);
-  int n_rows = 0, n_mb = 0, n_recent = 0;
+  int n_rows = 0, n_mb = 0, n_recent = 0, masked_seen = 0;
   for (int base = 0; base < N; base += 256) {
     int i = base + tid, pos = P + i;
-    int inM = 0, inR = 0;
+    int inM = 0, inR = 0, msk = 0;
     if (i < N) {
-      inM = (!st.done && pos >= blo && pos < bhi && a.masked[pos]) ? 1 : 0;
+      msk = a.masked[pos] ? 1 : 0;
+      inM = (!sliding && !st.done && pos >= blo && pos < bhi && msk) ? 1 : 0;
       inR = (!a.init_only && a.hist[i] != INT_MIN && a.hist[i] >= tauR) ? 1 : 0;
+    }
+    if (sliding) {
+      int tot_msk;
+      int pre_msk = block_excl_scan_flag(msk, scratch, &tot_msk);
+      inM = (msk && masked_seen + pre_msk < a.block) ? 1 : 0;
+      masked_seen += tot_msk;
     }
     int tot_any, tot_m, tot_r;
     int pre_any = block_excl_scan_flag(inM | inR, scratch, &tot_any);
@@ -309,6 +320,7 @@ __global__ __launch_bounds__(256) void decide_kernel(DecideArgs a) {
     n_mb += tot_m;
     n_recent += tot_r;
   }
+  if (sliding) st.done = (n_mb == 0);
   if (tid == 0) {
     st.n_mb = n_mb;
     st.n_rows_partial = n_rows;

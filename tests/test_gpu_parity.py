@@ -72,6 +72,23 @@ def test_confidence_threshold_decoding_and_gate_metrics(dtype, thr, metric, tau,
     assert s["steps"] < 80, "no step decoded several tokens: the threshold path did not run"
 
 
+@pytest.mark.parametrize("dtype,block,k,n,thr,tau", [
+    ("f32", 16, 3, 2, 0.0, 2.5),      # window slides by two slots a step
+    ("bf16", 32, 4, 1, 0.5, 2.5),     # with confidence-based parallel decoding
+])
+def test_sliding_window_schedule(dtype, block, k, n, thr, tau):
+    """Sliding-window decoding: M^t is the leftmost `block` masked slots, so the row sets differ
+    from the blockwise ones at every step."""
+    cfg = small_cfg(dtype, 4, 2, 64, scale=13.0)
+    w = ec_inputs.make_weights(cfg, 17, gain_jitter=0.1)
+    dec = ec_inputs.DecodeCfg(gen_len=70, block=block, k_recent=k, tokens_per_step=n, tau=tau,
+                              conf_threshold=thr, schedule=ec.EC_SCHED_SLIDING)
+    prompt = ec_inputs.make_prompt(cfg.vocab, 45, 9)
+    s = run_teacher_forced(cfg, w, dec, prompt, TOL[dtype])
+    print(s)
+    assert s["modes"][eco.PARTIAL] >= 1 and s["modes"][eco.FULL] >= 1
+
+
 @pytest.mark.parametrize("hq,hkv,hd", [(4, 4, 64), (4, 2, 128)])
 def test_long_context_partial_steps(hq, hkv, hd):
     """More than 2048 keys: the partial-step attention cuts the keys into slices that different

@@ -81,3 +81,39 @@ def test_entropy_sum_equals_max_entropy_when_one_token_is_decoded_per_step():
     _, b = run(model, prompt, gate_metric=1)
     assert [(r["mode"], r["positions"], r["tokens"], r["E"]) for r in a] == \
            [(r["mode"], r["positions"], r["tokens"], r["E"]) for r in b]
+
+
+def test_sliding_window_limits_and_invariants():
+    """Sliding-window schedule: with a window covering the whole generation it is the single-block
+    schedule; with a window of one it decodes strictly left to right; in between the window
+    always holds min(w, remaining) masked slots and nothing right of it is decoded early."""
+    model, prompt = model_and_prompt()
+    N = 24
+
+    def gen(**kw):
+        d = ec_inputs.DecodeCfg(gen_len=N, k_recent=2, tokens_per_step=1, tau=1.0, **kw)
+        st = eco.eco_init(model, d, prompt)
+        return st, eco.eco_generate(st)
+
+    _, whole_blocks = gen(block=N, schedule=0)
+    _, whole_window = gen(block=N, schedule=1)
+    assert [(r["mode"], r["positions"], r["tokens"]) for r in whole_blocks] == \
+           [(r["mode"], r["positions"], r["tokens"]) for r in whole_window]
+
+    st, one = gen(block=1, schedule=1)
+    assert [r["positions"][0] for r in one] == list(range(st.P, st.P + N))
+
+    st, mid = gen(block=5, schedule=1)
+    remaining = N
+    decoded = set()
+    for r in mid:
+        Mb = [int(p) for p in r["Mb"]]
+        assert len(Mb) == min(5, remaining)
+        # every generation slot left of the window's last position is either in it or decoded
+        for p in range(st.P, Mb[-1] + 1):
+            assert p in Mb or p in decoded
+        decoded.update(r["positions"])
+        remaining -= len(r["positions"])
+    assert remaining == 0 and len(mid) == N
+    # unlike fixed blocks, the window moves before it is empty
+    assert any(r["Mb"][-1] > st.P + 4 and len(r["Mb"]) == 5 for r in mid[:6])
