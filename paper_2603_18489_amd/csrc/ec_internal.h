@@ -37,7 +37,7 @@ struct SeqDesc {
   int n_mb, lm0;    // masked rows of its block; the first of them in the logits buffer
   int forced_n;     // teacher forcing: tokens to commit, -1 = the step's own choice
 };
-constexpr int kSmallRows = 64;
+constexpr int kSmallRows = 96;
 
 // What the decision kernel hands back to the host after each step.
 struct StepOut {

@@ -40,6 +40,7 @@ def test_tiny_f32_whole_generation():
     ("bf16", 4, 4, 64, 64, 64, 32, 2, 1, 3.0),
     ("bf16", 4, 2, 128, 50, 70, 32, 4, 2, 2.5),     # GQA, head_dim 128, 70 = 2 blocks + 6
     ("bf16", 8, 2, 64, 100, 33, 32, 2, 3, 1e9),     # T = 133 > 128 rows: tiled GEMM in FULL
+    ("bf16", 4, 2, 64, 40, 128, 32, 64, 1, 1e9),    # k = 64: partial steps of 65 .. 96 rows
 ])
 def test_small_models_whole_generation(dtype, hq, hkv, hd, P, N, block, k, n, tau):
     cfg = small_cfg(dtype, hq, hkv, hd, d=hq * hd if hq * hd >= 256 else 256)
