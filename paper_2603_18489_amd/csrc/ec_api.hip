@@ -440,7 +440,12 @@ int forward_bf16(ec_ctx* c, const StepPlan& sp) {
     e.sumsq_in = sums(2 * L); e.d_in = d; e.eps = m.rms_eps; e.sum_stride = b.sumsq_stride;
     e.scale = m.logit_scale; e.logits = b.logits; e.ldc = m.vocab;
     e.w_grp = skinny_tiles_per_block(EPI_LOGITS, m.vocab / 16);
-    launch_gemm_bf16(EPI_LOGITS, u, R, b.lm_head_p, m.vocab, d, e, s); }
+    if (sp.n_lm <= 64) {
+      launch_gemm_bf16(EPI_LOGITS, u, R, b.lm_head_p, m.vocab, d, e, s);
+    } else {  // many sequences: gather the rows once, then one pass over the LM head
+      launch_gather_rows_packed(u, R, b.lm_sel, sp.n_lm, d, (bf16_t*)b.u_lm, s);
+      launch_gemm_bf16(EPI_LOGITS, (bf16_t*)b.u_lm, sp.n_lm, b.lm_head_p, m.vocab, d, e, s);
+    } }
   return EC_OK;
 }
 

@@ -164,6 +164,9 @@ void launch_repack_weight(const bf16_t* W, int N, int K, bf16_t* Wp, int mode, i
 // Weight tiles per block the skinny GEMM uses for a matrix of total_nt tiles, which is also the
 // group size its packed layout should have.
 int skinny_tiles_per_block(int epi, int total_nt);
+// dst rows 0..n (padded with zero rows to whole tiles) = src rows sel[0..n), both packed, K wide.
+void launch_gather_rows_packed(const bf16_t* src, int M_src, const int* sel, int n, int K,
+                               bf16_t* dst, hipStream_t s);
 void launch_unpack_cache(const bf16_t* packed, int is_v, int T, int Tpad, int Hkv, int hd,
                          bf16_t* out, hipStream_t s);
 // A: packed activations holding M_src rows; W: packed [N/16 tiles][K/32]; see GemmEpi.

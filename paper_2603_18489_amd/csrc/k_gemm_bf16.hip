@@ -908,7 +908,7 @@ static void launch_epi(const bf16_t* Ap, int M_src, const bf16_t* Wp, int N, int
   // Up to 96 rows (a block of 32 plus the paper's default budget of 64 recent tokens) the GEMMs
   // are weight-streaming: 3.7 ms a step at 64 rows, 4.5 ms at 96, against 7.8 ms through the
   // tiled kernels.
-  if (MT <= 6 && !(EPI == EPI_LOGITS && MT > 4)) {
+  if (MT <= 6 && !(EPI == EPI_LOGITS && MT > 4)) {  // (gathered LM-head rows: 64 at most)
     switch (MT) {
       case 1: launch_skinny_mt<EPI, 1>(Ap, MT_src, Wp, total_nt, KB, e, s); break;
       case 2: launch_skinny_mt<EPI, 2>(Ap, MT_src, Wp, total_nt, KB, e, s); break;
@@ -939,14 +939,10 @@ void launch_gemm_bf16(int epi, const bf16_t* Ap, int M_src, const bf16_t* Wp, in
     case EPI_RESID: launch_epi<EPI_RESID>(Ap, M_src, Wp, N, K, e, s); break;
     case EPI_SWIGLU: launch_epi<EPI_SWIGLU>(Ap, M_src, Wp, N, K, e, s); break;
     default:
-      // gathered rows are only handled by the skinny kernel: more than 64 rows go in chunks
-      for (int r0 = 0; r0 < e.M; r0 += 64) {
-        GemmEpi c = e;
-        c.M = e.M - r0 < 64 ? e.M - r0 : 64;
-        c.row_sel = e.row_sel + r0;
-        c.logits = e.logits + (size_t)r0 * e.ldc;
-        launch_epi<EPI_LOGITS>(Ap, M_src, Wp, N, K, c, s);
-      }
+      // Up to 64 rows the skinny kernel gathers the rows row_sel names out of Ap itself.  More
+      // rows go through the tiled kernels, which read their rows in place: the caller hands
+      // over the gathered rows then (row_sel still names the rows whose 1/rms applies).
+      launch_epi<EPI_LOGITS>(Ap, M_src, Wp, N, K, e, s);
       break;
   }
 }

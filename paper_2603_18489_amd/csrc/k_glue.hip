@@ -232,6 +232,27 @@ void launch_repack_weight(const bf16_t* W, int N, int K, bf16_t* Wp, int mode, i
                                                                        row0);
 }
 
+// Rows sel[0..n) of a packed activation buffer (MT_src m-tiles) -> rows 0..n of another one.
+__global__ __launch_bounds__(256) void gather_rows_packed_kernel(const bf16_t* __restrict__ src,
+                                                                 int MT_src, const int* __restrict__ sel,
+                                                                 int n, int K, bf16_t* __restrict__ dst,
+                                                                 int MT_dst) {
+  const int r = blockIdx.x;  // destination row, < MT_dst * 16
+  const int from = r < n ? sel[r] : -1;
+  for (int k8 = threadIdx.x * 8; k8 < K; k8 += 256 * 8) {
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (from >= 0) v = *(const uint4*)(src + packed_act_index(from, k8, MT_src));
+    *(uint4*)(dst + packed_act_index(r, k8, MT_dst)) = v;
+  }
+}
+
+void launch_gather_rows_packed(const bf16_t* src, int M_src, const int* sel, int n, int K,
+                               bf16_t* dst, hipStream_t s) {
+  if (n <= 0) return;
+  const int MT_dst = (n + 15) / 16;
+  gather_rows_packed_kernel<<<MT_dst * 16, 256, 0, s>>>(src, (M_src + 15) / 16, sel, n, K, dst, MT_dst);
+}
+
 // packed cache of one layer -> row-major [T, Hkv*hd]
 __global__ __launch_bounds__(256) void unpack_cache_kernel(const bf16_t* __restrict__ packed,
                                                            int is_v, int T, int Tpad, int Hkv,
