@@ -97,6 +97,87 @@ def calibrate_logit_scale(make_ctx, prompt, target_lo=0.08, target_hi=0.16):
     return best
 
 
+def bench_batch(args, wl, cfg, dec, dw):
+    """Many sequences side by side (decode.batch > 1): prompt b has prompt_len - 32 b ids.
+    Timed: K free-running steps of the whole batch; then the all-PARTIAL steady state and the
+    all-FULL step, forced.  One JSON line like the single-sequence run's, without the CPU leg."""
+    import torch
+    import ec_inputs
+    import paper_2603_18489_amd as ec
+    B = dec.batch
+    plens = [wl.prompt_len - 32 * b for b in range(B)]
+    prompts = [ec_inputs.make_prompt(cfg.vocab, P, wl.seed + 1000 + b) for b, P in enumerate(plens)]
+    scale = args.logit_scale if args.logit_scale > 0 else 8.0
+    g = ec.EntropyCache(cfg.replace(logit_scale=scale), dw, dec, prompts)
+
+    def steps_timed(mode_fn, n, reset=True):
+        if reset:
+            g.reset(prompts)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        toks = full = part = 0
+        for i in range(n):
+            rs = g.step(mode_fn(i))
+            for r in rs:
+                if r["n_query_rows"] > 0:
+                    toks += r["n_unmasked"]
+                    full += int(r["mode_run"] == ec.EC_FULL)
+                    part += int(r["mode_run"] == ec.EC_PARTIAL)
+            if all(r["done"] for r in rs):
+                break
+        torch.cuda.synchronize()
+        return i + 1, toks, full, part, time.perf_counter() - t0
+
+    steps_timed(lambda i: ec.EC_AUTO, args.warmup)
+    steps, toks, full, part, secs = steps_timed(lambda i: ec.EC_AUTO, args.steps)
+    _, _, _, _, t_f = steps_timed(lambda i: ec.EC_FULL, 3)
+    n_p, tok_p, _, _, t_p = steps_timed(lambda i: ec.EC_FULL if i == 0 else ec.EC_PARTIAL, 25)
+    full_ms = t_f / 3 * 1e3
+    partial_ms = (t_p - full_ms / 1e3) / (n_p - 1) * 1e3
+    g.reset(prompts)
+    g.step(ec.EC_FULL)
+    g.profile_enable(True)
+    for _ in range(8):
+        g.step(ec.EC_PARTIAL)
+    prof = g.profile_read()
+    g.profile_enable(False)
+    pp = {k: v / prof["steps"] for k, v in prof["ms"].items()}
+    R = sum((34 + 15) // 16 * 16 for _ in range(B))             # rows of the partial step's list
+    gu_ms = pp["gateup"] / cfg.n_layers
+    gu_flops = 2.0 * R * cfg.d_model * 2 * cfg.d_ffn
+    ach = gu_flops / (gu_ms * 1e-3) / 1e12
+    T_tot = sum(P + dec.gen_len for P in plens)
+    kv_bytes = 2.0 * T_tot * cfg.n_kv_heads * cfg.head_dim * 2 * cfg.n_layers
+    step_bytes = ec_inputs.weight_bytes(cfg) + kv_bytes          # weights once + every cache once
+    g.close()
+    out = {
+        "metric": "generated tokens per second, EntropyCache denoising, 16 sequences (LLaDA-8B shape)",
+        "value": toks / secs, "unit": "tok/s", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
+        "ms_per_step": secs / steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name}: L{cfg.n_layers} d{cfg.d_model} {cfg.n_heads}q/"
+                               f"{cfg.n_kv_heads}kv x{cfg.head_dim} F{cfg.d_ffn} V{cfg.vocab}, "
+                               f"{B} sequences, prompts {plens[0]}..{plens[-1]}, gen {dec.gen_len}, "
+                               f"block {dec.block}, n={dec.tokens_per_step}, k={dec.k_recent}, "
+                               f"tau={dec.tau}",
+                   "schedule": "free-running EC_AUTO", "logit_scale": scale,
+                   "sequence_steps_full": full, "sequence_steps_partial": part},
+        "all_partial_step": {"ms": partial_ms, "tok_per_s": B * dec.tokens_per_step / partial_ms * 1e3,
+                             "list_rows": R, "algorithmic_GB": step_bytes / 1e9,
+                             "hbm_frac": step_bytes / (partial_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "all_full_step": {"ms": full_ms, "rows": T_tot,
+                          "tflops": sum(full_step_flops(cfg, P + dec.gen_len, dec.block)
+                                        for P in plens) / (full_ms * 1e-3) / 1e12},
+        "kernel_ms_partial_step": pp,
+        "roofline": {"kernel": "tiled GEMM (gate/up projection, all-partial step of the batch)",
+                     "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "launch_ms": gu_ms, "flops_per_launch": gu_flops},
+        "cpu_baseline": None,
+    }
+    print(json.dumps(out))
+
+
 def cpu_oracle_baseline(cfg, w, dec, prompt, n_full, n_partial, n_tok):
     """Times the fp64 oracle on 2- and 4-layer prefixes of the model (one FULL and one PARTIAL
     step each) and extrapolates linearly in depth to the full model and the same mode schedule."""
@@ -162,6 +243,10 @@ def main():
     dw = ec.weights_to_device(cfg, w)
     torch.cuda.synchronize()
     log(f"[bench] weights uploaded in {time.perf_counter() - t0:.1f}s")
+
+    if dec.batch > 1:
+        del w
+        return bench_batch(args, wl, cfg, dec, dw)
 
     if args.calib_copy_mb > 0:
         src = torch.ones(args.calib_copy_mb << 18, dtype=torch.float32, device="cuda")

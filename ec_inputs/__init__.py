@@ -97,6 +97,11 @@ WORKLOADS: Dict[str, Workload] = {
     "llada8b_cot": Workload("llada8b_cot", _llada(),
                             DecodeCfg(gen_len=1024, block=32, k_recent=4, tokens_per_step=1,
                                       tau=0.5), 256, 2),
+    # 16 sequences side by side on the LLaDA-8B model, prompts 1024, 992, ... (ragged), 512
+    # generated tokens each: partial steps of 16 x (<= 34) rows, full steps of up to 24 576 rows
+    "llada8b_b16": Workload("llada8b_b16", _llada(),
+                            DecodeCfg(gen_len=512, block=32, k_recent=2, tokens_per_step=1,
+                                      tau=1.0, batch=16), 1024, 2),
     # reduced-depth twins (same widths and vocabulary, 2 layers) for whole-generation parity
     "llada8b_l2": Workload("llada8b_l2", _llada(n_layers=2),
                            DecodeCfg(gen_len=256, block=32, k_recent=2, tokens_per_step=1,
