@@ -402,7 +402,13 @@ __device__ __forceinline__ void tiled_epilogue_qkv(const GemmEpi& e, f32x4 (&acc
     head[i] = t / tph;
     w[i] = t - head[i] * tph;
   }
-  int pos[WTM], kvoff[WTM], tpad[WTM];
+  // Addresses split into a row part (per m-tile j) and a column part (per weight tile i): the
+  // cache index functions are sums of a function of the key and a function of the column.
+  //   q:  row m * Hq*hd            + head*hd + col
+  //   K:  slab(head) + K(key)      + C(col)       (k_common.h: kcache_index)
+  //   V:  slab(head) + Vk(key)     + w * Vs + (q4*4 + r) * 8,  Vs = keys/32 * 512 per hd tile
+  int pos[WTM], krow[WTM], vrow[WTM], vstep[WTM], slab[WTM];
+  size_t qrow[WTM];
   float rs[WTM];
   bool mvalid[WTM];
 #pragma unroll
@@ -412,10 +418,21 @@ __device__ __forceinline__ void tiled_epilogue_qkv(const GemmEpi& e, f32x4 (&acc
     const int4 ri = e.rowinfo[mm];
     mvalid[j] = m < e.M && ri.x >= 0;  // not a padding row
     pos[j] = ri.x >= 0 ? ri.x : 0;
-    kvoff[j] = ri.z;
-    tpad[j] = ri.w;
+    qrow[j] = (size_t)mm * (e.Hq * hd);
+    krow[j] = ri.z + (int)kcache_index(pos[j], 0, hd);
+    vrow[j] = ri.z + (int)vcache_index(pos[j], 0, ri.w);
+    vstep[j] = (ri.w >> 5) * 512;
+    slab[j] = ri.w * hd;  // elements per kv head
     rs[j] = rstd_of(e, mm);
   }
+  const int colq = (q4 & 1) * 4 + (hi ? half : 0);  // the lane's first column within a head, tile 0
+  int qcol[WTN], kcol[WTN];
+#pragma unroll
+  for (int i = 0; i < WTN; ++i) {
+    qcol[i] = head[i] * hd + w[i] * 8 + colq;
+    kcol[i] = (int)kcache_index(0, w[i] * 8 + colq, hd);
+  }
+  const unsigned sin_sign = hi ? 0u : 0x80000000u;  // first half: x cos - y sin; second: x cos + y sin
   float4 ca[WTN][2], cb[WTN][2];  // (cos, sin) x 4 columns for each rotary tile of one m-tile
 #define EC_QKV_LOADC(C, J)                                                                   \
   _Pragma("unroll") for (int i = 0; i < WTN; ++i) if (kind[i] < 2) {                           \
@@ -426,31 +443,27 @@ __device__ __forceinline__ void tiled_epilogue_qkv(const GemmEpi& e, f32x4 (&acc
 #define EC_QKV_STORE(C, J)                                                                   \
   _Pragma("unroll") for (int i = 0; i < WTN; ++i) {                                            \
     const f32x4 v = acc[i][J];                                                               \
-    const int m_ = (mt_base + (J)) * 16 + (lane & 15);                                       \
     if (kind[i] < 2) {                                                                       \
-      float o_[4], out_[4];                                                                  \
-      _Pragma("unroll") for (int r = 0; r < 4; ++r) o_[r] = other_half(v[r]);                  \
+      float out_[4];                                                                         \
       const float cc_[4] = {C[i][0].x, C[i][0].z, C[i][1].x, C[i][1].z};                      \
       const float ss_[4] = {C[i][0].y, C[i][0].w, C[i][1].y, C[i][1].w};                      \
       _Pragma("unroll") for (int r = 0; r < 4; ++r) {                                          \
-        const float x = v[r] * rs[J], y = o_[r] * rs[J];                                     \
-        out_[r] = hi ? x * cc_[r] + y * ss_[r] : x * cc_[r] - y * ss_[r];                     \
+        const float y_ = other_half(v[r]);                                                   \
+        const float s_ = __uint_as_float(__float_as_uint(ss_[r]) ^ sin_sign);                \
+        out_[r] = (v[r] * cc_[r] + y_ * s_) * rs[J];                                         \
       }                                                                                      \
       u32x2 pk_;                                                                             \
       pk_[0] = pack2(out_[0], out_[1]);                                                      \
       pk_[1] = pack2(out_[2], out_[3]);                                                      \
-      const int col_ = w[i] * 8 + (q4 & 1) * 4 + (hi ? half : 0);                             \
       if (mvalid[J]) {                                                                       \
         if (kind[i] == 0)                                                                    \
-          *(u32x2*)(e.q_out + (size_t)m_ * (e.Hq * hd) + head[i] * hd + col_) = pk_;          \
+          *(u32x2*)(e.q_out + qrow[J] + qcol[i]) = pk_;                                      \
         else                                                                                 \
-          *(u32x2*)(e.kc + kvoff[J] + (size_t)head[i] * tpad[J] * hd +                        \
-                    kcache_index(pos[J], col_, hd)) = pk_;                                   \
+          *(u32x2*)(e.kc + (size_t)head[i] * slab[J] + krow[J] + kcol[i]) = pk_;             \
       }                                                                                      \
     } else if (kind[i] == 2 && mvalid[J]) {                                                  \
-      bf16_t* slab_ = e.vc + kvoff[J] + (size_t)head[i] * tpad[J] * hd;                       \
-      _Pragma("unroll") for (int r = 0; r < 4; ++r)                                            \
-          slab_[vcache_index(pos[J], w[i] * 16 + q4 * 4 + r, tpad[J])] = f32_to_bf16(v[r] * rs[J]); \
+      bf16_t* dst_ = e.vc + (size_t)head[i] * slab[J] + vrow[J] + w[i] * vstep[J] + q4 * 32; \
+      _Pragma("unroll") for (int r = 0; r < 4; ++r) dst_[r * 8] = f32_to_bf16(v[r] * rs[J]);   \
     }                                                                                        \
   }
   EC_QKV_LOADC(ca, 0)
@@ -467,9 +480,6 @@ __device__ __forceinline__ void tiled_epilogue_qkv(const GemmEpi& e, f32x4 (&acc
 #undef EC_QKV_STORE
 }
 
-// ---------------------------------------------------------------------------------------------
-// Epilogue of the tiled kernels: one wave's WTN x WTM accumulator tiles (weights x activations).
-// ---------------------------------------------------------------------------------------------
 template <int EPI, int WTM, int WTN, bool PIPE = true>
 __device__ __forceinline__ void tiled_epilogue(const GemmEpi& e, f32x4 (&acc)[WTN][WTM],
                                                int mt_base, int nt_base, int total_nt, int lane,
@@ -891,7 +901,7 @@ static void launch_tiled_pick(const bf16_t* Ap, int MT, const bf16_t* Wp, int to
                               const GemmEpi& e, hipStream_t s, int tile, int ksplit) {
   switch (tile) {
     case 0: launch_tiled8_t<EPI, 2, 4, 6, 6, 3>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
-    case 1: launch_tiled8_t<EPI, 2, 4, 6, 4, 3>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
+    case 1: launch_tiled8_t<EPI, 2, 4, 6, 4, 3, true>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
     case 2: launch_tiled8_t<EPI, 2, 4, 6, 3, 3>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
     case 3: launch_tiled8_t<EPI, 2, 4, 6, 2, 3>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
     case 4: launch_tiled4_t<EPI, 6, 6>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
