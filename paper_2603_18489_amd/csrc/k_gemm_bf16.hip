@@ -85,6 +85,19 @@ __device__ __forceinline__ float epi_resid(const GemmEpi& e, int m, int vt, int 
   return h.x * h.x + h.y * h.y + h.z * h.z + h.w * h.w;
 }
 
+// epi_resid with h and the gains already in registers (fetched at kernel start)
+__device__ __forceinline__ float epi_resid_pre(const GemmEpi& e, int m, int vt, int q4, f32x4 v,
+                                               float4 h, u32x2 g4) {
+  int n = vt * 16 + q4 * 4;
+  h.x += v[0]; h.y += v[1]; h.z += v[2]; h.w += v[3];
+  *(float4*)(e.h + (size_t)m * e.d + n) = h;
+  u32x2 pk;
+  pk[0] = pack2(h.x * __uint_as_float(g4[0] << 16), h.y * __uint_as_float(g4[0] & 0xffff0000u));
+  pk[1] = pack2(h.z * __uint_as_float(g4[1] << 16), h.w * __uint_as_float(g4[1] & 0xffff0000u));
+  *(u32x2*)(e.a_next + packed_act_index(m, n, e.MT)) = pk;
+  return h.x * h.x + h.y * h.y + h.z * h.z + h.w * h.w;
+}
+
 __device__ __forceinline__ void epi_add_sumsq(const GemmEpi& e, int m, bool valid, float part) {
   // the 4 lanes l, l^16, l^32, l^48 hold the same row
   part += __shfl_xor(part, 16, 64);
@@ -252,6 +265,19 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* 
   // into 1/rms after the main loop, so neither the loop nor the epilogue waits on them.  All
   // threads load (those without a row of their own read row 0): no branch, so the compiler
   // still counts outstanding loads exactly.
+  // Epilogue operands of the thread's first output unit are fetched here too: the residual
+  // stream and gains (EPI_RESID) so that the epilogue does not start with a round trip to memory.
+  constexpr int UNITS = NTW * MT * 64;  // whole waves: the wave's 64 lanes share (tile, m-tile)
+  float4 pre_h = make_float4(0.f, 0.f, 0.f, 0.f);
+  u32x2 pre_g = {0u, 0u};
+  if constexpr (EPI == EPI_RESID) {
+    const int o = threadIdx.x < UNITS ? threadIdx.x : 0;
+    const int l = o & 63, unit = o >> 6, iu = unit / MT, j = unit - iu * MT;
+    const int m = j * 16 + (l & 15), vt = nt0 + iu;
+    const int mm = m < e.M ? m : 0, n = (vt < total_nt ? vt : 0) * 16 + (l >> 4) * 4;
+    pre_h = *(const float4*)(e.h + (size_t)mm * e.d + n);
+    pre_g = *(const u32x2*)(e.gain_next + n);
+  }
   unsigned long long ssq[kSumSlots];
   if constexpr (NORMED) {
 #pragma unroll
@@ -320,7 +346,6 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* 
   };
 
   static_assert(EPI != EPI_PARTIAL, "K-split partial products are a tiled-kernel epilogue");
-  constexpr int UNITS = NTW * MT * 64;  // whole waves: the wave's 64 lanes share (tile, m-tile)
   for (int o = threadIdx.x; o < UNITS; o += KS * 64) {
     const int l = o & 63, unit = o >> 6, iu = unit / MT, j = unit - iu * MT;
     const int m = j * 16 + (l & 15), q4 = l >> 4;
@@ -329,7 +354,8 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* 
     f32x4 v = ksum((iu * MT + j) * 64 + l);
     if constexpr (EPI == EPI_RESID) {
       float part = 0.f;
-      if (mvalid && vt < total_nt) part = epi_resid(e, m, vt, q4, v);
+      if (mvalid && vt < total_nt)
+        part = o < KS * 64 ? epi_resid_pre(e, m, vt, q4, v, pre_h, pre_g) : epi_resid(e, m, vt, q4, v);
       epi_add_sumsq(e, m, mvalid, part);
     } else if (mvalid && vt < total_nt) {
       if constexpr (EPI == EPI_LOGITS) epi_logits(e, m, vt, q4, v, rstd_s[m]);
