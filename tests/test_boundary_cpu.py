@@ -126,6 +126,40 @@ def test_init_argument_errors_without_gpu(lib):
     assert not ctx.value
 
 
+def test_batch_and_decode_option_checks(lib):
+    mc, dc, wl = _cfgs("llada8b_l2")
+    ctx = C.c_void_p()
+    ws = ec.ec_weights()
+    i32p = C.POINTER(C.c_int32)
+    plens = np.array([40, 7, 100], dtype=np.int32)
+    prompt = ec_inputs.make_prompt(wl.model.vocab, int(plens.sum()), 1)
+    pp, pl = prompt.ctypes.data_as(i32p), plens.ctypes.data_as(i32p)
+    one = ec.decode_cfg_struct(wl.decode.replace(batch=1))
+    three = ec.decode_cfg_struct(wl.decode.replace(batch=3))
+    # a batch needs room for every sequence's cache and rows
+    n1 = lib.ec_workspace_bytes(C.byref(mc), C.byref(one), pl)
+    n3 = lib.ec_workspace_bytes(C.byref(mc), C.byref(three), pl)
+    assert n1 > 0 and n3 > n1
+    # a valid batch configuration gets past the configuration check (and fails on the weights)
+    assert lib.ec_init(C.byref(ctx), C.byref(mc), C.byref(ws), C.byref(three), pp, pl, None, 0,
+                       None) == ec.EC_ERR_ARG
+    for field, val in (("batch", 0), ("batch", ec.EC_MAX_BATCH + 1), ("conf_threshold", 1.0),
+                       ("conf_threshold", -0.1), ("gate_metric", 3), ("schedule", 2)):
+        bad = ec.decode_cfg_struct(wl.decode.replace(**{field: val}))
+        assert lib.ec_workspace_bytes(C.byref(mc), C.byref(bad), pl) == 0, field
+        assert lib.ec_init(C.byref(ctx), C.byref(mc), C.byref(ws), C.byref(bad), pp, pl, None, 0,
+                           None) == ec.EC_ERR_CONFIG, field
+    # batches run on the bfloat16 path only
+    mcf, _, wlf = _cfgs("tiny_f32")
+    two = ec.decode_cfg_struct(wlf.decode.replace(batch=2))
+    assert lib.ec_init(C.byref(ctx), C.byref(mcf), C.byref(ws), C.byref(two), pp, pl, None, 0,
+                       None) == ec.EC_ERR_CONFIG
+    assert b"bfloat16" in lib.ec_last_error(None)
+    r = ec.ec_step_result()
+    assert lib.ec_step_forced_batch(None, pl, pl, pl, pl, C.byref(r)) == ec.EC_ERR_ARG
+    assert lib.ec_debug_read_seq(None, 0, 0, 0, None, 0) == ec.EC_ERR_ARG
+
+
 def test_null_context_calls(lib):
     r = ec.ec_step_result()
     assert lib.ec_step(None, ec.EC_AUTO, C.byref(r)) == ec.EC_ERR_ARG

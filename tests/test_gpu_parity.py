@@ -123,6 +123,57 @@ def test_batched_sequences_match_their_own_oracle_runs(hq, hkv, hd, plens, N, bl
         assert s["finished_early"] >= 1
 
 
+@pytest.mark.parametrize("dtype,P,N,block,k,n,tau", [
+    ("f32", 0, 20, 8, 2, 1, 2.5),          # no prompt at all
+    ("bf16", 3, 40, 128, 100, 32, 1e9),    # largest block and tokens per step, k beyond the generation
+    ("f32", 9, 12, 4, 1, 1, -1.0),         # threshold below any entropy: every step FULL
+    ("bf16", 17, 33, 1, 0, 1, 1e9),        # block of one: strictly left to right, no recent rows
+])
+def test_degenerate_shapes(dtype, P, N, block, k, n, tau):
+    cfg = small_cfg(dtype, 4, 2, 64)
+    w = ec_inputs.make_weights(cfg, 23, gain_jitter=0.1)
+    dec = ec_inputs.DecodeCfg(gen_len=N, block=block, k_recent=k, tokens_per_step=n, tau=tau)
+    prompt = ec_inputs.make_prompt(cfg.vocab, P, 4)
+    s = run_teacher_forced(cfg, w, dec, prompt, TOL[dtype])
+    print(s)
+    if tau < 0:
+        assert s["modes"][eco.PARTIAL] == 0
+
+
+def test_largest_context_properties():
+    """15000 positions (the largest context the library accepts) on a small model, where the
+    oracle is too slow: properties that hold at any size.  A second FULL step with nothing
+    committed in between is idempotent (same logits, same cache); a PARTIAL step after it sees an
+    exact cache and reproduces those logits on the block rows."""
+    cfg = small_cfg("bf16", 4, 2, 64)
+    w = ec_inputs.make_weights(cfg, 29, gain_jitter=0.1)
+    dec = ec_inputs.DecodeCfg(gen_len=200, block=32, k_recent=2, tokens_per_step=1, tau=1.0)
+    prompt = ec_inputs.make_prompt(cfg.vocab, 14800, 6)
+    g = ec.EntropyCache(cfg, ec.weights_to_device(cfg, w), dec, prompt)
+    try:
+        r1 = g.step_forced(ec.EC_FULL, [], [])
+        z1 = g.debug_read(ec.EC_DBG_LOGITS, count=32)
+        k1 = g.debug_read(ec.EC_DBG_KCACHE, 1)
+        r2 = g.step_forced(ec.EC_FULL, [], [])
+        z2 = g.debug_read(ec.EC_DBG_LOGITS, count=32)
+        k2 = g.debug_read(ec.EC_DBG_KCACHE, 1)
+        assert r1["n_query_rows"] == r2["n_query_rows"] == 15000
+        assert np.array_equal(z1, z2) and np.array_equal(k1, k2)      # same kernels, same inputs
+        assert np.isfinite(z1).all() and float(np.abs(z1).max()) > 0
+        r3 = g.step_forced(ec.EC_PARTIAL, [], [])
+        z3 = g.debug_read(ec.EC_DBG_LOGITS, count=32)
+        assert r3["n_query_rows"] == 32
+        assert relerr(z3, z1) <= TOL["bf16"]
+        # the partial step rewrote the block rows' K/V from the same inputs
+        assert relerr(ec_bits(g.debug_read(ec.EC_DBG_KCACHE, 1)), ec_bits(k1)) <= TOL["bf16"]
+    finally:
+        g.close()
+
+
+def ec_bits(a):
+    return (a.astype(np.uint32) << np.uint32(16)).view(np.float32) if a.dtype == np.uint16 else a
+
+
 def test_free_running_generation_matches_oracle_f32():
     """Without forcing: the GPU's own decisions reproduce the oracle's generation (float32 model,
     margins far above 1e-4 at every step of this seed)."""
