@@ -337,7 +337,9 @@ def main():
                                f"{cfg.n_heads}q/{cfg.n_kv_heads}kv x{cfg.head_dim} F{cfg.d_ffn} "
                                f"V{cfg.vocab}, prompt {wl.prompt_len}, gen {dec.gen_len}, block "
                                f"{dec.block}, n={dec.tokens_per_step}, k={dec.k_recent}, "
-                               f"tau={dec.tau}",
+                               f"tau={dec.tau}"
+                               + (f", confidence threshold {dec.conf_threshold}" if dec.conf_threshold else "")
+                               + (", sliding window" if dec.schedule else ""),
                    "schedule": "free-running EC_AUTO, calibrated logit scale",
                    "logit_scale": scale, "full_fraction": full / steps,
                    "full_steps": full, "partial_steps": partial},

@@ -97,6 +97,11 @@ WORKLOADS: Dict[str, Workload] = {
     "llada8b_cot": Workload("llada8b_cot", _llada(),
                             DecodeCfg(gen_len=1024, block=32, k_recent=4, tokens_per_step=1,
                                       tau=0.5), 256, 2),
+    # the paper's own decoding settings on the LLaDA-8B shape: sliding window of 32, confidence-
+    # based parallel decoding at 0.9, tau = 1.5, k = 64 (partial steps of up to 96 rows)
+    "llada8b_paper": Workload("llada8b_paper", _llada(),
+                              DecodeCfg(gen_len=256, block=32, k_recent=64, tokens_per_step=1,
+                                        tau=1.5, conf_threshold=0.9, schedule=1), 512, 2),
     # 16 sequences side by side on the LLaDA-8B model, prompts 1024, 992, ... (ragged), 512
     # generated tokens each: partial steps of 16 x (<= 34) rows, full steps of up to 24 576 rows
     "llada8b_b16": Workload("llada8b_b16", _llada(),
