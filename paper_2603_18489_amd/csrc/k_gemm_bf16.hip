@@ -708,14 +708,15 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 // PIPE: the fragments of k-step k+1 are read from LDS into a second register set while the
 // MFMAs of k-step k run.  Without it every k-step is a burst of LDS reads (all waves at once,
 // right after the barrier, matrix cores idle) followed by a burst of MFMAs.
-template <int EPI, int WM, int WN, int WTM, int WTN>
+template <int EPI, int WM, int WN, int WTM, int WTN, bool PIPE>
 constexpr int tiled8_waves_per_eu() {
-  return WM * WN == 4 ? 1 : (EPI == EPI_PARTIAL && WTM * WTN <= 18 ? 4 : 2);
+  // four-wave blocks: two to a CU (256 registers each) unless the read-ahead needs more
+  return WM * WN == 4 ? (PIPE ? 1 : 2) : (EPI == EPI_PARTIAL && WTM * WTN <= 18 ? 4 : 2);
 }
 template <int EPI, int WM, int WN, int WTM, int WTN, int NSTAGE, bool PIPE = false>
 __global__ __launch_bounds__(WM * WN * 64)
-__attribute__((amdgpu_waves_per_eu(tiled8_waves_per_eu<EPI, WM, WN, WTM, WTN>(),
-                                   tiled8_waves_per_eu<EPI, WM, WN, WTM, WTN>())))
+__attribute__((amdgpu_waves_per_eu(tiled8_waves_per_eu<EPI, WM, WN, WTM, WTN, PIPE>(),
+                                   tiled8_waves_per_eu<EPI, WM, WN, WTM, WTN, PIPE>())))
 void gemm_bf16_tiled8_kernel(
     const u32x4* __restrict__ Ap, const u32x4* __restrict__ Wp, int total_nt, int KB_all, int MT,
     GemmEpi e) {
