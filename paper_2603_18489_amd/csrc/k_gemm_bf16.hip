@@ -13,22 +13,23 @@
 // order-independent and therefore bit-reproducible.
 //
 // Epilogues (template parameter EPI):
-//   EPI_QKV    x 1/rms, rotary embedding on q and k (weight tiles are stored so that columns j
-//              and j + hd/2 of a head sit in adjacent tiles), q -> query buffer, k / v -> the
-//              packed KV cache rows of the row's position
+//   EPI_QKV    x 1/rms, rotary embedding on q and k (a weight tile holds 8 columns of a head
+//              and their 8 partners hd/2 further on, so a rotation pair meets in lanes l and
+//              l + 32), q -> query buffer, k / v -> the packed KV cache rows of the row's position
 //   EPI_RESID  h += result; writes bf16(h * next gain) as the next GEMM's operand and adds the
 //              row's sum of squares
-//   EPI_SWIGLU x 1/rms, silu(gate) * up (gate / up tiles interleaved), -> packed activations
+//   EPI_SWIGLU x 1/rms, silu(gate) * up (8 gate rows and their 8 up rows share a tile), -> packed
+//              activations
 //   EPI_LOGITS x 1/rms x logit scale -> fp32 logits
 //
 // Kernels:
-//   skinny (M <= 64): weight streaming.  A block of KS waves owns NTW weight tiles and splits K
+//   skinny (M <= 96): weight streaming.  A block of KS waves owns NTW weight tiles and splits K
 //     across its waves; each weight byte is read from HBM exactly once while the small
 //     activation fragments come from L2.  The KS partial tiles are summed in LDS in a fixed
 //     order, then the epilogue runs on the sums.
-//   tiled (M > 64): block tile chosen per shape so that the grid fills the 256 CUs.  Up to
-//     192x192: 4 waves, LDS double buffer fed through four register sets.  192x256 / 192x384:
-//     8 waves, operands loaded from global memory directly into a 3-stage LDS ring.
+//   tiled (M > 96): block tile chosen per shape so that the grid fills the 256 CUs.  4 waves:
+//     LDS double buffer fed through four register sets.  8 waves (192x128 .. 192x384): operands
+//     loaded from global memory directly into a 3-stage LDS ring.
 #include "ec_internal.h"
 
 namespace ec {
