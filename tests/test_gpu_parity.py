@@ -123,6 +123,34 @@ def test_batched_sequences_match_their_own_oracle_runs(hq, hkv, hd, plens, N, bl
         assert s["finished_early"] >= 1
 
 
+def _random_case(seed):
+    r = np.random.RandomState(seed)
+    hkv, hd = int(r.choice([1, 2, 4])), int(r.choice([64, 128]))
+    hq = hkv * int(r.choice([1, 2, 4])) if hd == 64 else hkv * int(r.choice([1, 2]))
+    return dict(dtype=str(r.choice(["f32", "bf16"])), hq=hq, hkv=hkv, hd=hd,
+                P=int(r.randint(0, 90)), N=int(r.randint(5, 70)), block=int(r.choice([4, 8, 16, 32])),
+                k=int(r.randint(0, 12)), n=int(r.randint(1, 4)), tau=float(r.choice([1.5, 2.5, 3.5, 1e9])),
+                thr=float(r.choice([0.0, 0.0, 0.4])), metric=int(r.choice([0, 0, 1, 2])),
+                schedule=int(r.choice([0, 1])), scale=float(r.choice([10.0, 13.0, 16.0])))
+
+
+@pytest.mark.parametrize("seed", list(range(100, 112)))
+def test_random_configurations(seed):
+    """Seeded sweep over head layouts, sizes, schedules and decoding rules (whole generations,
+    teacher forced)."""
+    c = _random_case(seed)
+    d = max(256, c["hq"] * c["hd"])
+    cfg = small_cfg(c["dtype"], c["hq"], c["hkv"], c["hd"], d=d, scale=c["scale"])
+    w = ec_inputs.make_weights(cfg, seed, gain_jitter=0.1)
+    tau = c["tau"] if c["metric"] != 2 else min(c["tau"], 0.5)
+    dec = ec_inputs.DecodeCfg(gen_len=c["N"], block=c["block"], k_recent=c["k"],
+                              tokens_per_step=c["n"], tau=tau, conf_threshold=c["thr"],
+                              gate_metric=c["metric"], schedule=c["schedule"])
+    prompt = ec_inputs.make_prompt(cfg.vocab, c["P"], seed + 1)
+    s = run_teacher_forced(cfg, w, dec, prompt, TOL[c["dtype"]], max_steps=40)
+    print(c, s)
+
+
 def test_batched_generate_runs_every_sequence_to_the_end():
     """ec_generate on a batch: free-running, sequences in different modes side by side; every
     generation slot ends up decoded, the counters add up, and a reset reproduces the run."""
