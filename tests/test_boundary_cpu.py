@@ -170,3 +170,14 @@ def test_null_context_calls(lib):
     lib.ec_destroy(None)
     for code in (0, -1, -2, -3, -4, -5, -99):
         assert len(lib.ec_strerror(code)) > 0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py is a one-GPU program: any other --gpus value ends with a message, before any GPU
+    or library work."""
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert p.returncode == 2
+    assert "one GPU" in p.stderr and p.stdout.strip() == ""
