@@ -98,14 +98,15 @@ def calibrate_logit_scale(make_ctx, prompt, target_lo=0.08, target_hi=0.16):
 
 
 def bench_batch(args, wl, cfg, dec, dw):
-    """Many sequences side by side (decode.batch > 1): prompt b has prompt_len - 32 b ids.
+    """Many sequences side by side (decode.batch > 1), every prompt prompt_len ids long (their
+    modes still differ from step to step).
     Timed: K free-running steps of the whole batch; then the all-PARTIAL steady state and the
     all-FULL step, forced.  One JSON line like the single-sequence run's, without the CPU leg."""
     import torch
     import ec_inputs
     import paper_2603_18489_amd as ec
     B = dec.batch
-    plens = [wl.prompt_len - 32 * b for b in range(B)]
+    plens = [wl.prompt_len] * B
     prompts = [ec_inputs.make_prompt(cfg.vocab, P, wl.seed + 1000 + b) for b, P in enumerate(plens)]
     scale = args.logit_scale if args.logit_scale > 0 else 8.0
     g = ec.EntropyCache(cfg.replace(logit_scale=scale), dw, dec, prompts)
@@ -157,7 +158,7 @@ def bench_batch(args, wl, cfg, dec, dw):
         "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{wl.name}: L{cfg.n_layers} d{cfg.d_model} {cfg.n_heads}q/"
                                f"{cfg.n_kv_heads}kv x{cfg.head_dim} F{cfg.d_ffn} V{cfg.vocab}, "
-                               f"{B} sequences, prompts {plens[0]}..{plens[-1]}, gen {dec.gen_len}, "
+                               f"{B} sequences, prompt {plens[0]} each, gen {dec.gen_len}, "
                                f"block {dec.block}, n={dec.tokens_per_step}, k={dec.k_recent}, "
                                f"tau={dec.tau}",
                    "schedule": "free-running EC_AUTO", "logit_scale": scale,

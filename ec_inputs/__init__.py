@@ -102,8 +102,8 @@ WORKLOADS: Dict[str, Workload] = {
     "llada8b_paper": Workload("llada8b_paper", _llada(),
                               DecodeCfg(gen_len=256, block=32, k_recent=64, tokens_per_step=1,
                                         tau=1.5, conf_threshold=0.9, schedule=1), 512, 2),
-    # 16 sequences side by side on the LLaDA-8B model, prompts 1024, 992, ... (ragged), 512
-    # generated tokens each: partial steps of 16 x (<= 34) rows, full steps of up to 24 576 rows
+    # 16 sequences side by side on the LLaDA-8B model, prompts of 1024, 512 generated tokens each:
+    # partial steps of 16 x (<= 34) rows, full steps of up to 24 576 rows, mixed within a step
     "llada8b_b16": Workload("llada8b_b16", _llada(),
                             DecodeCfg(gen_len=512, block=32, k_recent=2, tokens_per_step=1,
                                       tau=1.0, batch=16), 1024, 2),
