@@ -44,6 +44,7 @@ struct Buffers {
   float* row_stats; StepOut* out; int* forced_pos; int* forced_tok; int* prompt;
   // the step's row list (bf16 path)
   SeqDesc* seqs; int4* rowinfo; int4* tileinfo; int* lm_sel;
+  int4* pairs;  // (row tile, sequence) visits of the few-row sequences, [rmax/16 + B]
   float2* rope_cs;
   char* kv;  // [L][2] planes; a plane holds every sequence's [Hkv][keys][hd] slabs, storage type
   size_t kv_plane;  // elements per plane
@@ -113,6 +114,7 @@ void carve(Carver& c, const ec_model_cfg& m, const ec_decode_cfg& d, const Geome
   b.forced_tok = c.take<int>((size_t)B * EC_MAX_N); b.prompt = c.take<int>(g.ptot);
   b.seqs = c.take<SeqDesc>(B); b.rowinfo = c.take<int4>(R); b.tileinfo = c.take<int4>(R / 16);
   b.lm_sel = c.take<int>(BL);
+  b.pairs = c.take<int4>(R / 16 + B);
   b.rope_cs = c.take<float2>((size_t)g.tmax * (m.head_dim / 2));
   b.kv_plane = g.kv_plane;
   b.kv = c.take<char>((size_t)m.n_layers * 2 * g.kv_plane * es);
@@ -202,6 +204,7 @@ struct ec_ctx {
   StepOut* host_out = nullptr;   // pinned [B]
   int* host_stage = nullptr;     // pinned: prompts / forced lists on their way to the device
   SeqDesc* host_seqs = nullptr;  // pinned [B]
+  int4* host_pairs = nullptr;    // pinned [rmax/16 + B]
   // host mirror of the scalar state, per sequence
   int steps_run = 0;
   std::vector<int> next_mode, has_full, done, n_mb, n_rows_partial;
@@ -330,6 +333,7 @@ struct StepPlan {
   int R = 0, n_lm = 0;                      // rows of the list (with padding), masked block rows
   bool has_small = false, has_large = false;
   int max_T_small = 1;
+  int npairs = 0;                           // (row tile, sequence) visits of few-row sequences
   bool single = false;                      // one sequence takes part: one_seq is its tile entry
   int4 one_seq = make_int4(0, 0, 32, 0);
   int64_t rows = 0;                         // sum of the sequences' own row counts
@@ -412,9 +416,10 @@ int forward_bf16(ec_ctx* c, const StepPlan& sp) {
       e.w_grp = skinny_tiles_per_block(EPI_QKV, nqkv / 16);
       launch_gemm_bf16(EPI_QKV, u, R, b.pl[l].wqkv, nqkv, d, e, s); }
     { Scope p(c, EC_K_ATTN);
-      launch_attention_mfma(q, kc, vc, R, b.rowinfo, sp.single ? nullptr : b.tileinfo, sp.one_seq,
-                            sp.has_small, sp.has_large, sp.max_T_small, m.n_heads, m.n_kv_heads,
-                            hd, attn, b.ksplit_part, b.ksplit_floats, b.attn_tickets, s); }
+      launch_attention_mfma(q, kc, vc, R, b.rowinfo, sp.single ? nullptr : b.tileinfo,
+                            sp.single ? nullptr : b.pairs, sp.npairs, sp.one_seq, sp.has_small,
+                            sp.has_large, sp.max_T_small, m.n_heads, m.n_kv_heads, hd, attn,
+                            b.ksplit_part, b.ksplit_floats, b.attn_tickets, s); }
     { Scope p(c, EC_K_OPROJ);
       GemmEpi e{}; e.M = M; e.MT = MT; e.h = b.h; e.d = d; e.gain_next = G(c->mlp_norm[l]);
       e.a_next = u; e.sumsq_out = sums(2 * l + 1); e.sum_stride = b.sumsq_stride;
@@ -502,8 +507,12 @@ int run_step(ec_ctx* c, const int32_t* modes, int modes_n, const int32_t* forced
       const bool large = n_rows > kSmallRows;
       if (large != (pass == 0)) continue;
       SeqDesc& sd = c->host_seqs[b];
-      sd.mode = mode[b]; sd.n_rows = n_rows; sd.row0 = sp.R; sd.seg_rows = seg_rows_of(n_rows);
+      sd.mode = mode[b]; sd.n_rows = n_rows; sd.row0 = sp.R;
+      sd.seg_rows = large ? seg_rows_of(n_rows) : n_rows;   // few-row sequences: back to back
       sd.n_mb = c->n_mb[b]; sd.forced_n = fn;
+      if (!large)
+        for (int mt = sd.row0 / 16; mt <= (sd.row0 + n_rows - 1) / 16; ++mt)
+          c->host_pairs[sp.npairs++] = make_int4(mt, sd.kv_off, sd.T, sd.tpad);
       sp.R += sd.seg_rows; sp.rows += n_rows;
       (large ? sp.has_large : sp.has_small) = true;
       if (!large && c->g.T[b] > sp.max_T_small) sp.max_T_small = c->g.T[b];
@@ -522,6 +531,10 @@ int run_step(ec_ctx* c, const int32_t* modes, int modes_n, const int32_t* forced
       sp.one_seq = make_int4(sd.kv_off, sd.T, sd.tpad, sd.n_rows > kSmallRows ? 1 : 0);
     }
   sp.single = sp.n_full + sp.n_partial == 1;
+  sp.R = (sp.R + 15) / 16 * 16;
+  if (!sp.single && sp.npairs > 0)
+    EC_HIP(c, hipMemcpyAsync(c->b.pairs, c->host_pairs, (size_t)sp.npairs * sizeof(int4),
+                             hipMemcpyHostToDevice, c->stream));
   EC_HIP(c, hipMemcpyAsync(c->b.seqs, c->host_seqs, (size_t)B * sizeof(SeqDesc),
                            hipMemcpyHostToDevice, c->stream));
   if (forced_n) {
@@ -662,6 +675,7 @@ int ec_init(ec_ctx** out, const ec_model_cfg* model, const ec_weights* weights,
     if (c->host_out) (void)hipHostFree(c->host_out);
     if (c->host_stage) (void)hipHostFree(c->host_stage);
     if (c->host_seqs) (void)hipHostFree(c->host_seqs);
+    if (c->host_pairs) (void)hipHostFree(c->host_pairs);
     delete c;
     return fail(nullptr, code, msg);
   };
@@ -672,6 +686,8 @@ int ec_init(ec_ctx** out, const ec_model_cfg* model, const ec_weights* weights,
   if (e != hipSuccess) return bail(EC_ERR_HIP, std::string("hipHostMalloc: ") + hipGetErrorString(e));
   e = hipHostMalloc((void**)&c->host_seqs, (size_t)B * sizeof(SeqDesc), hipHostMallocDefault);
   if (e != hipSuccess) return bail(EC_ERR_HIP, std::string("hipHostMalloc: ") + hipGetErrorString(e));
+  e = hipHostMalloc((void**)&c->host_pairs, (g.rmax / 16 + B) * sizeof(int4), hipHostMallocDefault);
+  if (e != hipSuccess) return bail(EC_ERR_HIP, std::string("hipHostMalloc: ") + hipGetErrorString(e));
 
   // one-time device set-up: RoPE table, re-tiled bf16 matrices, finite padding keys
   launch_rope_table(c->b.rope_cs, g.tmax, c->m.head_dim, c->m.rope_base, c->stream);
@@ -679,6 +695,10 @@ int ec_init(ec_ctx** out, const ec_model_cfg* model, const ec_weights* weights,
     size_t kvbytes = (size_t)L * 2 * c->b.kv_plane * 2;
     e = hipMemsetAsync(c->b.kv, 0, kvbytes, c->stream);
     if (e == hipSuccess) e = hipMemsetAsync(c->b.attn_tickets, 0, 256 * sizeof(int), c->stream);
+    // the last tile's padding rows of q and of the attention output are never written: zeros
+    const size_t qbytes = g.rmax * (size_t)c->m.n_heads * c->m.head_dim * 2;
+    if (e == hipSuccess) e = hipMemsetAsync(c->b.q, 0, qbytes, c->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(c->b.attn, 0, qbytes, c->stream);
     if (e != hipSuccess) return bail(EC_ERR_HIP, std::string("hipMemsetAsync: ") + hipGetErrorString(e));
     const int d = c->m.d_model, F = c->m.d_ffn;
     const int nq = c->m.n_heads * c->m.head_dim, nkv = c->m.n_kv_heads * c->m.head_dim;
@@ -828,6 +848,7 @@ void ec_destroy(ec_ctx* ctx) {
   if (ctx->host_out) (void)hipHostFree(ctx->host_out);
   if (ctx->host_stage) (void)hipHostFree(ctx->host_stage);
   if (ctx->host_seqs) (void)hipHostFree(ctx->host_seqs);
+  if (ctx->host_pairs) (void)hipHostFree(ctx->host_pairs);
   delete ctx;
 }
 

@@ -23,9 +23,10 @@ struct DevState {
 };
 
 // One sequence of the batch as a step sees it; the host rewrites the table before every step.
-// A step's rows are the sequences' row sets one after the other, each padded to whole 16-row
-// tiles (to 256 rows once it has more than kSmallRows, so that an attention block's query tiles
-// never straddle two sequences); sequences with many rows come first.
+// A step's rows are the sequences' row sets one after the other: first the sequences with more
+// than kSmallRows rows, each padded to 256 rows (so that an attention block's query tiles never
+// straddle two of them), then the others back to back without padding; the list ends on a whole
+// 16-row tile.
 struct SeqDesc {
   int P, T, tpad;   // prompt length, positions, keys per cache slab (padded to 32)
   int x_off;        // first element of the sequence in x / masked / rows_partial
@@ -33,7 +34,7 @@ struct SeqDesc {
   int mode;         // EC_FULL / EC_PARTIAL this step, -1 = takes no part (finished)
   int n_rows;       // rows it contributes: T or |M u R|
   int row0;         // its first row in the step's row list
-  int seg_rows;     // rows of its segment including the padding
+  int seg_rows;     // rows of its segment (with the padding of a many-row sequence)
   int n_mb, lm0;    // masked rows of its block; the first of them in the logits buffer
   int forced_n;     // teacher forcing: tokens to commit, -1 = the step's own choice
 };
@@ -176,14 +177,17 @@ void launch_gemm_bf16(int epi, const bf16_t* Ap, int M_src, const bf16_t* Wp, in
 // part / tickets: scratch for splitting the keys over blocks when there are few query rows
 // (part_floats floats; 256 counters, zero on entry and again on exit); null = never split.
 // R rows (rowinfo / tileinfo as the step prologue wrote them), kc / vc: one layer's planes.
-// tileinfo may be NULL when the step has a single sequence: then one_seq is every tile's entry.
-// has_small / has_large: whether any sequence of the step has at most / more than kSmallRows
-// rows; max_T: most positions of any few-row sequence taking part.
+// Sequences with at most kSmallRows rows are served through `pairs`: npairs entries (row tile,
+// cache offset, positions, keys per slab), one for every sequence a row tile holds rows of.
+// pairs (and tileinfo) may be NULL when the step has a single sequence: then one_seq (cache
+// offset, positions, keys per slab, many-rows flag) describes every tile.  has_small /
+// has_large: whether any sequence of the step has at most / more than kSmallRows rows; max_T:
+// most positions of any few-row sequence taking part.
 void launch_attention_mfma(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int R,
-                           const int4* rowinfo, const int4* tileinfo, int4 one_seq,
-                           bool has_small, bool has_large, int max_T, int Hq, int Hkv, int hd,
-                           bf16_t* out, float* part, size_t part_floats, int* tickets,
-                           hipStream_t s);
+                           const int4* rowinfo, const int4* tileinfo, const int4* pairs,
+                           int npairs, int4 one_seq, bool has_small, bool has_large, int max_T,
+                           int Hq, int Hkv, int hd, bf16_t* out, float* part, size_t part_floats,
+                           int* tickets, hipStream_t s);
 
 // decision
 int vocab_reduce_parts(int V);

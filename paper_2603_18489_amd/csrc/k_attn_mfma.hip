@@ -3,8 +3,8 @@
 // The step's rows come as a list (sequence after sequence, each padded to whole 16-row tiles);
 // a query tile is one 16-row tile of that list for one query head, tile number g * MT + mt for
 // head g of the kv head's group, so the tiles of a group share the K/V fragments in cache.
-// tileinfo tells each row tile which sequence's cache it attends to (offset, positions, padded
-// keys) and whether that sequence has many rows in this step.  Per 32-key chunk and query tile:
+// tileinfo tells the row tiles of many-row sequences which cache they attend to (offset,
+// positions, padded keys); the few-row sequences come as (row tile, sequence) pairs.  Per 32-key chunk and query tile:
 //   S^T[keys x queries] = K . Q^T          (2 key tiles x HD/32 MFMAs, K fragments straight from
 //                                            the cache, Q fragments held in registers)
 //   online softmax down the key axis        (a lane owns 8 consecutive keys of one query; the
@@ -126,18 +126,28 @@ __device__ __forceinline__ float2 ld_agent(const float* p) {
 template <int HD>
 __global__ __launch_bounds__(512) void attn_mfma_split_kernel(
     const bf16_t* __restrict__ q, const au32x4* __restrict__ kp, const au32x4* __restrict__ vp,
-    int R, const int4* __restrict__ rowinfo, const int4* __restrict__ tileinfo, int4 one_seq,
-    int Hq, int Hkv, float scale_log2e, bf16_t* __restrict__ out, AttnSplit sp) {
+    int R, const int4* __restrict__ rowinfo, const int4* __restrict__ pairs, int npairs,
+    int4 one_seq, int Hq, int Hkv, float scale_log2e, bf16_t* __restrict__ out, AttnSplit sp) {
   constexpr int HB = HD / 32, HT = HD / 16, NW = 8;
   extern __shared__ float4 lds[];
   // scalar wave index: no MFMA may sit under a condition the compiler could treat as divergent
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int kvh = blockIdx.x, G = Hq / Hkv, MT = (R + 15) >> 4;
-  const int mt = blockIdx.y % MT, gq = blockIdx.y / MT;
-  // cache offset, positions, keys per slab, many-rows flag: from the table, or (tileinfo ==
-  // NULL: a single sequence) from the arguments, which saves a dependent load
-  const int4 ti = tileinfo ? tileinfo[mt] : one_seq;
-  if (ti.w != 0) return;         // that sequence's tiles belong to the other kernel
+  // The block's (row tile, sequence) pair: the few-row sequences are packed into the row list
+  // without padding, so a tile can hold rows of two of them; it is then visited once for each,
+  // and a visit serves only the rows of its own sequence.  pairs == NULL: a single sequence,
+  // every tile is its own (one_seq).  Entry: row tile, cache offset, positions, keys per slab.
+  int mt, gq;
+  int4 ti;
+  if (pairs) {
+    const int4 pr = pairs[blockIdx.y % npairs];
+    mt = pr.x; gq = blockIdx.y / npairs;
+    ti = make_int4(pr.y, pr.z, pr.w, 0);
+  } else {
+    mt = blockIdx.y % MT; gq = blockIdx.y / MT;
+    ti = one_seq;
+    if (ti.w != 0) return;  // a many-row sequence: the other kernel's
+  }
   const int T = ti.y, Tpad = ti.z;
   const int nchunks = (T + 31) >> 5, KB32 = Tpad >> 5;
   const int qcol = lane & 15, grp = lane >> 4;
@@ -149,7 +159,8 @@ __global__ __launch_bounds__(512) void attn_mfma_split_kernel(
   // ---- Q fragments (B operand): lane (query qcol, group grp) holds 8 hd columns -------------
   const int qrow = mt * 16 + qcol, qhead = kvh * G + gq;
   const int qr = qrow < R ? qrow : 0;
-  const bool qvalid = qrow < R && rowinfo[qr].x >= 0;
+  const int4 qri = rowinfo[qr];
+  const bool qvalid = qrow < R && qri.x >= 0 && qri.z == ti.x;  // a row of this pair's sequence
   bf16x8 qf[HB];
 #pragma unroll
   for (int hb = 0; hb < HB; ++hb) {
@@ -243,8 +254,7 @@ __global__ __launch_bounds__(512) void attn_mfma_split_kernel(
       // lane holds hd rows h*16 + grp*4 .. +3 of query qcol
       const float inv = 1.0f / l_all;
       uint2 pk = make_uint2(pack2_bf16(o.x * inv, o.y * inv), pack2_bf16(o.z * inv, o.w * inv));
-      if (!qvalid) pk = make_uint2(0u, 0u);  // padding rows of the list read as zeros downstream
-      if (qrow < R) *(uint2*)(out + packed_act_index(qrow, qhead * HD + h * 16 + grp * 4, MT)) = pk;
+      if (qvalid) *(uint2*)(out + packed_act_index(qrow, qhead * HD + h * 16 + grp * 4, MT)) = pk;
     } else {
       st_agent(mine + (h * 64 + lane) * 4, o.x, o.y);
       st_agent(mine + (h * 64 + lane) * 4 + 2, o.z, o.w);
@@ -264,7 +274,7 @@ __global__ __launch_bounds__(512) void attn_mfma_split_kernel(
     *flag = (old == nz - 1);
   }
   __syncthreads();
-  if (*flag == 0 || qrow >= R) return;
+  if (*flag == 0 || !qvalid) return;
   const float* base = sp.part + (size_t)pair * nz * PSLOT;
   float m_fin = -INFINITY, l_fin = 0.f;
   for (int z = 0; z < nz; ++z) m_fin = fmaxf(m_fin, ld_agent(base + (size_t)z * PSLOT + HT * 256 + lane * 2).x);
@@ -281,7 +291,6 @@ __global__ __launch_bounds__(512) void attn_mfma_split_kernel(
     }
     const float inv = 1.0f / l_fin;
     uint2 pk = make_uint2(pack2_bf16(o.x * inv, o.y * inv), pack2_bf16(o.z * inv, o.w * inv));
-    if (!qvalid) pk = make_uint2(0u, 0u);
     *(uint2*)(out + packed_act_index(qrow, qhead * HD + h * 16 + grp * 4, MT)) = pk;
   }
 }
@@ -405,10 +414,10 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_shared_kernel(
 
 template <int HD>
 static void launch_attn_mfma_hd(const bf16_t* q, const uint4* kp, const uint4* vp, int R,
-                                const int4* rowinfo, const int4* tileinfo, int4 one_seq,
-                                bool has_small, bool has_large, int max_T, int Hq, int Hkv,
-                                bf16_t* out, float* part, size_t part_floats, int* tickets,
-                                hipStream_t s) {
+                                const int4* rowinfo, const int4* tileinfo, const int4* pairs,
+                                int npairs, int4 one_seq, bool has_small, bool has_large,
+                                int max_T, int Hq, int Hkv, bf16_t* out, float* part,
+                                size_t part_floats, int* tickets, hipStream_t s) {
   const int G = Hq / Hkv, MT = (R + 15) / 16;
   const float sc = 1.4426950408889634f / sqrtf((float)HD);
   if (has_small) {
@@ -424,23 +433,24 @@ static void launch_attn_mfma_hd(const bf16_t* q, const uint4* kp, const uint4* v
     // Key slices over blocks pay only for long contexts (the pieces go through write-through
     // stores and a ticket, about 3 us): from 64 chunks on, two or more chunks per wave, and no
     // more blocks than compute units.
-    const int nchunks = (max_T + 31) / 32, pairs = G * MT * Hkv;
+    const int nvis = pairs ? npairs : MT;  // (row tile, sequence) visits
+    const int nchunks = (max_T + 31) / 32, blocks1 = G * nvis * Hkv;
     constexpr size_t PSLOT = (HD / 16) * 256 + 128;
     int nz = 1;
-    if (nchunks >= 64 && pairs <= 256) {
+    if (nchunks >= 64 && blocks1 <= 256) {
       nz = nchunks / 16;
-      if (nz > 256 / pairs) nz = 256 / pairs;
+      if (nz > 256 / blocks1) nz = 256 / blocks1;
       if (nz > 8) nz = 8;
       if (nz < 1) nz = 1;
     }
-    while (nz > 1 && (size_t)pairs * nz * PSLOT > part_floats) --nz;
+    while (nz > 1 && (size_t)blocks1 * nz * PSLOT > part_floats) --nz;
     if (!part || !tickets) nz = 1;
     AttnSplit sp;
     sp.part = part;
     sp.tickets = tickets;
-    attn_mfma_split_kernel<HD><<<dim3(Hkv, G * MT, nz), 512, smem, s>>>(
-        q, (const au32x4*)kp, (const au32x4*)vp, R, rowinfo, tileinfo, one_seq, Hq, Hkv, sc, out,
-        sp);
+    attn_mfma_split_kernel<HD><<<dim3(Hkv, G * nvis, nz), 512, smem, s>>>(
+        q, (const au32x4*)kp, (const au32x4*)vp, R, rowinfo, pairs, npairs, one_seq, Hq, Hkv, sc,
+        out, sp);
   }
   if (has_large) {
     // two query tiles per wave halve the LDS reads per MFMA, but only pay once the grid still
@@ -462,16 +472,18 @@ static void launch_attn_mfma_hd(const bf16_t* q, const uint4* kp, const uint4* v
 }
 
 void launch_attention_mfma(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int R,
-                           const int4* rowinfo, const int4* tileinfo, int4 one_seq,
-                           bool has_small, bool has_large, int max_T, int Hq, int Hkv, int hd,
-                           bf16_t* out, float* part, size_t part_floats, int* tickets,
-                           hipStream_t s) {
+                           const int4* rowinfo, const int4* tileinfo, const int4* pairs,
+                           int npairs, int4 one_seq, bool has_small, bool has_large, int max_T,
+                           int Hq, int Hkv, int hd, bf16_t* out, float* part, size_t part_floats,
+                           int* tickets, hipStream_t s) {
   if (R <= 0) return;
   if (hd == 64)
-    launch_attn_mfma_hd<64>(q, (const uint4*)kc, (const uint4*)vc, R, rowinfo, tileinfo, one_seq,
+    launch_attn_mfma_hd<64>(q, (const uint4*)kc, (const uint4*)vc, R, rowinfo, tileinfo, pairs,
+                            npairs, one_seq,
                             has_small, has_large, max_T, Hq, Hkv, out, part, part_floats, tickets, s);
   else
-    launch_attn_mfma_hd<128>(q, (const uint4*)kc, (const uint4*)vc, R, rowinfo, tileinfo, one_seq,
+    launch_attn_mfma_hd<128>(q, (const uint4*)kc, (const uint4*)vc, R, rowinfo, tileinfo, pairs,
+                             npairs, one_seq,
                              has_small, has_large, max_T, Hq, Hkv, out, part, part_floats, tickets,
                              s);
 }
