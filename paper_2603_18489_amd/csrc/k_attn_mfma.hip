@@ -61,8 +61,9 @@ __device__ __forceinline__ void attn_chunk_tile(const bf16x8 (&kf)[2][HB], const
   }
   float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
                    fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
-  mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  // (lane swaps in the vector ALU: the cross-lane path through LDS costs four round trips here)
+  mx = fmaxf(mx, other_row(mx));
+  mx = fmaxf(mx, other_half(mx));
   const float m_new = fmaxf(m_run, mx * scale_log2e);  // scale > 0: max commutes with it
   float rs = 0.f;
 #pragma unroll
@@ -70,8 +71,8 @@ __device__ __forceinline__ void attn_chunk_tile(const bf16x8 (&kf)[2][HB], const
     sv[e] = exp2f(fmaf(sv[e], scale_log2e, -m_new));
     rs += sv[e];
   }
-  rs += __shfl_xor(rs, 16, 64);
-  rs += __shfl_xor(rs, 32, 64);
+  rs += other_row(rs);
+  rs += other_half(rs);
   // the accumulators are rescaled only when some query of the wave saw a new maximum
   if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
     const float alpha = exp2f(m_run - m_new);  // 0 on the first chunk, 1 where nothing changed
@@ -306,12 +307,15 @@ template <int N> __device__ __forceinline__ void attn_wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+// Chunks of the LDS ring (a deeper ring was measured: no gain, the loop is not waiting on loads).
+constexpr int kAttnStages = 3;
+
 template <int HD, int QT, int NW>
 __global__ __launch_bounds__(NW * 64) void attn_mfma_shared_kernel(
     const bf16_t* __restrict__ q, const au32x4* __restrict__ kp, const au32x4* __restrict__ vp,
     int R, const int4* __restrict__ rowinfo, const int4* __restrict__ tileinfo, int4 one_seq,
     int Hq, int Hkv, float scale_log2e, bf16_t* __restrict__ out) {
-  constexpr int HB = HD / 32, HT = HD / 16, NSTAGE = 3;
+  constexpr int HB = HD / 32, HT = HD / 16, NSTAGE = kAttnStages;
   constexpr int NFRAG = 2 * HB + HT, LF = NFRAG / NW;
   static_assert(NFRAG % NW == 0, "fragments per chunk must divide over the waves");
   extern __shared__ au32x4 ring[];  // [NSTAGE][NFRAG][64]
@@ -456,15 +460,24 @@ static void launch_attn_mfma_hd(const bf16_t* q, const uint4* kp, const uint4* v
     // two query tiles per wave halve the LDS reads per MFMA, but only pay once the grid still
     // covers the chip's 256 compute units
     constexpr int NW = 8, NFRAG = 2 * (HD / 32) + HD / 16;
+    constexpr size_t ring_bytes = (size_t)kAttnStages * NFRAG * 1024;
+    static bool ring_attr_set = false;
+    if (ring_bytes > 48 * 1024 && !ring_attr_set) {
+      (void)hipFuncSetAttribute((const void*)attn_mfma_shared_kernel<HD, 1, NW>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)ring_bytes);
+      (void)hipFuncSetAttribute((const void*)attn_mfma_shared_kernel<HD, 2, NW>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)ring_bytes);
+      ring_attr_set = true;
+    }
     const int tiles = G * ((MT + 15) & ~15);
     if ((tiles / (2 * NW)) * Hkv >= 256) {
       dim3 grid(tiles / (2 * NW), Hkv);
-      attn_mfma_shared_kernel<HD, 2, NW><<<grid, NW * 64, 3 * NFRAG * 1024, s>>>(
+      attn_mfma_shared_kernel<HD, 2, NW><<<grid, NW * 64, ring_bytes, s>>>(
           q, (const au32x4*)kp, (const au32x4*)vp, R, rowinfo, tileinfo, one_seq, Hq, Hkv, sc,
           out);
     } else {
       dim3 grid(tiles / NW, Hkv);
-      attn_mfma_shared_kernel<HD, 1, NW><<<grid, NW * 64, 3 * NFRAG * 1024, s>>>(
+      attn_mfma_shared_kernel<HD, 1, NW><<<grid, NW * 64, ring_bytes, s>>>(
           q, (const au32x4*)kp, (const au32x4*)vp, R, rowinfo, tileinfo, one_seq, Hq, Hkv, sc,
           out);
     }

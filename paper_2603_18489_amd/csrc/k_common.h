@@ -49,6 +49,15 @@ __device__ __forceinline__ float other_half(float x) {
   return __uint_as_float((threadIdx.x & 32) ? r[0] : r[1]);
 }
 
+// value held by the lane 16 positions away within its 32-lane half, lane ^ 16 (one
+// v_permlane16_swap: rows of 16 lanes; with both operands x it returns {[r0,r0,r2,r2],
+// [r1,r1,r3,r3]})
+__device__ __forceinline__ float other_row(float x) {
+  const unsigned u = __float_as_uint(x);
+  auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  return __uint_as_float((threadIdx.x & 16) ? r[0] : r[1]);
+}
+
 template <typename T> __device__ __forceinline__ float load_f32(const T* p);
 template <> __device__ __forceinline__ float load_f32<float>(const float* p) { return *p; }
 template <> __device__ __forceinline__ float load_f32<bf16_t>(const bf16_t* p) { return bf16_to_f32(*p); }
