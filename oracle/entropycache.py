@@ -28,11 +28,18 @@ Readings taken where the paper is silent or inconsistent (each is listed in the 
   * model details: pre-norm Llama block without biases, untied embedding / LM head, rotate-half
     RoPE on absolute positions, softmax scale 1/sqrt(head_dim), grouped-query head a uses KV
     head a // (Hq/Hkv), the cache holds post-RoPE keys, logits only for the rows of M^t;
-  * `logit_scale` multiplies the LM-head output (1.0 reproduces the paper's model).
+  * `logit_scale` multiplies the LM-head output (1.0 reproduces the paper's model);
+  * optional decoding rules (defaults off): confidence-based parallel decoding unmasks every
+    block row whose confidence is strictly above `conf_threshold`, the n most confident in any
+    case (the experimental setup names the rule and the threshold 0.9, not its details);
+    `gate_metric` selects the thresholding variable of the ablation (entropy sum, max
+    confidence; a confidence skips at or above tau); `schedule` = 1 is sliding-window decoding
+    with M^t = the leftmost `block` still-masked slots (the paper gives no advance rule).
 
 Pins (tests/test_oracle_*.py): closed forms of the entropy, RoPE identities, a dense
 no-cache forward written independently with explicit T x T scores, partial-step invariants,
-and brute-force enumeration of Eq. 3 / tau_R on tiny histories.
+brute-force enumeration of Eq. 3 / tau_R on tiny histories, and for the optional rules their
+limiting cases and the per-row statistics a step reports.
 End-to-end generations are "parity unpinned" against the paper: it prints no token-level
 values and its weights and datasets are not available.
 """
