@@ -160,35 +160,51 @@ enum {
   EC_DBG_ROW_STATS   /* float32 [n_block_rows, 4]: token id (as float), confidence, entropy, max logit of the last step's rows */
 };
 
-/* Bytes of DEVICE workspace ec_init needs for this model, decode setup and prompt length
- * (KV cache, activations, state, and for bfloat16 a re-tiled copy of the matrices).
- * Returns 0 on invalid arguments. */
+/* Bytes of DEVICE workspace ec_init needs for this model, decode setup and prompt lengths
+ * (every sequence's KV cache - the cached K, V of the appendix algorithm - activations, state,
+ * and for bfloat16 a re-tiled copy of the matrices).  Pure host computation.
+ * Returns 0 on NULL arguments or a configuration ec_init would reject. */
 size_t ec_workspace_bytes(const ec_model_cfg *model, const ec_decode_cfg *decode,
                           const int32_t *prompt_lens /*HOST [batch]*/);
 
-/* Creates a context: validates the configuration, carves the workspace, uploads the prompt,
- * fills the generation slots with mask_id, clears the history (t = 1, flag = recompute).
+/* Creates a context (initialisation lines of Algorithm 1 and of the appendix algorithm):
+ * validates the configuration, carves the workspace, uploads the prompts, fills the generation
+ * slots with mask_id, clears the history (t = 1, flag = recompute), re-tiles bfloat16 matrices.
  * No forward pass runs here; the first step is FULL (appendix algorithm, t == 1 branch).
+ *  out         receives the context (NULL on failure); destroy it with ec_destroy
+ *  model, weights, decode   HOST structs, copied; the weight tensors they point to are DEVICE
+ *              memory, BORROWED for the life of the context and never written
  *  prompt_ids  HOST, the batch's prompts one after the other, prompt_lens[b] ids each; any id
  *              in [0, vocab) is accepted
  *  workspace   DEVICE, 256-byte aligned, >= ec_workspace_bytes(); BORROWED
- *  hip_stream  hipStream_t to enqueue on (NULL = the default stream)                          */
+ *  hip_stream  hipStream_t to enqueue on (NULL = the default stream)
+ * Errors: EC_ERR_ARG (NULL pointer, prompt id outside the vocabulary), EC_ERR_CONFIG (shape or
+ * decode setting the kernels do not support; ec_last_error(NULL) names it), EC_ERR_WORKSPACE,
+ * EC_ERR_HIP.  Synchronises the stream once. */
 int ec_init(ec_ctx **out, const ec_model_cfg *model, const ec_weights *weights,
             const ec_decode_cfg *decode, const int32_t *prompt_ids, const int32_t *prompt_lens,
             void *workspace, size_t workspace_bytes, void *hip_stream);
 
-/* Restarts the generation of an existing context with new prompts of the SAME lengths. */
+/* Restarts the generation of an existing context with new prompts of the SAME lengths (state
+ * as after ec_init; the cache contents become meaningless until the next FULL step).
+ * Errors: EC_ERR_ARG, EC_ERR_HIP. */
 int ec_reset(ec_ctx *ctx, const int32_t *prompt_ids /*HOST*/);
 
-/* One denoising step (Algorithm 1 loop body) of every unfinished sequence.  mode = EC_AUTO
- * follows each sequence's entropy flag; EC_FULL / EC_PARTIAL override it for all of them.
- * out: HOST, batch ec_step_result; a sequence that had finished earlier reports done = 1 and
- * zeros. */
+/* One denoising step (Algorithm 1 loop body; appendix algorithm: full branch or partial branch,
+ * decode, history update, Eq. 1 - 3, flag) of every unfinished sequence.  mode = EC_AUTO follows
+ * each sequence's entropy flag; EC_FULL / EC_PARTIAL override it for all of them.
+ * out: HOST, batch ec_step_result, written on success only; a sequence that had finished earlier
+ * reports done = 1 and zeros.
+ * Errors: EC_ERR_ARG (NULL, bad mode), EC_ERR_STATE (every sequence finished; EC_PARTIAL for a
+ * sequence that has not run a FULL step yet) - the state is untouched then - and EC_ERR_HIP.
+ * Synchronises the stream once, for the read-back. */
 int ec_step(ec_ctx *ctx, int mode, ec_step_result *out);
 
 /* Teacher forcing: runs the forward pass and the vocabulary reduction in `mode`, reports the
  * step's own choice in `out`, but commits the caller's n (position, token) pairs (HOST arrays;
- * n may be 0) to x, the mask set and the history. */
+ * n may be 0) to x, the mask set and the history; the flag follows the committed tokens.
+ * Batch 1 only.  Errors as ec_step, plus EC_ERR_ARG for a position that is not a masked
+ * generation slot, a token outside the vocabulary, a repeated position, n > EC_MAX_N. */
 int ec_step_forced(ec_ctx *ctx, int mode, int32_t n, const int32_t *positions,
                    const int32_t *tokens, ec_step_result *out);
 /* The same for a batch: modes[b] and n[b] per sequence (entries of finished sequences are
@@ -196,9 +212,10 @@ int ec_step_forced(ec_ctx *ctx, int mode, int32_t n, const int32_t *positions,
 int ec_step_forced_batch(ec_ctx *ctx, const int32_t *modes, const int32_t *n,
                          const int32_t *positions, const int32_t *tokens, ec_step_result *out);
 
-/* Runs EC_AUTO steps until no masked position is left in any sequence (Algorithm 1).
- * out_tokens: HOST [batch, gen_len] final ids of the generation slots.  stats may be NULL; its
- * full_steps / partial_steps count sequence-steps. */
+/* Runs EC_AUTO steps until no masked position is left in any sequence (Algorithm 1, whole
+ * loop; returns the generated part of x).  out_tokens: HOST [batch, gen_len] final ids of the
+ * generation slots.  stats may be NULL; its full_steps / partial_steps count sequence-steps.
+ * Errors: those of ec_step; on failure out_tokens is not written. */
 int ec_generate(ec_ctx *ctx, int32_t *out_tokens, ec_gen_stats *stats);
 
 /* Per-kernel-class device timing with HIP events on the context's stream.  While enabled every
@@ -207,8 +224,9 @@ int ec_generate(ec_ctx *ctx, int32_t *out_tokens, ec_gen_stats *stats);
 int ec_profile_enable(ec_ctx *ctx, int on);
 int ec_profile_read(ec_ctx *ctx, ec_profile *out);
 
-/* Copies internal state to the host (synchronises the stream).  bytes must not exceed the
- * size of the item; the copy is truncated to bytes. */
+/* Copies internal state of one sequence to the host (synchronises the stream; test and
+ * diagnosis aid, not part of the method).  bytes must not exceed the size of the item
+ * (EC_ERR_ARG otherwise); the copy is truncated to bytes. */
 int ec_debug_read(ec_ctx *ctx, int what, int layer, void *host_dst, size_t bytes); /* sequence 0 */
 int ec_debug_read_seq(ec_ctx *ctx, int seq, int what, int layer, void *host_dst, size_t bytes);
 
