@@ -123,6 +123,19 @@ def test_batched_sequences_match_their_own_oracle_runs(hq, hkv, hd, plens, N, bl
         assert s["finished_early"] >= 1
 
 
+def test_tile_counts_that_do_not_divide_the_block_widths():
+    """Feature counts whose 16-row tiles are not a multiple of the tiles a GEMM block owns:
+    772 gate/up tiles in groups of 3, 257 vocabulary tiles in groups of 4 (the last group of the
+    packed layout is partly empty, the last block's surplus tiles must be dropped)."""
+    cfg = small_cfg("bf16", 4, 2, 64, f=6176, vocab=4112)
+    w = ec_inputs.make_weights(cfg, 37, gain_jitter=0.1)
+    dec = ec_inputs.DecodeCfg(gen_len=40, block=32, k_recent=2, tokens_per_step=2, tau=3.0)
+    prompt = ec_inputs.make_prompt(cfg.vocab, 150, 8)    # 190 rows in FULL steps: tiled GEMMs
+    s = run_teacher_forced(cfg, w, dec, prompt, TOL["bf16"])
+    print(s)
+    assert s["modes"][eco.PARTIAL] >= 1 and s["modes"][eco.FULL] >= 1
+
+
 def _random_case(seed):
     r = np.random.RandomState(seed)
     hkv, hd = int(r.choice([1, 2, 4])), int(r.choice([64, 128]))
