@@ -164,6 +164,18 @@ def test_random_configurations(seed):
     print(c, s)
 
 
+def test_largest_batch():
+    """EC_MAX_BATCH sequences with ragged prompts, every one against its own oracle run."""
+    cfg = small_cfg("bf16", 4, 2, 64, scale=13.0)
+    w = ec_inputs.make_weights(cfg, 41, gain_jitter=0.1)
+    B = ec.EC_MAX_BATCH
+    dec = ec_inputs.DecodeCfg(gen_len=12, block=8, k_recent=2, tokens_per_step=2, tau=2.5, batch=B)
+    prompts = [ec_inputs.make_prompt(cfg.vocab, 1 + (7 * b) % 23, 300 + b) for b in range(B)]
+    s = run_teacher_forced_batch(cfg, w, dec, prompts, TOL["bf16"], check_cache_every=3)
+    print(s)
+    assert s["steps"] == 6 and s["modes"][eco.FULL] >= B
+
+
 def test_batched_generate_runs_every_sequence_to_the_end():
     """ec_generate on a batch: free-running, sequences in different modes side by side; every
     generation slot ends up decoded, the counters add up, and a reset reproduces the run."""
