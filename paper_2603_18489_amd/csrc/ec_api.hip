@@ -158,6 +158,7 @@ const char* check_config(const ec_model_cfg* m, const ec_decode_cfg* d, const in
   if (m->head_dim != 64 && m->head_dim != 128) return "head_dim must be 64 or 128";
   if (m->n_heads % m->n_kv_heads != 0) return "n_heads must be a multiple of n_kv_heads";
   if (m->mask_id < 0 || m->mask_id >= m->vocab) return "mask_id outside the vocabulary";
+  if (m->vocab > 163840) return "vocab larger than 163840";  // staging room of the decision kernel
   if (!(m->rms_eps >= 0.f) || !(m->rope_base > 1.f) || !(m->logit_scale > 0.f))
     return "rms_eps >= 0, rope_base > 1 and logit_scale > 0 are required";
   if (m->d_model % 8 || m->d_ffn % 8) return "d_model and d_ffn must be multiples of 8";

@@ -65,6 +65,9 @@ __device__ __forceinline__ VTuple vt_shfl_down(const VTuple& v, int o) {
 }
 
 constexpr int VR_CHUNK = 2048;  // logits per block
+constexpr int kMergeRows = 32;   // rows whose partials the decision kernel stages at a time
+constexpr int kMaxParts = 80;    // partials per row it has room for: vocabularies up to 163840
+constexpr int kHistLds = 4096;   // generation lengths up to this keep the history in LDS
 
 int vocab_reduce_parts(int V) { return (V + VR_CHUNK - 1) / VR_CHUNK; }
 
@@ -158,6 +161,8 @@ __global__ __launch_bounds__(256) void decide_kernel(DecideArgs a) {
   __shared__ int s_taken[EC_MAX_BLOCK];
   __shared__ int scratch[4];
   __shared__ float sh_f[2];
+  __shared__ float4 s_part[kMergeRows * kMaxParts];
+  __shared__ int s_hist[kHistLds];
   const int tid = threadIdx.x;
   DevState st = *a.st;  // every thread holds a private copy; thread 0 writes it back
   const int t = st.t;
@@ -166,26 +171,36 @@ __global__ __launch_bounds__(256) void decide_kernel(DecideArgs a) {
 
   if (!a.init_only) {
     // ---- merge the vocabulary partials of each block row (fixed order) ----------------------
-    if (tid < a.n_mb) {
-      VTuple v = vt_identity();
-      for (int p = 0; p < a.nparts; ++p) {
-        float4 q = a.partials[(size_t)tid * a.nparts + p];
-        VTuple o = {q.x, __float_as_int(q.y), q.z, q.w};
-        v = vt_merge(v, o);
+    // 32 rows at a time: the whole block fetches their partials into LDS in one sweep (a row's
+    // thread fetching them one by one would wait for memory nparts times), then one thread per
+    // row merges them in part order.
+    for (int r0 = 0; r0 < a.n_mb; r0 += kMergeRows) {
+      const int nr = min(kMergeRows, a.n_mb - r0);
+      for (int i = tid; i < nr * a.nparts; i += 256)
+        s_part[i] = a.partials[(size_t)r0 * a.nparts + i];
+      __syncthreads();
+      if (tid < nr) {
+        const int row = r0 + tid;
+        VTuple v = vt_identity();
+        for (int p = 0; p < a.nparts; ++p) {
+          float4 q = s_part[tid * a.nparts + p];
+          VTuple o = {q.x, __float_as_int(q.y), q.z, q.w};
+          v = vt_merge(v, o);
+        }
+        float conf = 1.0f / v.s;                 // max probability = e^0 / S
+        float H = logf(v.s) - v.t / v.s;         // -sum p ln p
+        H = fmaxf(H, 0.f);
+        s_tok[row] = v.idx;
+        s_conf[row] = conf;
+        s_H[row] = H;
+        s_taken[row] = 0;
+        a.row_stats[row * 4 + 0] = (float)v.idx;
+        a.row_stats[row * 4 + 1] = conf;
+        a.row_stats[row * 4 + 2] = H;
+        a.row_stats[row * 4 + 3] = v.m;
       }
-      float conf = 1.0f / v.s;                 // max probability = e^0 / S
-      float H = logf(v.s) - v.t / v.s;         // -sum p ln p
-      H = fmaxf(H, 0.f);
-      s_tok[tid] = v.idx;
-      s_conf[tid] = conf;
-      s_H[tid] = H;
-      s_taken[tid] = 0;
-      a.row_stats[tid * 4 + 0] = (float)v.idx;
-      a.row_stats[tid * 4 + 1] = conf;
-      a.row_stats[tid * 4 + 2] = H;
-      a.row_stats[tid * 4 + 3] = v.m;
+      __syncthreads();
     }
-    __syncthreads();
     // ---- decode(): most confident rows first; ties -> lowest position (= lowest row) --------
     if (tid == 0) {
       ec_step_result& R = a.out->r;
@@ -254,10 +269,17 @@ __global__ __launch_bounds__(256) void decide_kernel(DecideArgs a) {
     if (a.mode_run == EC_FULL) t_lastfull = t;
     int kth = INT_MIN;
     if (a.k_recent > 0) {
+      // the bisection reads the history log2(t) times: from LDS if it fits
+      const bool in_lds = N <= kHistLds;
+      if (in_lds) {
+        for (int i = tid; i < N; i += 256) s_hist[i] = a.hist[i];
+        __syncthreads();
+      }
       int lo = 1, hi = t, found = INT_MIN;
       while (lo <= hi) {  // uniform across the block
         int mid = (lo + hi) >> 1, c = 0;
-        for (int i = tid; i < N; i += 256) c += (a.hist[i] >= mid);
+        if (in_lds) { for (int i = tid; i < N; i += 256) c += (s_hist[i] >= mid); }
+        else { for (int i = tid; i < N; i += 256) c += (a.hist[i] >= mid); }
         c = block_sum_int(c, scratch);
         if (c >= a.k_recent) { found = mid; lo = mid + 1; } else { hi = mid - 1; }
       }
