@@ -62,7 +62,10 @@ enum {
 
 /* Model shape.  "Bidirectional Llama-style": pre-norm blocks, RMSNorm, rotate-half RoPE on
  * absolute positions, grouped-query attention without mask, SwiGLU MLP, no biases, untied
- * embedding and LM head.  logit_scale multiplies the LM-head output (1.0 = the model as is). */
+ * embedding and LM head.  logit_scale multiplies the LM-head output (1.0 = the model as is).
+ * Supported (EC_ERR_CONFIG otherwise): head_dim 64 or 128; n_heads a multiple of n_kv_heads;
+ * d_model and d_ffn multiples of 8 (bfloat16: of 32, and vocab a multiple of 16); vocab at most
+ * 163840; prompt + generation at most 15000 positions per sequence. */
 typedef struct {
   int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab, mask_id;
   float rms_eps, rope_base, logit_scale;
