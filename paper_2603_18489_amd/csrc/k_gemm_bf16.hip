@@ -579,6 +579,22 @@ __device__ __forceinline__ void tiled_epilogue(const GemmEpi& e, f32x4 (&acc)[WT
   }
 }
 
+// Which (n-block, m-block) a thread block works on.  Blocks go to the 8 XCDs round-robin by
+// their linear index, and each XCD has its own L2: the m-blocks that share an n-block's weight
+// tiles should meet in one L2.  gridDim.x a multiple of 8 gives that by itself.  Otherwise the
+// linear index is first turned into "XCD-major" order (all blocks of XCD 0, then XCD 1, ...)
+// and m runs fastest in that order, so an n-block's m-blocks are neighbours on one XCD.
+__device__ __forceinline__ void tiled_block_xy(int& bx, int& by) {
+  const int gx = gridDim.x, gy = gridDim.y, nb = gx * gy;
+  bx = blockIdx.x; by = blockIdx.y;
+  if ((gx & 7) != 0) {
+    const int lin = blockIdx.y * gx + blockIdx.x, xcd = lin & 7;
+    // blocks before this one in XCD-major order: those of the lower XCDs, then its own earlier ones
+    const int j = xcd * (nb >> 3) + min(xcd, nb & 7) + (lin >> 3);
+    bx = j / gy; by = j - bx * gy;
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // tiled, 4 waves (2x2): wave tile = WTM x WTN fragments, K step 32.  Operands are double-buffered
 // in LDS; global loads run through four register sets, four k-steps ahead.  This variant is the
@@ -617,7 +633,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_tiled4_kernel(const u32x4* __re
   constexpr int LF = (NF + 3) / 4;                             // fragments loaded per wave
   __shared__ u32x4 lds[2][NF][64];
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int mt0 = blockIdx.y * BMT, nt0 = blockIdx.x * BNT;
+  int bx, by;
+  tiled_block_xy(bx, by);
+  const int mt0 = by * BMT, nt0 = bx * BNT;
   const int wm = wave >> 1, wn = wave & 1;
   // blockIdx.z picks one of gridDim.z contiguous K ranges (EPI_PARTIAL; otherwise gridDim.z = 1)
   const int kb_first = (int)(((long)blockIdx.z * KB_all) / gridDim.z);
@@ -726,7 +744,9 @@ void gemm_bf16_tiled8_kernel(
   static_assert(LF * NSTAGE <= 63, "vmcnt counts at most 63 outstanding loads");
   extern __shared__ u32x4 lds[];  // [NSTAGE][NF][64] + one dump fragment
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int mt0 = blockIdx.y * BMT, nt0 = blockIdx.x * BNT;
+  int bx, by;
+  tiled_block_xy(bx, by);
+  const int mt0 = by * BMT, nt0 = bx * BNT;
   const int wm = wave / WN, wn = wave % WN;
   // blockIdx.z picks one of gridDim.z contiguous K ranges (EPI_PARTIAL; otherwise gridDim.z = 1)
   const int kb_first = (int)(((long)blockIdx.z * KB_all) / gridDim.z);
