@@ -320,10 +320,12 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_shared_kernel(
   static_assert(NFRAG % NW == 0, "fragments per chunk must divide over the waves");
   extern __shared__ au32x4 ring[];  // [NSTAGE][NFRAG][64]
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int kvh = blockIdx.y, G = Hq / Hkv, MT = (R + 15) >> 4, MTp = (MT + 15) & ~15;
+  // grid (kv heads, tile groups): the blocks of one head are Hkv apart in launch order, which
+  // for Hkv a multiple of 8 puts them on one XCD, whose L2 then holds the head's K/V once
+  const int kvh = blockIdx.x, G = Hq / Hkv, MT = (R + 15) >> 4, MTp = (MT + 15) & ~15;
   // the block's NW*QT query tiles: one head of the group, consecutive row tiles that all lie in
   // one many-row sequence (such sequences come first and are padded to 16 row tiles) or in none
-  const int t_first = blockIdx.x * NW * QT;
+  const int t_first = blockIdx.y * NW * QT;
   const int gq = t_first / MTp, mt_first = t_first - gq * MTp;
   if (mt_first >= MT) return;
   const int4 ti = tileinfo ? tileinfo[mt_first] : one_seq;
@@ -471,12 +473,12 @@ static void launch_attn_mfma_hd(const bf16_t* q, const uint4* kp, const uint4* v
     }
     const int tiles = G * ((MT + 15) & ~15);
     if ((tiles / (2 * NW)) * Hkv >= 256) {
-      dim3 grid(tiles / (2 * NW), Hkv);
+      dim3 grid(Hkv, tiles / (2 * NW));
       attn_mfma_shared_kernel<HD, 2, NW><<<grid, NW * 64, ring_bytes, s>>>(
           q, (const au32x4*)kp, (const au32x4*)vp, R, rowinfo, tileinfo, one_seq, Hq, Hkv, sc,
           out);
     } else {
-      dim3 grid(tiles / NW, Hkv);
+      dim3 grid(Hkv, tiles / NW);
       attn_mfma_shared_kernel<HD, 1, NW><<<grid, NW * 64, ring_bytes, s>>>(
           q, (const au32x4*)kp, (const au32x4*)vp, R, rowinfo, tileinfo, one_seq, Hq, Hkv, sc,
           out);
