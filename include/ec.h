@@ -14,7 +14,8 @@
  * algorithm".
  *
  * Conventions
- *  - Every call returns EC_OK or a negative error code; it never throws or aborts.  Outputs are
+ *  - Every call returns EC_OK or a negative error code; it never throws or aborts (a failed host
+ *    allocation inside a call comes back as EC_ERR_HOST_MEMORY).  Outputs are
  *    written only on success.  ec_last_error() gives a message for the last failure of a context
  *    (or of ec_init when passed NULL).
  *  - Pointers marked DEVICE are device addresses on the current HIP device; HOST are host
@@ -57,7 +58,8 @@ enum {
   EC_ERR_CONFIG = -2,    /* model / decode configuration outside what the kernels support       */
   EC_ERR_WORKSPACE = -3, /* workspace missing, misaligned or smaller than ec_workspace_bytes()  */
   EC_ERR_STATE = -4,     /* PARTIAL before any FULL step; step after the generation is done     */
-  EC_ERR_HIP = -5        /* a HIP runtime call failed                                           */
+  EC_ERR_HIP = -5,       /* a HIP runtime call failed                                           */
+  EC_ERR_HOST_MEMORY = -6 /* the host ran out of memory inside the call; the context is unusable */
 };
 
 /* Model shape.  "Bidirectional Llama-style": pre-norm blocks, RMSNorm, rotate-half RoPE on
@@ -65,7 +67,11 @@ enum {
  * embedding and LM head.  logit_scale multiplies the LM-head output (1.0 = the model as is).
  * Supported (EC_ERR_CONFIG otherwise): head_dim 64 or 128; n_heads a multiple of n_kv_heads;
  * d_model and d_ffn multiples of 8 (bfloat16: of 32, and vocab a multiple of 16); vocab at most
- * 163840; prompt + generation at most 15000 positions per sequence. */
+ * 163840; prompt + generation at most 15000 positions per sequence.
+ * bfloat16 path: the sum of squares of a row of the residual stream is kept in 44.20 fixed point
+ * (exact to 5e-7 per 16 features, which is all a row needs down to sums of squares of ~1e-3); it
+ * saturates at about 4e12 (|h| of ~3e4 at d_model 4096) instead of overflowing - such a row's
+ * RMSNorm output is then too large rather than garbage. */
 typedef struct {
   int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab, mask_id;
   float rms_eps, rope_base, logit_scale;
@@ -112,16 +118,18 @@ typedef struct {
   int32_t schedule;
 } ec_decode_cfg;
 
-/* What one step did.  positions/tokens/entropy/confidence list the step's OWN decode() choice
- * (n_unmasked entries, most confident first); max_entropy is E of that choice (Eq. 1);
- * max_entropy holds the gate value (the maximum entropy unless gate_metric says otherwise);
- * next_mode is EC_PARTIAL iff it passes the threshold (max entropy: <= tau).  Under ec_step_forced the caller's tokens are
- * committed instead, but these fields still report the step's own choice. */
+/* What one step did.  positions / tokens / entropy / confidence list the step's OWN decode()
+ * choice (n_unmasked entries, most confident first).  max_entropy is the gate value of that
+ * choice: the maximum entropy E of Eq. 1, or what gate_metric selects instead.  next_mode is
+ * EC_PARTIAL iff that value passes the threshold (max entropy: E <= tau).
+ * Under ec_step_forced the caller's tokens are committed instead and the context's flag follows
+ * THEIR gate value: these fields still describe the step's own choice, so next_mode is then what
+ * the step would have chosen, not necessarily what EC_AUTO runs next. */
 typedef struct {
   int32_t n_unmasked;
   int32_t done;         /* 1 when no masked position is left after this step                   */
   int32_t mode_run;     /* EC_FULL | EC_PARTIAL: what this step executed                        */
-  int32_t next_mode;    /* what EC_AUTO will execute next                                       */
+  int32_t next_mode;    /* EC_AUTO's next mode (forced steps: what the own choice would give)   */
   int32_t n_query_rows; /* |S|: rows that recomputed Q/K/V in this step                         */
   int32_t step_index;   /* t of this step, starting at 1                                        */
   int32_t n_block_rows; /* |M^t|: masked rows of the current block = rows that got logits       */
@@ -232,6 +240,23 @@ int ec_profile_read(ec_ctx *ctx, ec_profile *out);
  * (EC_ERR_ARG otherwise); the copy is truncated to bytes. */
 int ec_debug_read(ec_ctx *ctx, int what, int layer, void *host_dst, size_t bytes); /* sequence 0 */
 int ec_debug_read_seq(ec_ctx *ctx, int seq, int what, int layer, void *host_dst, size_t bytes);
+
+/* The O(V) reduction behind the method's decision (Eq. 1 and the complexity discussion of the
+ * Method section) as a call of its own, for logits that already sit on the device: for each row
+ * of a float32 matrix, stats[row] = (argmax token id as a float, lowest id on ties; confidence =
+ * maximum softmax probability; entropy -sum p ln p in nats; maximum logit).  One pass over the
+ * logits; partial (max, argmax, sum e, sum e*(z-max)) tuples per 2048 columns are merged in a
+ * fixed order, so the result is bit-reproducible.  A logit of -inf has probability 0.
+ *  logits     DEVICE float32 [rows, vocab], row stride ld elements (ld >= vocab); read only
+ *  rows       0 .. EC_MAX_BLOCK; vocab 2 .. 163840
+ *  stats      DEVICE float32 [rows, 4], 16-byte aligned; written
+ *  workspace  DEVICE, 256-byte aligned, >= ec_row_entropy_workspace_bytes(rows, vocab) (0 for
+ *             arguments outside the limits); holds the partial tuples; BORROWED for the call
+ * Enqueues on hip_stream (NULL = default stream) and returns without synchronising.
+ * Errors: EC_ERR_ARG, EC_ERR_WORKSPACE, EC_ERR_HIP; ec_last_error(NULL) names the cause. */
+size_t ec_row_entropy_workspace_bytes(int32_t rows, int32_t vocab);
+int ec_row_entropy(const float *logits, int32_t rows, int32_t vocab, size_t ld, float *stats,
+                   void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Frees host-side state only; never frees weights or workspace.  NULL is allowed. */
 void ec_destroy(ec_ctx *ctx);

@@ -20,6 +20,7 @@ EC_FULL, EC_PARTIAL, EC_AUTO = 0, 1, 2
 EC_GATE_MAX_ENTROPY, EC_GATE_ENTROPY_SUM, EC_GATE_MAX_CONFIDENCE = 0, 1, 2
 EC_SCHED_BLOCKS, EC_SCHED_SLIDING = 0, 1
 EC_OK, EC_ERR_ARG, EC_ERR_CONFIG, EC_ERR_WORKSPACE, EC_ERR_STATE, EC_ERR_HIP = 0, -1, -2, -3, -4, -5
+EC_ERR_HOST_MEMORY = -6
 (EC_K_EMBED, EC_K_NORM, EC_K_QKV, EC_K_ROPE_KV, EC_K_ATTN, EC_K_OPROJ, EC_K_GATEUP, EC_K_SWIGLU,
  EC_K_DOWN, EC_K_LMHEAD, EC_K_VOCAB_REDUCE, EC_K_DECIDE, EC_K_COUNT) = range(13)
 KERNEL_CLASS_NAMES = ["embed", "norm", "qkv", "rope_kv", "attn", "oproj", "gateup", "swiglu",
@@ -29,7 +30,8 @@ KERNEL_CLASS_NAMES = ["embed", "norm", "qkv", "rope_kv", "attn", "oproj", "gateu
 
 EXPORTS = ["ec_workspace_bytes", "ec_init", "ec_reset", "ec_step", "ec_step_forced",
            "ec_step_forced_batch", "ec_generate", "ec_profile_enable", "ec_profile_read",
-           "ec_debug_read", "ec_debug_read_seq", "ec_destroy", "ec_strerror", "ec_last_error"]
+           "ec_debug_read", "ec_debug_read_seq", "ec_destroy", "ec_strerror", "ec_last_error",
+           "ec_row_entropy_workspace_bytes", "ec_row_entropy"]
 
 
 class ec_model_cfg(C.Structure):
@@ -116,6 +118,10 @@ def load_library() -> C.CDLL:
     lib.ec_debug_read.argtypes = [vp, C.c_int, C.c_int, vp, C.c_size_t]
     lib.ec_debug_read_seq.restype = C.c_int
     lib.ec_debug_read_seq.argtypes = [vp, C.c_int, C.c_int, C.c_int, vp, C.c_size_t]
+    lib.ec_row_entropy_workspace_bytes.restype = C.c_size_t
+    lib.ec_row_entropy_workspace_bytes.argtypes = [C.c_int32, C.c_int32]
+    lib.ec_row_entropy.restype = C.c_int
+    lib.ec_row_entropy.argtypes = [vp, C.c_int32, C.c_int32, C.c_size_t, vp, vp, C.c_size_t, vp]
     lib.ec_destroy.restype = None
     lib.ec_destroy.argtypes = [vp]
     lib.ec_strerror.restype = C.c_char_p
@@ -165,6 +171,27 @@ def weights_to_device(cfg, w: Dict[str, object], device="cuda:0") -> Dict[str, o
     for k, v in w.items():
         out[k] = [up(x) for x in v] if isinstance(v, list) else up(v)
     return out
+
+
+def row_entropy(logits, stream=None):
+    """ec_row_entropy on a float32 CUDA tensor [rows, vocab] (row stride = logits.stride(0)):
+    returns a float32 CUDA tensor [rows, 4] (token, confidence, entropy, max logit).  The
+    workspace is a torch allocation; the call is enqueued on `stream` (default: current)."""
+    import torch
+    lib = load_library()
+    rows, vocab = logits.shape
+    assert logits.dtype == torch.float32 and logits.stride(1) == 1
+    stats = torch.empty((rows, 4), dtype=torch.float32, device=logits.device)
+    need = lib.ec_row_entropy_workspace_bytes(rows, vocab)
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device=logits.device)
+    st = stream if stream is not None else torch.cuda.current_stream()
+    rc = lib.ec_row_entropy(C.c_void_p(logits.data_ptr()), rows, vocab,
+                            logits.stride(0) if rows > 1 else vocab, C.c_void_p(stats.data_ptr()),
+                            C.c_void_p(ws.data_ptr()), need, C.c_void_p(st.cuda_stream))
+    if rc != EC_OK:
+        raise EcError(rc, lib.ec_last_error(None).decode())
+    st.synchronize()     # the workspace is released on return
+    return stats
 
 
 class EntropyCache:

@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libec.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
-SOURCES = ["ec_api.hip", "k_glue.hip", "k_gemm_f32.hip", "k_gemm_bf16.hip", "k_attn.hip", "k_attn_mfma.hip",
+SOURCES = ["ec_api.hip", "ec_rowstats.hip", "k_glue.hip", "k_gemm_f32.hip", "k_gemm_bf16.hip", "k_attn.hip", "k_attn_mfma.hip",
            "k_decide.hip"]
 FLAGS = ["-O3", *os.environ.get("EC_EXTRA_FLAGS", "").split(), "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Wall", "-Wno-unused-function",
          # packed-fp32 code generation is switched off on purpose for the test machines

@@ -51,7 +51,7 @@ struct Buffers {
   // activations
   float* h; void* u; float* qkv; void* q; void* attn; float* gu; void* act; void* u_lm;
   float* logits; float4* partials;
-  // bf16 only: row sums of squares [2L+1][kSumSlots][sumsq_stride] (32.32 fixed point), packed matrices
+  // bf16 only: row sums of squares [2L+1][kSumSlots][sumsq_stride] (44.20 fixed point), packed matrices
   unsigned long long* sumsq; int sumsq_stride;
   float* ksplit_part;  // [kMaxKSplit][T][d] partial products of K-split residual GEMMs; between
                        // them, the key slices of the partial-step attention
@@ -192,6 +192,11 @@ const char* check_config(const ec_model_cfg* m, const ec_decode_cfg* d, const in
 struct ProfEvent { int cls; hipEvent_t a, b; };
 
 }  // namespace
+
+namespace ec {
+// message of a failure that has no context to hang on (ec_init, the context-free calls)
+void set_global_error(const char* msg) { g_init_error = msg; }
+}
 
 struct ec_ctx {
   ec_model_cfg m;
@@ -549,7 +554,7 @@ int run_step(ec_ctx* c, const int32_t* modes, int modes_n, const int32_t* forced
                                   : forward_bf16(c, sp);
   if (rc != EC_OK) return rc;
   { Scope p(c, EC_K_VOCAB_REDUCE);
-    launch_vocab_reduce(c->b.logits, sp.n_lm, c->m.vocab, c->b.partials, c->stream); }
+    launch_vocab_reduce(c->b.logits, sp.n_lm, c->m.vocab, (size_t)c->m.vocab, c->b.partials, c->stream); }
   EC_HIP(c, hipGetLastError());
   DecideArgs a{};
   fill_decide_args(c, a);
@@ -609,22 +614,40 @@ int run_step(ec_ctx* c, const int32_t* modes, int modes_n, const int32_t* forced
 // =============================================================================================
 // C ABI
 // =============================================================================================
+// No exception may cross the C boundary: the bodies run under this guard.
+template <typename Fn> static int guarded(ec_ctx* c, Fn&& fn) {
+  try {
+    return fn();
+  } catch (const std::bad_alloc&) {
+    try { fail(c, EC_ERR_HOST_MEMORY, "out of host memory"); } catch (...) {}
+    return EC_ERR_HOST_MEMORY;
+  } catch (...) {
+    try { fail(c, EC_ERR_ARG, "unexpected exception"); } catch (...) {}
+    return EC_ERR_ARG;
+  }
+}
+
 extern "C" {
 
 size_t ec_workspace_bytes(const ec_model_cfg* model, const ec_decode_cfg* decode,
                           const int32_t* prompt_lens) {
   if (!model || !decode || !prompt_lens) return 0;
   if (decode->batch < 1 || decode->batch > EC_MAX_BATCH) return 0;
-  if (check_config(model, decode, prompt_lens) != nullptr) return 0;
-  Carver c(nullptr);
-  Buffers b;
-  carve(c, *model, *decode, geometry(*model, *decode, prompt_lens), b);
-  return c.off;
+  try {
+    if (check_config(model, decode, prompt_lens) != nullptr) return 0;
+    Carver c(nullptr);
+    Buffers b;
+    carve(c, *model, *decode, geometry(*model, *decode, prompt_lens), b);
+    return c.off;
+  } catch (...) {
+    return 0;
+  }
 }
 
-int ec_init(ec_ctx** out, const ec_model_cfg* model, const ec_weights* weights,
-            const ec_decode_cfg* decode, const int32_t* prompt_ids, const int32_t* prompt_lens,
-            void* workspace, size_t workspace_bytes, void* hip_stream) {
+static int init_impl(ec_ctx** out, const ec_model_cfg* model, const ec_weights* weights,
+                     const ec_decode_cfg* decode, const int32_t* prompt_ids,
+                     const int32_t* prompt_lens, void* workspace, size_t workspace_bytes,
+                     void* hip_stream) {
   if (!out) return fail(nullptr, EC_ERR_ARG, "out is NULL");
   *out = nullptr;
   if (!model || !weights || !decode || !prompt_lens)
@@ -729,18 +752,29 @@ int ec_init(ec_ctx** out, const ec_model_cfg* model, const ec_weights* weights,
   return EC_OK;
 }
 
+int ec_init(ec_ctx** out, const ec_model_cfg* model, const ec_weights* weights,
+            const ec_decode_cfg* decode, const int32_t* prompt_ids, const int32_t* prompt_lens,
+            void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return guarded(nullptr, [&] {
+    return init_impl(out, model, weights, decode, prompt_ids, prompt_lens, workspace,
+                     workspace_bytes, hip_stream);
+  });
+}
+
 int ec_reset(ec_ctx* ctx, const int32_t* prompt_ids) {
-  if (!ctx) return fail(nullptr, EC_ERR_ARG, "ctx is NULL");
-  if (ctx->g.ptot > 0 && !prompt_ids) return fail(ctx, EC_ERR_ARG, "prompt_ids is NULL");
-  for (size_t i = 0; i < ctx->g.ptot; ++i)
-    if (prompt_ids[i] < 0 || prompt_ids[i] >= ctx->m.vocab)
-      return fail(ctx, EC_ERR_ARG, "prompt id outside the vocabulary");
-  return upload_and_init_state(ctx, prompt_ids);
+  return guarded(ctx, [&]() -> int {
+    if (!ctx) return fail(nullptr, EC_ERR_ARG, "ctx is NULL");
+    if (ctx->g.ptot > 0 && !prompt_ids) return fail(ctx, EC_ERR_ARG, "prompt_ids is NULL");
+    for (size_t i = 0; i < ctx->g.ptot; ++i)
+      if (prompt_ids[i] < 0 || prompt_ids[i] >= ctx->m.vocab)
+        return fail(ctx, EC_ERR_ARG, "prompt id outside the vocabulary");
+    return upload_and_init_state(ctx, prompt_ids);
+  });
 }
 
 int ec_step(ec_ctx* ctx, int mode, ec_step_result* out) {
   const int32_t m = mode;
-  return run_step(ctx, &m, 1, nullptr, nullptr, nullptr, out);
+  return guarded(ctx, [&] { return run_step(ctx, &m, 1, nullptr, nullptr, nullptr, out); });
 }
 
 int ec_step_forced(ec_ctx* ctx, int mode, int32_t n, const int32_t* positions,
@@ -749,37 +783,39 @@ int ec_step_forced(ec_ctx* ctx, int mode, int32_t n, const int32_t* positions,
     return fail(ctx, EC_ERR_ARG, "ec_step_forced is for batch 1; use ec_step_forced_batch");
   if (n < 0) return fail(ctx, EC_ERR_ARG, "n must be >= 0");
   const int32_t m = mode;
-  return run_step(ctx, &m, 1, &n, positions, tokens, out);
+  return guarded(ctx, [&] { return run_step(ctx, &m, 1, &n, positions, tokens, out); });
 }
 
 int ec_step_forced_batch(ec_ctx* ctx, const int32_t* modes, const int32_t* n,
                          const int32_t* positions, const int32_t* tokens, ec_step_result* out) {
   if (!ctx) return fail(nullptr, EC_ERR_ARG, "ctx is NULL");
   if (!n) return fail(ctx, EC_ERR_ARG, "n is NULL");
-  return run_step(ctx, modes, ctx->B, n, positions, tokens, out);
+  return guarded(ctx, [&] { return run_step(ctx, modes, ctx->B, n, positions, tokens, out); });
 }
 
 int ec_generate(ec_ctx* ctx, int32_t* out_tokens, ec_gen_stats* stats) {
   if (!ctx) return fail(nullptr, EC_ERR_ARG, "ctx is NULL");
   if (!out_tokens) return fail(ctx, EC_ERR_ARG, "out_tokens is NULL");
-  auto t0 = std::chrono::steady_clock::now();
-  std::vector<ec_step_result> r(ctx->B);
-  const int32_t m = EC_AUTO;
-  while (!ctx->all_done) {
-    int rc = run_step(ctx, &m, 1, nullptr, nullptr, nullptr, r.data());
-    if (rc != EC_OK) return rc;
-  }
-  for (int b = 0; b < ctx->B; ++b)
-    EC_HIP(ctx, hipMemcpy(out_tokens + (size_t)b * ctx->N, ctx->b.x + ctx->g.x_off[b] + ctx->g.P[b],
-                          (size_t)ctx->N * sizeof(int), hipMemcpyDeviceToHost));
-  if (stats) {
-    stats->steps = ctx->steps_run; stats->full_steps = ctx->full_steps;
-    stats->partial_steps = ctx->partial_steps; stats->tokens = ctx->tokens;
-    stats->rows_recomputed = ctx->rows_recomputed;
-    stats->ms_total = std::chrono::duration<double, std::milli>(
-                          std::chrono::steady_clock::now() - t0).count();
-  }
-  return EC_OK;
+  return guarded(ctx, [&]() -> int {
+    auto t0 = std::chrono::steady_clock::now();
+    std::vector<ec_step_result> r(ctx->B);
+    const int32_t m = EC_AUTO;
+    while (!ctx->all_done) {
+      int rc = run_step(ctx, &m, 1, nullptr, nullptr, nullptr, r.data());
+      if (rc != EC_OK) return rc;
+    }
+    for (int b = 0; b < ctx->B; ++b)
+      EC_HIP(ctx, hipMemcpy(out_tokens + (size_t)b * ctx->N, ctx->b.x + ctx->g.x_off[b] + ctx->g.P[b],
+                            (size_t)ctx->N * sizeof(int), hipMemcpyDeviceToHost));
+    if (stats) {
+      stats->steps = ctx->steps_run; stats->full_steps = ctx->full_steps;
+      stats->partial_steps = ctx->partial_steps; stats->tokens = ctx->tokens;
+      stats->rows_recomputed = ctx->rows_recomputed;
+      stats->ms_total = std::chrono::duration<double, std::milli>(
+                            std::chrono::steady_clock::now() - t0).count();
+    }
+    return EC_OK;
+  });
 }
 
 int ec_profile_enable(ec_ctx* ctx, int on) {
@@ -861,6 +897,7 @@ const char* ec_strerror(int code) {
     case EC_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case EC_ERR_STATE: return "call not valid in the current state";
     case EC_ERR_HIP: return "HIP runtime error";
+    case EC_ERR_HOST_MEMORY: return "out of host memory";
     default: return "unknown error code";
   }
 }

@@ -81,6 +81,9 @@ struct DecideArgs {
   int schedule;            // EC_SCHED_*
 };
 
+// thread-local message behind ec_last_error(NULL)
+void set_global_error(const char* msg);
+
 // ---- launchers (each enqueues on `s`; shapes are validated by the caller) --------------------
 // float32 path
 void launch_embed_f32(const float* emb, const int* x, const int* rows, int M, int d, float* h,
@@ -109,13 +112,13 @@ constexpr int kMaxKSplit = 4;
 constexpr int kSumSlots = 8;
 enum { REPACK_PLAIN = 0, REPACK_ROPE_HALVES = 1, REPACK_LO8 = 2, REPACK_HI8 = 3 };
 
-// What a GEMM epilogue needs (k_gemm_bf16.hip).  Row sums of squares are 32.32 fixed point.
+// What a GEMM epilogue needs (k_gemm_bf16.hip).  Row sums of squares are 44.20 fixed point.
 struct GemmEpi {
   int M;                          // activation rows of this launch
   int MT;                         // m-tiles of the packed buffers written (a_next, act)
   const int* row_sel;             // nullable: activation row m is read from source row row_sel[m]
   const unsigned long long* sumsq_in;  // [kSumSlots][sum_stride], per SOURCE row: the slots add up
-                                       // to the sum of squares of the normed input (32.32)
+                                       // to the sum of squares of the normed input (44.20)
   int sum_stride;
   int w_grp;  // tiles per group of the weight matrix' layout (k_common.h)
   int d_in;                       // its length
@@ -191,7 +194,11 @@ void launch_attention_mfma(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, 
 
 // decision
 int vocab_reduce_parts(int V);
-void launch_vocab_reduce(const float* logits, int n_rows, int V, float4* partials, hipStream_t s);
+// logits [n_rows, V] with row stride ld -> partials [n_rows][vocab_reduce_parts(V)]
+void launch_vocab_reduce(const float* logits, int n_rows, int V, size_t ld, float4* partials,
+                         hipStream_t s);
+// partials -> stats [n_rows] (token id as float, confidence, entropy, max logit)
+void launch_row_stats(const float4* partials, int nparts, int n_rows, float4* stats, hipStream_t s);
 void launch_decide(const DecideArgs& a, int B, hipStream_t s);
 void launch_init_state(int* x, uint8_t* masked, int* hist, DevState* st, const int* prompt_dev,
                        int P, int N, int mask_id, hipStream_t s);

@@ -105,9 +105,9 @@ __device__ __forceinline__ void attn_chunk_tile(const bf16x8 (&kf)[2][HB], const
 // microsecond, and one head's K/V is too much for one): every block leaves its unnormalised
 // (m, l, O) in `part`, takes a ticket, and the block that draws the last ticket of its (head,
 // query tile) adds the pieces up in slice order - so the result does not depend on which block
-// that is - and stores the output.  Pieces and tickets go through agent-scope atomics, which are
-// write-through / uncached on this chip, so no cache write-back or invalidate is needed; nobody
-// waits for anybody, so the scheme cannot hang.
+// that is - and stores the output.  Pieces go through agent-scope atomic stores and loads, the
+// ticket is an agent-scope acquire-release increment; nobody waits for anybody, so the scheme
+// cannot hang.
 struct AttnSplit {
   float* part;    // [pairs][gridDim.z][HT*64*4 + 64*2] floats
   int* tickets;   // [pairs], zero between launches (the last block of a pair resets its own)
@@ -264,12 +264,16 @@ __global__ __launch_bounds__(512) void attn_mfma_split_kernel(
   if (nz == 1) return;
 
   // ---- cross-block: leave (m, l), draw a ticket, the last block of the pair finishes ---------
+  // Ordering: every thread's pieces happen-before the block barrier (work-group scope); thread
+  // 0's ticket increment RELEASES them at agent scope, and the finishing block's increment
+  // ACQUIRES every earlier block's pieces, which its barrier then hands to its other threads.
   if (wave == 0) st_agent(mine + HT * 256 + lane * 2, m_all, l_all);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this thread's pieces have reached memory
   __syncthreads();
   int* flag = (int*)lds;  // the parked copies are no longer needed
   if (threadIdx.x == 0) {
-    int old = __hip_atomic_fetch_add(sp.tickets + pair, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    int old = __hip_atomic_fetch_add(sp.tickets + pair, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    // (the counter returns to zero for the next launch; no other block of this launch reads it
+    // any more, and a kernel boundary orders it for the next one)
     if (old == nz - 1)
       __hip_atomic_store(sp.tickets + pair, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     *flag = (old == nz - 1);

@@ -102,6 +102,25 @@ __device__ __forceinline__ size_t vcache_index(int key, int c, int Tpad) {
   return (((size_t)ht * (Tpad >> 5) + kb) * 64 + g * 16 + j) * 8 + e;
 }
 
+// ---- fixed-point row sums of squares ----------------------------------------------------------
+// A row's sum of squares is accumulated by many blocks with 64-bit integer atomics (integer
+// addition is associative, so the total does not depend on the order).  Format 44.20: one unit
+// is 2^-20 (a contribution is rounded to it: absolute error below 5e-7).  A contribution
+// saturates at 2^CAP units, CAP chosen by the caller so that all contributions of a row cannot
+// wrap the 64-bit total: 52 where up to 2^10 blocks add to a row (4.3e9 each), 58 for the few
+// adds of the K-split finish, 62 for the prologue's single store.  Rows whose sum of squares
+// exceeds about 4e12 therefore saturate (their 1/rms comes out too large) instead of wrapping.
+constexpr double kSumsqUnit = 1048576.0;  // 2^20
+template <int CAP = 52>
+__device__ __forceinline__ unsigned long long sumsq_to_fixed(float part) {
+  constexpr unsigned long long cap = 1ull << CAP;
+  const double v = (double)part * kSumsqUnit + 0.5;
+  return v < (double)cap ? (unsigned long long)v : cap;  // (a NaN saturates too)
+}
+__device__ __forceinline__ double sumsq_from_fixed(unsigned long long fx) {
+  return (double)fx * (1.0 / kSumsqUnit);
+}
+
 // ---- reductions (fixed order => deterministic) -----------------------------------------------
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

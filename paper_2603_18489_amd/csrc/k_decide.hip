@@ -72,11 +72,11 @@ constexpr int kHistLds = 4096;   // generation lengths up to this keep the histo
 int vocab_reduce_parts(int V) { return (V + VR_CHUNK - 1) / VR_CHUNK; }
 
 __global__ __launch_bounds__(256) void vocab_reduce_kernel(const float* __restrict__ logits, int V,
-                                                           int nparts,
+                                                           size_t ld, int nparts,
                                                            float4* __restrict__ partials) {
   __shared__ VTuple wt[4];
   const int part = blockIdx.x, row = blockIdx.y, tid = threadIdx.x;
-  const float* z = logits + (size_t)row * V;
+  const float* z = logits + (size_t)row * ld;
   int lo = part * VR_CHUNK, hi = min(V, lo + VR_CHUNK);
   VTuple v = vt_identity();
   for (int i = lo + tid; i < hi; i += 256) vt_push(v, z[i], i);
@@ -94,10 +94,40 @@ __global__ __launch_bounds__(256) void vocab_reduce_kernel(const float* __restri
   }
 }
 
-void launch_vocab_reduce(const float* logits, int n_rows, int V, float4* partials, hipStream_t s) {
+void launch_vocab_reduce(const float* logits, int n_rows, int V, size_t ld, float4* partials,
+                         hipStream_t s) {
   if (n_rows <= 0) return;
   int nparts = vocab_reduce_parts(V);
-  vocab_reduce_kernel<<<dim3(nparts, n_rows), 256, 0, s>>>(logits, V, nparts, partials);
+  vocab_reduce_kernel<<<dim3(nparts, n_rows), 256, 0, s>>>(logits, V, ld, nparts, partials);
+}
+
+// Eq. 1 from a row's merged tuple: confidence = max probability = e^0 / S, entropy
+// H = -sum p ln p = ln S - T / S (clamped at 0 against rounding).
+__device__ __forceinline__ void vt_finish(const VTuple& v, float& conf, float& H) {
+  conf = 1.0f / v.s;
+  H = fmaxf(logf(v.s) - v.t / v.s, 0.f);
+}
+
+// One thread per row: merges the row's partials in part order and writes
+// (token id as float, confidence, entropy, max logit).
+__global__ __launch_bounds__(64) void row_stats_kernel(const float4* __restrict__ partials,
+                                                       int nparts, int n_rows,
+                                                       float4* __restrict__ stats) {
+  const int row = blockIdx.x * 64 + threadIdx.x;
+  if (row >= n_rows) return;
+  VTuple v = vt_identity();
+  for (int p = 0; p < nparts; ++p) {
+    const float4 q = partials[(size_t)row * nparts + p];
+    v = vt_merge(v, VTuple{q.x, __float_as_int(q.y), q.z, q.w});
+  }
+  float conf, H;
+  vt_finish(v, conf, H);
+  stats[row] = make_float4((float)v.idx, conf, H, v.m);
+}
+
+void launch_row_stats(const float4* partials, int nparts, int n_rows, float4* stats, hipStream_t s) {
+  if (n_rows <= 0) return;
+  row_stats_kernel<<<(n_rows + 63) / 64, 64, 0, s>>>(partials, nparts, n_rows, stats);
 }
 
 // ---- block-wide integer helpers (256 threads) -------------------------------------------------
@@ -187,9 +217,8 @@ __global__ __launch_bounds__(256) void decide_kernel(DecideArgs a) {
           VTuple o = {q.x, __float_as_int(q.y), q.z, q.w};
           v = vt_merge(v, o);
         }
-        float conf = 1.0f / v.s;                 // max probability = e^0 / S
-        float H = logf(v.s) - v.t / v.s;         // -sum p ln p
-        H = fmaxf(H, 0.f);
+        float conf, H;
+        vt_finish(v, conf, H);
         s_tok[row] = v.idx;
         s_conf[row] = conf;
         s_H[row] = H;

@@ -9,7 +9,7 @@
 // RMSNorm is folded in: the A operand of a GEMM that follows a norm holds bf16(h * gain), NOT
 // normalised, and the row's 1/rms is applied to the fp32 accumulator in the epilogue (it is a
 // per-row scalar, so it commutes with the contraction).  The sum of squares of each row of h is
-// accumulated by the producing epilogue with integer (fixed-point) atomics, which are
+// accumulated by the producing epilogue with integer (44.20 fixed-point) atomics, which are
 // order-independent and therefore bit-reproducible.
 //
 // Epilogues (template parameter EPI):
@@ -50,7 +50,7 @@ __device__ __forceinline__ float silu_f(float x) {
 }
 
 __device__ __forceinline__ float rstd_from_sum(const GemmEpi& e, unsigned long long fx) {
-  double ss = (double)fx * (1.0 / 4294967296.0);
+  double ss = sumsq_from_fixed(fx);
   return 1.0f / sqrtf((float)(ss / (double)e.d_in) + e.eps);
 }
 __device__ __forceinline__ float rstd_of(const GemmEpi& e, int row) {
@@ -104,7 +104,7 @@ __device__ __forceinline__ void epi_add_sumsq(const GemmEpi& e, int m, bool vali
   part += __shfl_xor(part, 16, 64);
   part += __shfl_xor(part, 32, 64);
   if (valid && (threadIdx.x & 63) < 16) {
-    unsigned long long fx = (unsigned long long)((double)part * 4294967296.0 + 0.5);
+    unsigned long long fx = sumsq_to_fixed(part);
     const int slot = (blockIdx.x + blockIdx.y) & (kSumSlots - 1);
     // (the padding rows of the row list are all zeros: nothing to add)
     if (fx) atomicAdd((unsigned long long*)(e.sumsq_out + (size_t)slot * e.sum_stride + m), fx);
@@ -903,7 +903,7 @@ __global__ __launch_bounds__(256) void resid_finish_kernel(GemmEpi e, int ksplit
   }
   part = block_sum<4>(part, red);
   if (threadIdx.x == 0) {
-    unsigned long long fx = (unsigned long long)((double)part * 4294967296.0 + 0.5);
+    unsigned long long fx = sumsq_to_fixed<58>(part);
     if (fx) atomicAdd((unsigned long long*)(e.sumsq_out + (size_t)(blockIdx.x & (kSumSlots - 1)) * e.sum_stride + m), fx);
   }
 }

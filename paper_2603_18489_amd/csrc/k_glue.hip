@@ -31,7 +31,7 @@ void launch_embed_f32(const float* emb, const int* x, const int* rows, int M, in
 // bf16: the step's first kernel, one block per row of the step's row list.  It derives the
 // row's sequence and position from the sequence table (and records them for the later kernels),
 // gathers the embedding, emits the first GEMM's operand bf16(h * gain) in fragment order and the
-// row's sum of squares (32.32 fixed point), and clears the step's other sum buffers for the row.
+// row's sum of squares (44.20 fixed point), and clears the step's other sum buffers for the row.
 __global__ __launch_bounds__(256) void step_prologue_bf16_kernel(
     StepLists L, const bf16_t* __restrict__ emb, int d, const bf16_t* __restrict__ gain,
     float* __restrict__ h, bf16_t* __restrict__ a_out, unsigned long long* __restrict__ sumsq,
@@ -84,7 +84,7 @@ __global__ __launch_bounds__(256) void step_prologue_bf16_kernel(
   }
   ss = block_sum<4>(ss, red);
   if (threadIdx.x == 0)
-    sumsq[r] = (unsigned long long)((double)ss * 4294967296.0 + 0.5);
+    sumsq[r] = sumsq_to_fixed<62>(ss);
   for (int b = 1 + threadIdx.x; b < nbuf; b += 256) sumsq[(size_t)b * sumsq_stride + r] = 0ull;
 }
 

@@ -181,3 +181,26 @@ def test_bench_refuses_more_than_one_gpu():
                        capture_output=True, text=True, timeout=120)
     assert p.returncode == 2
     assert "one GPU" in p.stderr and p.stdout.strip() == ""
+
+
+def test_row_entropy_argument_errors_without_gpu(lib):
+    """The context-free reduction call validates before any HIP work."""
+    vp = C.c_void_p
+    z, st, ws = vp(0x100000), vp(0x200000), vp(0x300000)
+    need = lib.ec_row_entropy_workspace_bytes(32, 126464)
+    assert need == 32 * 62 * 16 and need % 256 == 0
+    assert lib.ec_row_entropy_workspace_bytes(ec.EC_MAX_BLOCK + 1, 4096) == 0
+    assert lib.ec_row_entropy_workspace_bytes(4, 1) == 0
+    assert lib.ec_row_entropy_workspace_bytes(4, 163841) == 0
+    call = lib.ec_row_entropy
+    assert call(None, 4, 4096, 4096, st, ws, need, None) == ec.EC_ERR_ARG
+    assert call(z, 4, 4096, 4096, None, ws, need, None) == ec.EC_ERR_ARG
+    assert call(z, -1, 4096, 4096, st, ws, need, None) == ec.EC_ERR_ARG
+    assert call(z, ec.EC_MAX_BLOCK + 1, 4096, 4096, st, ws, need, None) == ec.EC_ERR_ARG
+    assert call(z, 4, 4096, 4095, st, ws, need, None) == ec.EC_ERR_ARG
+    assert b"stride" in lib.ec_last_error(None)
+    assert call(z, 4, 4096, 4096, vp(0x200004), ws, need, None) == ec.EC_ERR_ARG
+    assert call(z, 4, 4096, 4096, st, None, need, None) == ec.EC_ERR_WORKSPACE
+    assert call(z, 4, 4096, 4096, st, vp(0x300010), need, None) == ec.EC_ERR_WORKSPACE
+    assert call(z, 32, 126464, 126464, st, ws, need - 256, None) == ec.EC_ERR_WORKSPACE
+    assert len(lib.ec_strerror(ec.EC_ERR_HOST_MEMORY)) > 0

@@ -50,6 +50,7 @@ def test_small_models_whole_generation(dtype, hq, hkv, hd, P, N, block, k, n, ta
     s = run_teacher_forced(cfg, w, dec, prompt, TOL[dtype])
     print(s)
     assert s["modes"][eco.PARTIAL] >= 1
+    assert s["tokens_exact"] > 0 and s["choices_exact"] > 0 and s["modes_exact"] > 0
 
 
 @pytest.mark.parametrize("dtype,thr,metric,tau,scale", [
@@ -71,6 +72,7 @@ def test_confidence_threshold_decoding_and_gate_metrics(dtype, thr, metric, tau,
     print(s)
     assert s["modes"][eco.PARTIAL] >= 1 and s["modes"][eco.FULL] >= 1
     assert s["steps"] < 80, "no step decoded several tokens: the threshold path did not run"
+    assert s["tokens_exact"] > 0 and s["choices_exact"] > 0 and s["modes_exact"] > 0
 
 
 @pytest.mark.parametrize("dtype,block,k,n,thr,tau", [
@@ -88,6 +90,7 @@ def test_sliding_window_schedule(dtype, block, k, n, thr, tau):
     s = run_teacher_forced(cfg, w, dec, prompt, TOL[dtype])
     print(s)
     assert s["modes"][eco.PARTIAL] >= 1 and s["modes"][eco.FULL] >= 1
+    assert s["tokens_exact"] > 0 and s["choices_exact"] > 0 and s["modes_exact"] > 0
 
 
 @pytest.mark.parametrize("hq,hkv,hd", [(4, 4, 64), (4, 2, 128)])
@@ -101,6 +104,7 @@ def test_long_context_partial_steps(hq, hkv, hd):
     s = run_teacher_forced(cfg, w, dec, prompt, TOL["bf16"], max_steps=8)
     print(s)
     assert s["modes"][eco.PARTIAL] >= 6
+    assert s["tokens_exact"] > 0 and s["choices_exact"] > 0 and s["modes_exact"] > 0
 
 
 @pytest.mark.parametrize("hq,hkv,hd,plens,N,block,k,n,tau,fast", [
@@ -119,6 +123,7 @@ def test_batched_sequences_match_their_own_oracle_runs(hq, hkv, hd, plens, N, bl
     s = run_teacher_forced_batch(cfg, w, dec, prompts, TOL["bf16"], fast_seq=fast)
     print(s)
     assert s["modes"][eco.PARTIAL] >= 1 and s["modes"][eco.FULL] >= len(plens)
+    assert s["tokens_exact"] > 0 and s["choices_exact"] > 0 and s["modes_exact"] > 0
     if fast is not None:
         assert s["finished_early"] >= 1
 
@@ -134,6 +139,7 @@ def test_tile_counts_that_do_not_divide_the_block_widths():
     s = run_teacher_forced(cfg, w, dec, prompt, TOL["bf16"])
     print(s)
     assert s["modes"][eco.PARTIAL] >= 1 and s["modes"][eco.FULL] >= 1
+    assert s["tokens_exact"] > 0 and s["choices_exact"] > 0 and s["modes_exact"] > 0
 
 
 def _random_case(seed):
@@ -162,6 +168,7 @@ def test_random_configurations(seed):
     prompt = ec_inputs.make_prompt(cfg.vocab, c["P"], seed + 1)
     s = run_teacher_forced(cfg, w, dec, prompt, TOL[c["dtype"]], max_steps=40)
     print(c, s)
+    assert s["tokens_exact"] > 0 and s["choices_exact"] > 0
 
 
 def test_largest_batch():
@@ -174,6 +181,7 @@ def test_largest_batch():
     s = run_teacher_forced_batch(cfg, w, dec, prompts, TOL["bf16"], check_cache_every=3)
     print(s)
     assert s["steps"] == 6 and s["modes"][eco.FULL] >= B
+    assert s["tokens_exact"] > 0 and s["choices_exact"] > 0 and s["modes_exact"] > 0
 
 
 def test_batched_generate_runs_every_sequence_to_the_end():
@@ -211,6 +219,7 @@ def test_degenerate_shapes(dtype, P, N, block, k, n, tau):
     prompt = ec_inputs.make_prompt(cfg.vocab, P, 4)
     s = run_teacher_forced(cfg, w, dec, prompt, TOL[dtype])
     print(s)
+    assert s["tokens_exact"] > 0 and s["choices_exact"] > 0
     if tau < 0:
         assert s["modes"][eco.PARTIAL] == 0
 

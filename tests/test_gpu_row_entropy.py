@@ -1,0 +1,64 @@
+"""The vocabulary reduction as a call of its own (ec_row_entropy) against the oracle's Eq. 1 and
+its closed forms, through the C ABI."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2603_18489_amd as ec
+from oracle import entropycache as eco
+
+pytestmark = pytest.mark.gpu
+
+
+def oracle_stats(z):
+    out = np.zeros((z.shape[0], 4))
+    for i in range(z.shape[0]):
+        tok, conf, H = eco.softmax_stats(z[i].astype(np.float64))
+        out[i] = (tok, conf, H, z[i].max())
+    return out
+
+
+@pytest.mark.parametrize("rows,V,pad", [(1, 2, 0), (7, 4096, 0), (32, 126464, 0), (34, 152064, 64),
+                                        (128, 5000, 3), (3, 163840, 0), (0, 4096, 0)])
+def test_row_entropy_matches_oracle(rows, V, pad):
+    rng = np.random.default_rng(rows * 7 + V)
+    # rows of different sharpness, one with -inf entries, one with two equal maxima
+    z = (rng.standard_normal((rows, V)) * rng.uniform(0.5, 12.0, (rows, 1))).astype(np.float32)
+    if rows > 2 and V > 8:
+        z[1, ::3] = -np.inf
+        z[2, 5] = z[2, V - 3] = z[2].max() + 1.0
+    buf = torch.zeros((max(rows, 1), V + pad), dtype=torch.float32, device="cuda")
+    zt = buf[:rows, :V]
+    zt.copy_(torch.from_numpy(z))
+    got = ec.row_entropy(zt).cpu().numpy().astype(np.float64)
+    ref = oracle_stats(z)
+    assert got.shape == (rows, 4)
+    if rows == 0:
+        return
+    assert np.array_equal(got[:, 0], ref[:, 0])                 # argmax, lowest id on ties
+    assert np.array_equal(got[:, 3], ref[:, 3])
+    assert np.abs(got[:, 1] - ref[:, 1]).max() <= 2e-5 * ref[:, 1].max()
+    assert np.abs(got[:, 2] - ref[:, 2]).max() <= 2e-5 * math.log(V)
+    if rows > 2 and V > 8:
+        assert int(got[2, 0]) == 5
+
+
+def test_row_entropy_closed_forms():
+    V = 126464
+    z = torch.zeros((4, V), dtype=torch.float32, device="cuda")
+    z[1] = 3.25                       # uniform at another level: shift invariance
+    z[2, :] = -float("inf")
+    z[2, 77] = z[2, 99000] = 1.5      # two equal maxima, nothing else: H = ln 2
+    z[3, :] = -1e4
+    z[3, 123] = 50.0                  # one dominant logit: H = 0, confidence 1
+    s = ec.row_entropy(z).cpu().numpy()
+    for r in (0, 1):
+        assert s[r, 0] == 0 and s[r, 2] == pytest.approx(math.log(V), rel=1e-6)
+        assert s[r, 1] == pytest.approx(1.0 / V, rel=1e-6)
+    assert s[2, 0] == 77 and s[2, 1] == pytest.approx(0.5, rel=1e-6)
+    assert s[2, 2] == pytest.approx(math.log(2.0), rel=1e-6)
+    assert s[3, 0] == 123 and s[3, 1] == 1.0 and s[3, 2] == 0.0
+    # deterministic: the same input gives the same bits
+    assert np.array_equal(s, ec.row_entropy(z).cpu().numpy())
