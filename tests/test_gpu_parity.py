@@ -50,7 +50,7 @@ def test_small_models_whole_generation(dtype, hq, hkv, hd, P, N, block, k, n, ta
     s = run_teacher_forced(cfg, w, dec, prompt, TOL[dtype])
     print(s)
     assert s["modes"][eco.PARTIAL] >= 1
-    assert s["tokens_exact"] > 0 and s["choices_exact"] > 0 and s["modes_exact"] > 0
+    assert s["tokens_exact"] > 0 and s["rows_decided"] > 0 and s["modes_exact"] > 0
 
 
 @pytest.mark.parametrize("dtype,thr,metric,tau,scale", [
@@ -72,7 +72,7 @@ def test_confidence_threshold_decoding_and_gate_metrics(dtype, thr, metric, tau,
     print(s)
     assert s["modes"][eco.PARTIAL] >= 1 and s["modes"][eco.FULL] >= 1
     assert s["steps"] < 80, "no step decoded several tokens: the threshold path did not run"
-    assert s["tokens_exact"] > 0 and s["choices_exact"] > 0 and s["modes_exact"] > 0
+    assert s["tokens_exact"] > 0 and s["rows_decided"] > 0 and s["modes_exact"] > 0
 
 
 @pytest.mark.parametrize("dtype,block,k,n,thr,tau", [
@@ -90,7 +90,7 @@ def test_sliding_window_schedule(dtype, block, k, n, thr, tau):
     s = run_teacher_forced(cfg, w, dec, prompt, TOL[dtype])
     print(s)
     assert s["modes"][eco.PARTIAL] >= 1 and s["modes"][eco.FULL] >= 1
-    assert s["tokens_exact"] > 0 and s["choices_exact"] > 0 and s["modes_exact"] > 0
+    assert s["tokens_exact"] > 0 and s["rows_decided"] > 0 and s["modes_exact"] > 0
 
 
 @pytest.mark.parametrize("hq,hkv,hd", [(4, 4, 64), (4, 2, 128)])
@@ -104,7 +104,7 @@ def test_long_context_partial_steps(hq, hkv, hd):
     s = run_teacher_forced(cfg, w, dec, prompt, TOL["bf16"], max_steps=8)
     print(s)
     assert s["modes"][eco.PARTIAL] >= 6
-    assert s["tokens_exact"] > 0 and s["choices_exact"] > 0 and s["modes_exact"] > 0
+    assert s["tokens_exact"] > 0 and s["modes_exact"] > 0
 
 
 @pytest.mark.parametrize("hq,hkv,hd,plens,N,block,k,n,tau,fast", [
@@ -123,7 +123,7 @@ def test_batched_sequences_match_their_own_oracle_runs(hq, hkv, hd, plens, N, bl
     s = run_teacher_forced_batch(cfg, w, dec, prompts, TOL["bf16"], fast_seq=fast)
     print(s)
     assert s["modes"][eco.PARTIAL] >= 1 and s["modes"][eco.FULL] >= len(plens)
-    assert s["tokens_exact"] > 0 and s["choices_exact"] > 0 and s["modes_exact"] > 0
+    assert s["tokens_exact"] > 0 and s["rows_decided"] > 0 and s["modes_exact"] > 0
     if fast is not None:
         assert s["finished_early"] >= 1
 
@@ -139,7 +139,7 @@ def test_tile_counts_that_do_not_divide_the_block_widths():
     s = run_teacher_forced(cfg, w, dec, prompt, TOL["bf16"])
     print(s)
     assert s["modes"][eco.PARTIAL] >= 1 and s["modes"][eco.FULL] >= 1
-    assert s["tokens_exact"] > 0 and s["choices_exact"] > 0 and s["modes_exact"] > 0
+    assert s["tokens_exact"] > 0 and s["rows_decided"] > 0 and s["modes_exact"] > 0
 
 
 def _random_case(seed):
@@ -168,7 +168,7 @@ def test_random_configurations(seed):
     prompt = ec_inputs.make_prompt(cfg.vocab, c["P"], seed + 1)
     s = run_teacher_forced(cfg, w, dec, prompt, TOL[c["dtype"]], max_steps=40)
     print(c, s)
-    assert s["tokens_exact"] > 0 and s["choices_exact"] > 0
+    assert s["tokens_exact"] > 0
 
 
 def test_largest_batch():
@@ -181,7 +181,7 @@ def test_largest_batch():
     s = run_teacher_forced_batch(cfg, w, dec, prompts, TOL["bf16"], check_cache_every=3)
     print(s)
     assert s["steps"] == 6 and s["modes"][eco.FULL] >= B
-    assert s["tokens_exact"] > 0 and s["choices_exact"] > 0 and s["modes_exact"] > 0
+    assert s["tokens_exact"] > 0 and s["rows_decided"] > 0 and s["modes_exact"] > 0
 
 
 def test_batched_generate_runs_every_sequence_to_the_end():
@@ -219,7 +219,7 @@ def test_degenerate_shapes(dtype, P, N, block, k, n, tau):
     prompt = ec_inputs.make_prompt(cfg.vocab, P, 4)
     s = run_teacher_forced(cfg, w, dec, prompt, TOL[dtype])
     print(s)
-    assert s["tokens_exact"] > 0 and s["choices_exact"] > 0
+    assert s["tokens_exact"] > 0 and s["rows_decided"] > 0
     if tau < 0:
         assert s["modes"][eco.PARTIAL] == 0
 
@@ -339,3 +339,30 @@ def test_entropy_closed_forms_through_the_whole_path():
     assert stats[0, 2] == pytest.approx(math.log(2.0), rel=1e-4)
     assert stats[0, 1] == pytest.approx(0.5, rel=1e-4)
     g.close()
+
+
+def test_large_magnitude_residual_stream():
+    """Residual rows with sums of squares near 1e10 (embeddings of magnitude ~6000, as the
+    massive activations of trained models): the fixed-point row sums behind the folded RMSNorm
+    must neither wrap nor lose the row."""
+    from tests.gpu_harness import bf16_bits_to_f32
+    cfg = small_cfg("bf16", 4, 2, 64)
+    w = ec_inputs.make_weights(cfg, 43, gain_jitter=0.1)
+    w["tok_emb"] = ec_inputs.f32_to_bf16_bits(bf16_bits_to_f32(w["tok_emb"]) * np.float32(3e5))
+    dec = ec_inputs.DecodeCfg(gen_len=40, block=32, k_recent=2, tokens_per_step=2, tau=1e9)
+    prompt = ec_inputs.make_prompt(cfg.vocab, 150, 8)
+    s = run_teacher_forced(cfg, w, dec, prompt, TOL["bf16"])
+    print(s)
+    assert s["modes"][eco.PARTIAL] >= 1 and s["rows_decided"] > 0 and s["modes_exact"] > 0
+
+
+def test_long_context_ragged_batch_gqa():
+    """Two sequences of more than 2048 positions with grouped-query heads of 128: the key slices
+    of the partial-step attention (pieces summed by the last block to arrive) on a ragged batch."""
+    cfg = small_cfg("bf16", 4, 2, 128, d=512)
+    w = ec_inputs.make_weights(cfg, 47, gain_jitter=0.1)
+    dec = ec_inputs.DecodeCfg(gen_len=24, block=16, k_recent=3, tokens_per_step=2, tau=1e9, batch=2)
+    prompts = [ec_inputs.make_prompt(cfg.vocab, P, 60 + i) for i, P in enumerate((2100, 2333))]
+    s = run_teacher_forced_batch(cfg, w, dec, prompts, TOL["bf16"], max_steps=6, check_cache_every=3)
+    print(s)
+    assert s["modes"][eco.PARTIAL] >= 8 and s["tokens_exact"] > 0

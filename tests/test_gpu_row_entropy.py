@@ -39,8 +39,8 @@ def test_row_entropy_matches_oracle(rows, V, pad):
         return
     assert np.array_equal(got[:, 0], ref[:, 0])                 # argmax, lowest id on ties
     assert np.array_equal(got[:, 3], ref[:, 3])
-    assert np.abs(got[:, 1] - ref[:, 1]).max() <= 2e-5 * ref[:, 1].max()
-    assert np.abs(got[:, 2] - ref[:, 2]).max() <= 2e-5 * math.log(V)
+    assert np.abs(got[:, 1] - ref[:, 1]).max() <= 4e-6 * ref[:, 1].max()
+    assert np.abs(got[:, 2] - ref[:, 2]).max() <= 4e-6 * math.log(V)
     if rows > 2 and V > 8:
         assert int(got[2, 0]) == 5
 
