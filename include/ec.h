@@ -161,7 +161,8 @@ typedef struct {
 
 /* What ec_debug_read copies to the host. */
 enum {
-  EC_DBG_LOGITS = 0, /* float32 [n_block_rows, vocab] of the last step (already scaled)        */
+  EC_DBG_LOGITS = 0, /* float32 [n_block_rows, vocab] of the last step (already scaled); needs
+                        ec_debug_keep_logits to have been on during that step                 */
   EC_DBG_KCACHE,     /* layer's keys, post-RoPE, storage type, [T, n_kv_heads, head_dim]       */
   EC_DBG_VCACHE,     /* layer's values, same layout                                            */
   EC_DBG_X,          /* int32 [T] current token ids                                            */
@@ -235,9 +236,17 @@ int ec_generate(ec_ctx *ctx, int32_t *out_tokens, ec_gen_stats *stats);
 int ec_profile_enable(ec_ctx *ctx, int on);
 int ec_profile_read(ec_ctx *ctx, ec_profile *out);
 
+/* The bfloat16 path reduces the vocabulary (Eq. 1: argmax, confidence, entropy) inside the
+ * LM-head kernel and never writes the logits to memory.  on != 0 makes the following steps store
+ * them as well (16 MB per step at a 126464-token vocabulary) so that EC_DBG_LOGITS can read them;
+ * the step's results are bit-identical either way.  Off by default.  (Float32 models and steps with
+ * more than 64 block rows over the batch materialise their logits anyway.)  Errors: EC_ERR_ARG. */
+int ec_debug_keep_logits(ec_ctx *ctx, int on);
+
 /* Copies internal state of one sequence to the host (synchronises the stream; test and
  * diagnosis aid, not part of the method).  bytes must not exceed the size of the item
- * (EC_ERR_ARG otherwise); the copy is truncated to bytes. */
+ * (EC_ERR_ARG otherwise); the copy is truncated to bytes.  EC_DBG_LOGITS of a step that did not
+ * store its logits is EC_ERR_STATE. */
 int ec_debug_read(ec_ctx *ctx, int what, int layer, void *host_dst, size_t bytes); /* sequence 0 */
 int ec_debug_read_seq(ec_ctx *ctx, int seq, int what, int layer, void *host_dst, size_t bytes);
 

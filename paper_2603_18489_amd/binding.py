@@ -28,7 +28,7 @@ KERNEL_CLASS_NAMES = ["embed", "norm", "qkv", "rope_kv", "attn", "oproj", "gateu
 (EC_DBG_LOGITS, EC_DBG_KCACHE, EC_DBG_VCACHE, EC_DBG_X, EC_DBG_MASKED, EC_DBG_HIST, EC_DBG_ROWS,
  EC_DBG_ROW_STATS) = range(8)
 
-EXPORTS = ["ec_workspace_bytes", "ec_init", "ec_reset", "ec_step", "ec_step_forced",
+EXPORTS = ["ec_workspace_bytes", "ec_init", "ec_reset", "ec_step", "ec_step_forced", "ec_debug_keep_logits",
            "ec_step_forced_batch", "ec_generate", "ec_profile_enable", "ec_profile_read",
            "ec_debug_read", "ec_debug_read_seq", "ec_destroy", "ec_strerror", "ec_last_error",
            "ec_row_entropy_workspace_bytes", "ec_row_entropy"]
@@ -114,6 +114,8 @@ def load_library() -> C.CDLL:
     lib.ec_profile_enable.argtypes = [vp, C.c_int]
     lib.ec_profile_read.restype = C.c_int
     lib.ec_profile_read.argtypes = [vp, C.POINTER(ec_profile)]
+    lib.ec_debug_keep_logits.restype = C.c_int
+    lib.ec_debug_keep_logits.argtypes = [vp, C.c_int]
     lib.ec_debug_read.restype = C.c_int
     lib.ec_debug_read.argtypes = [vp, C.c_int, C.c_int, vp, C.c_size_t]
     lib.ec_debug_read_seq.restype = C.c_int
@@ -182,6 +184,8 @@ def row_entropy(logits, stream=None):
     rows, vocab = logits.shape
     assert logits.dtype == torch.float32 and logits.stride(1) == 1
     stats = torch.empty((rows, 4), dtype=torch.float32, device=logits.device)
+    if rows == 0:
+        return stats         # (an empty tensor has no address to hand over)
     need = lib.ec_row_entropy_workspace_bytes(rows, vocab)
     ws = torch.empty(max(need, 256), dtype=torch.uint8, device=logits.device)
     st = stream if stream is not None else torch.cuda.current_stream()
@@ -278,6 +282,10 @@ class EntropyCache:
         self._check(self.lib.ec_generate(self.ctx, _i32p(out), C.byref(st)))
         stats = {k: getattr(st, k) for k, _ in ec_gen_stats._fields_}
         return (out if self.B == 1 else out.reshape(self.B, self.N)), stats
+
+    def keep_logits(self, on: bool = True):
+        """Makes the following steps store their logits so that EC_DBG_LOGITS can read them."""
+        self._check(self.lib.ec_debug_keep_logits(self.ctx, int(on)))
 
     def profile_enable(self, on: bool):
         self._check(self.lib.ec_profile_enable(self.ctx, int(on)))

@@ -127,7 +127,11 @@ void carve(Carver& c, const ec_model_cfg& m, const ec_decode_cfg& d, const Geome
   b.act = c.take<char>(R * m.d_ffn * es);
   b.u_lm = c.take<char>(BL16 * m.d_model * es);
   b.logits = c.take<float>(BL * m.vocab);
-  b.partials = c.take<float4>(BL * vocab_reduce_parts(m.vocab));
+  {  // partial tuples of the vocabulary reduction: from the LM-head epilogue or from vocab_reduce
+    const size_t np_fused = m.dtype == EC_BF16 ? (size_t)lm_head_parts(m.vocab) : 0;
+    const size_t np_plain = (size_t)vocab_reduce_parts(m.vocab);
+    b.partials = c.take<float4>(BL * (np_fused > np_plain ? np_fused : np_plain));
+  }
   b.pl.clear();
   b.lm_head_p = nullptr;
   b.sumsq = nullptr;
@@ -218,6 +222,12 @@ struct ec_ctx {
   std::vector<uint8_t> masked_host;  // concatenated by x_off
   int64_t rows_recomputed = 0;
   int full_steps = 0, partial_steps = 0, tokens = 0;
+  // vocabulary reduction of the step in flight: fused behind the LM head (then the logits are
+  // only stored on request) or a pass of its own over materialised logits
+  bool keep_logits = false;   // ec_debug_keep_logits
+  bool logits_stored = false; // the last step left its logits in b.logits
+  bool fused_reduce = false;
+  int step_nparts = 0;
   // profiling
   bool prof_on = false;
   std::vector<ProfEvent> prof_pool;
@@ -275,7 +285,7 @@ char* kv_ptr(ec_ctx* c, int layer, int which) {
 
 void fill_decide_args(ec_ctx* c, DecideArgs& a) {
   a.seqs = c->b.seqs;
-  a.partials = c->b.partials; a.nparts = vocab_reduce_parts(c->m.vocab);
+  a.partials = c->b.partials; a.nparts = c->step_nparts;
   a.forced_pos = c->b.forced_pos; a.forced_tok = c->b.forced_tok;
   a.x = c->b.x; a.masked = c->b.masked; a.hist = c->b.hist; a.st = c->b.st;
   a.mb_pos = c->b.mb_pos; a.rows_partial = c->b.rows_partial; a.mb_idx = c->b.mb_idx;
@@ -313,6 +323,7 @@ int upload_and_init_state(ec_ctx* c, const int32_t* prompt_ids) {
   }
   EC_HIP(c, hipMemcpyAsync(c->b.seqs, c->host_seqs, (size_t)B * sizeof(SeqDesc),
                            hipMemcpyHostToDevice, c->stream));
+  c->logits_stored = false;
   DecideArgs a{};
   fill_decide_args(c, a);
   a.init_only = 1;
@@ -451,9 +462,16 @@ int forward_bf16(ec_ctx* c, const StepPlan& sp) {
     e.sumsq_in = sums(2 * L); e.d_in = d; e.eps = m.rms_eps; e.sum_stride = b.sumsq_stride;
     e.scale = m.logit_scale; e.logits = b.logits; e.ldc = m.vocab;
     e.w_grp = skinny_tiles_per_block(EPI_LOGITS, m.vocab / 16);
-    if (sp.n_lm <= 64) {
+    if (sp.n_lm <= kLmSkinnyRows) {
+      // the epilogue reduces the vocabulary itself; the logits go to memory only on request
+      e.vparts = b.partials;
+      if (!c->keep_logits) e.logits = nullptr;
+      c->fused_reduce = true; c->step_nparts = lm_head_parts(m.vocab);
+      c->logits_stored = c->keep_logits;
       launch_gemm_bf16(EPI_LOGITS, u, R, b.lm_head_p, m.vocab, d, e, s);
     } else {  // many sequences: gather the rows once, then one pass over the LM head
+      c->fused_reduce = false; c->step_nparts = vocab_reduce_parts(m.vocab);
+      c->logits_stored = true;
       launch_gather_rows_packed(u, R, b.lm_sel, sp.n_lm, d, (bf16_t*)b.u_lm, s);
       launch_gemm_bf16(EPI_LOGITS, (bf16_t*)b.u_lm, sp.n_lm, b.lm_head_p, m.vocab, d, e, s);
     } }
@@ -550,11 +568,14 @@ int run_step(ec_ctx* c, const int32_t* modes, int modes_n, const int32_t* forced
                              (size_t)B * EC_MAX_N * sizeof(int), hipMemcpyHostToDevice, c->stream));
   }
   // ---- forward, vocabulary reduction, decision ---------------------------------------------------
+  c->fused_reduce = false; c->step_nparts = vocab_reduce_parts(c->m.vocab); c->logits_stored = true;
   int rc = (c->m.dtype == EC_F32) ? forward_f32(c, mode[0], c->host_seqs[0].n_rows, c->n_mb[0])
                                   : forward_bf16(c, sp);
   if (rc != EC_OK) return rc;
-  { Scope p(c, EC_K_VOCAB_REDUCE);
-    launch_vocab_reduce(c->b.logits, sp.n_lm, c->m.vocab, (size_t)c->m.vocab, c->b.partials, c->stream); }
+  if (!c->fused_reduce) {
+    Scope p(c, EC_K_VOCAB_REDUCE);
+    launch_vocab_reduce(c->b.logits, sp.n_lm, c->m.vocab, (size_t)c->m.vocab, c->b.partials, c->stream);
+  }
   EC_HIP(c, hipGetLastError());
   DecideArgs a{};
   fill_decide_args(c, a);
@@ -848,6 +869,8 @@ int ec_debug_read_seq(ec_ctx* ctx, int seq, int what, int layer, void* host_dst,
       src = ctx->b.logits + (size_t)ctx->host_seqs[seq].lm0 * ctx->m.vocab;
       avail = (size_t)blk * ctx->m.vocab * 4;
       if (ctx->host_seqs[seq].mode < 0) avail = 0;
+      if (!ctx->logits_stored)
+        return fail(ctx, EC_ERR_STATE, "the last step did not store its logits: ec_debug_keep_logits");
       break;
     case EC_DBG_KCACHE:
     case EC_DBG_VCACHE:
@@ -871,6 +894,12 @@ int ec_debug_read_seq(ec_ctx* ctx, int seq, int what, int layer, void* host_dst,
   if (bytes > avail) return fail(ctx, EC_ERR_ARG, "bytes exceeds the size of the item");
   EC_HIP(ctx, hipStreamSynchronize(ctx->stream));
   if (bytes) EC_HIP(ctx, hipMemcpy(host_dst, src, bytes, hipMemcpyDeviceToHost));
+  return EC_OK;
+}
+
+int ec_debug_keep_logits(ec_ctx* ctx, int on) {
+  if (!ctx) return fail(nullptr, EC_ERR_ARG, "ctx is NULL");
+  ctx->keep_logits = on != 0;
   return EC_OK;
 }
 

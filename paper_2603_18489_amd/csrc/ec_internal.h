@@ -124,7 +124,9 @@ struct GemmEpi {
   int d_in;                       // its length
   float eps;
   float scale;                    // EPI_LOGITS
-  float* logits; int ldc;
+  float* logits; int ldc;         // (skinny kernel: nullable = do not store the logits)
+  float4* vparts;                 // EPI_LOGITS, skinny kernel: [row][blocks] partial tuples of
+                                  // the vocabulary reduction (k_vtuple.h), one per block
   float* h; int d;                // EPI_RESID: residual stream [M, d]
   float* partial; int max_ksplit; // nullable: room for [max_ksplit][M][d] fp32 partial products
   const bf16_t* gain_next;        // gain of the norm that follows
@@ -168,6 +170,10 @@ void launch_repack_weight(const bf16_t* W, int N, int K, bf16_t* Wp, int mode, i
 // Weight tiles per block the skinny GEMM uses for a matrix of total_nt tiles, which is also the
 // group size its packed layout should have.
 int skinny_tiles_per_block(int epi, int total_nt);
+// Up to this many activation rows the LM head runs through the skinny kernel, which reduces the
+// vocabulary on the fly: lm_head_parts(V) partial tuples per row.
+constexpr int kLmSkinnyRows = 64;
+int lm_head_parts(int V);
 // dst rows 0..n (padded with zero rows to whole tiles) = src rows sel[0..n), both packed, K wide.
 void launch_gather_rows_packed(const bf16_t* src, int M_src, const int* sel, int n, int K,
                                bf16_t* dst, hipStream_t s);

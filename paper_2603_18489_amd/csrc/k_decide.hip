@@ -9,64 +9,11 @@
 #include <limits.h>
 
 #include "ec_internal.h"
+#include "k_vtuple.h"
 
 namespace ec {
 
-// ---- (max, argmax, S, T) tuples ---------------------------------------------------------------
-struct VTuple {
-  float m;   // running maximum
-  int idx;   // its index (lowest index among equal maxima)
-  float s;   // sum exp(z - m)
-  float t;   // sum exp(z - m) * (z - m)
-};
-
-__device__ __forceinline__ VTuple vt_identity() { return {-INFINITY, INT_MAX, 0.f, 0.f}; }
-
-// Associative merge: re-base both sides to the common maximum.
-__device__ __forceinline__ VTuple vt_merge(const VTuple& a, const VTuple& b) {
-  if (b.s == 0.f) return a;
-  if (a.s == 0.f) return b;
-  VTuple r;
-  bool a_wins = (a.m > b.m) || (a.m == b.m && a.idx < b.idx);
-  r.m = fmaxf(a.m, b.m);
-  r.idx = a_wins ? a.idx : b.idx;
-  float da = a.m - r.m, db = b.m - r.m;  // <= 0
-  float ea = expf(da), eb = expf(db);
-  r.s = a.s * ea + b.s * eb;
-  r.t = ea * (a.t + da * a.s) + eb * (b.t + db * b.s);
-  return r;
-}
-
-__device__ __forceinline__ void vt_push(VTuple& v, float z, int idx) {
-  if (z == -INFINITY) return;  // probability 0 contributes 0 (0 ln 0 := 0)
-  if (z > v.m) {  // new maximum: re-base what was accumulated so far
-    if (v.s != 0.f) {
-      float d = v.m - z, e = expf(d);
-      v.t = e * (v.t + d * v.s);
-      v.s = v.s * e;
-    }
-    v.m = z;
-    v.idx = idx;
-    v.s += 1.f;
-  } else {
-    float d = z - v.m, e = expf(d);
-    v.s += e;
-    v.t += e * d;
-  }
-}
-
-__device__ __forceinline__ VTuple vt_shfl_down(const VTuple& v, int o) {
-  VTuple r;
-  r.m = __shfl_down(v.m, o, 64);
-  r.idx = __shfl_down(v.idx, o, 64);
-  r.s = __shfl_down(v.s, o, 64);
-  r.t = __shfl_down(v.t, o, 64);
-  return r;
-}
-
 constexpr int VR_CHUNK = 2048;  // logits per block
-constexpr int kMergeRows = 32;   // rows whose partials the decision kernel stages at a time
-constexpr int kMaxParts = 80;    // partials per row it has room for: vocabularies up to 163840
 constexpr int kHistLds = 4096;   // generation lengths up to this keep the history in LDS
 
 int vocab_reduce_parts(int V) { return (V + VR_CHUNK - 1) / VR_CHUNK; }
@@ -101,13 +48,6 @@ void launch_vocab_reduce(const float* logits, int n_rows, int V, size_t ld, floa
   vocab_reduce_kernel<<<dim3(nparts, n_rows), 256, 0, s>>>(logits, V, ld, nparts, partials);
 }
 
-// Eq. 1 from a row's merged tuple: confidence = max probability = e^0 / S, entropy
-// H = -sum p ln p = ln S - T / S (clamped at 0 against rounding).
-__device__ __forceinline__ void vt_finish(const VTuple& v, float& conf, float& H) {
-  conf = 1.0f / v.s;
-  H = fmaxf(logf(v.s) - v.t / v.s, 0.f);
-}
-
 // One thread per row: merges the row's partials in part order and writes
 // (token id as float, confidence, entropy, max logit).
 __global__ __launch_bounds__(64) void row_stats_kernel(const float4* __restrict__ partials,
@@ -130,15 +70,8 @@ void launch_row_stats(const float4* partials, int nparts, int n_rows, float4* st
   row_stats_kernel<<<(n_rows + 63) / 64, 64, 0, s>>>(partials, nparts, n_rows, stats);
 }
 
-// ---- block-wide integer helpers (256 threads) -------------------------------------------------
-__device__ __forceinline__ int block_sum_int(int v, int* scratch) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
-  __syncthreads();
-  return scratch[0] + scratch[1] + scratch[2] + scratch[3];
-}
+// ---- block-wide integer helpers (kDecideThreads threads) --------------------------------------
+constexpr int kDecideThreads = 1024, kDecideWaves = kDecideThreads / 64;
 
 // Exclusive prefix of a 0/1 flag over the block; returns the prefix, *total gets the block sum.
 __device__ __forceinline__ int block_excl_scan_flag(int flag, int* scratch, int* total) {
@@ -148,9 +81,14 @@ __device__ __forceinline__ int block_excl_scan_flag(int flag, int* scratch, int*
   __syncthreads();
   if (lane == 0) scratch[w] = __popcll(ball);
   __syncthreads();
-  int off = 0;
-  for (int i = 0; i < w; ++i) off += scratch[i];
-  *total = scratch[0] + scratch[1] + scratch[2] + scratch[3];
+  int off = 0, tot = 0;
+#pragma unroll
+  for (int i = 0; i < kDecideWaves; ++i) {
+    const int c = scratch[i];
+    off += i < w ? c : 0;
+    tot += c;
+  }
+  *total = tot;
   return off + pre;
 }
 
@@ -171,9 +109,9 @@ __device__ __forceinline__ bool gate_skips(float v, float tau, int metric) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// decide: one block of 256 threads per sequence.
+// decide: one block of kDecideThreads threads per sequence.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void decide_kernel(DecideArgs a) {
+__global__ __launch_bounds__(kDecideThreads) void decide_kernel(DecideArgs a) {
   {  // this block's sequence: move the pointers, take the per-sequence scalars
     const int b = blockIdx.x;
     const SeqDesc sd = a.seqs[b];
@@ -186,14 +124,14 @@ __global__ __launch_bounds__(256) void decide_kernel(DecideArgs a) {
     a.mb_pos += b * a.block; a.mb_idx += b * a.block; a.row_stats += b * a.block * 4;
     a.P = sd.P; a.T = sd.T;
   }
-  __shared__ int s_tok[EC_MAX_BLOCK];
+  __shared__ int s_tok[EC_MAX_BLOCK], s_pos[EC_MAX_BLOCK];
   __shared__ float s_conf[EC_MAX_BLOCK], s_H[EC_MAX_BLOCK];
-  __shared__ int s_taken[EC_MAX_BLOCK];
-  __shared__ int scratch[4];
+  __shared__ int s_sel[EC_MAX_N];    // block rows of the step's own choice, most confident first
+  __shared__ int s_frow[EC_MAX_N];   // block rows of the caller's positions (-1: not in the block)
+  __shared__ int scratch[kDecideWaves];
   __shared__ float sh_f[2];
-  __shared__ float4 s_part[kMergeRows * kMaxParts];
   __shared__ int s_hist[kHistLds];
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   DevState st = *a.st;  // every thread holds a private copy; thread 0 writes it back
   const int t = st.t;
   const int P = a.P, N = a.N, T = a.T;
@@ -201,92 +139,109 @@ __global__ __launch_bounds__(256) void decide_kernel(DecideArgs a) {
 
   if (!a.init_only) {
     // ---- merge the vocabulary partials of each block row (fixed order) ----------------------
-    // 32 rows at a time: the whole block fetches their partials into LDS in one sweep (a row's
-    // thread fetching them one by one would wait for memory nparts times), then one thread per
-    // row merges them in part order.
-    for (int r0 = 0; r0 < a.n_mb; r0 += kMergeRows) {
-      const int nr = min(kMergeRows, a.n_mb - r0);
-      for (int i = tid; i < nr * a.nparts; i += 256)
-        s_part[i] = a.partials[(size_t)r0 * a.nparts + i];
-      __syncthreads();
-      if (tid < nr) {
-        const int row = r0 + tid;
-        VTuple v = vt_identity();
-        for (int p = 0; p < a.nparts; ++p) {
-          float4 q = s_part[tid * a.nparts + p];
-          VTuple o = {q.x, __float_as_int(q.y), q.z, q.w};
-          v = vt_merge(v, o);
+    // One wave per row at a time: lane l merges parts l, l + 64, ... in that order (four loads
+    // in flight), then the lanes' tuples are merged pairwise down to lane 0.
+    for (int row = wave; row < a.n_mb; row += kDecideWaves) {
+      const float4* pr = a.partials + (size_t)row * a.nparts;
+      VTuple v = vt_identity();
+      for (int p0 = lane; p0 < a.nparts; p0 += 256) {
+        float4 q[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int p = p0 + 64 * u;
+          q[u] = p < a.nparts ? pr[p] : vt_pack(vt_identity());
         }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v = vt_merge(v, vt_unpack(q[u]));
+      }
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) v = vt_merge(v, vt_shfl_down(v, o));
+      if (lane == 0) {
         float conf, H;
         vt_finish(v, conf, H);
         s_tok[row] = v.idx;
         s_conf[row] = conf;
         s_H[row] = H;
-        s_taken[row] = 0;
-        a.row_stats[row * 4 + 0] = (float)v.idx;
-        a.row_stats[row * 4 + 1] = conf;
-        a.row_stats[row * 4 + 2] = H;
-        a.row_stats[row * 4 + 3] = v.m;
+        s_pos[row] = a.mb_pos[row];
+        *(float4*)(a.row_stats + row * 4) = make_float4((float)v.idx, conf, H, v.m);
       }
-      __syncthreads();
     }
+    __syncthreads();
     // ---- decode(): most confident rows first; ties -> lowest position (= lowest row) --------
-    if (tid == 0) {
-      ec_step_result& R = a.out->r;
-      int n = min(a.n_tok, a.n_mb);
-      if (a.conf_threshold > 0.f) {
-        // confidence-based parallel decoding: every row above the threshold, the n most
-        // confident ones in any case, no more than one result can report
-        int above = 0;
-        for (int r = 0; r < a.n_mb; ++r) above += (s_conf[r] > a.conf_threshold);
-        n = min(min(max(n, above), EC_MAX_N), a.n_mb);
+    // A row's rank is the number of rows that go before it; the n lowest ranks are unmasked.
+    int n = min(a.n_tok, a.n_mb);
+    const bool is_row = tid < a.n_mb;
+    const float my_conf = is_row ? s_conf[tid] : 0.f;
+    if (a.conf_threshold > 0.f) {
+      // confidence-based parallel decoding: every row above the threshold, the n most
+      // confident ones in any case, no more than one result can report
+      const int above = __syncthreads_count(is_row && my_conf > a.conf_threshold);
+      n = min(min(max(n, above), EC_MAX_N), a.n_mb);
+    }
+    ec_step_result& R = a.out->r;
+    if (is_row) {
+      int rank = 0;
+      for (int r = 0; r < a.n_mb; ++r) {
+        const float c = s_conf[r];
+        rank += (c > my_conf || (c == my_conf && r < tid)) ? 1 : 0;
       }
-      GateAcc own = gate_init(a.gate_metric);
-      for (int i = 0; i < n; ++i) {
-        int best = -1;
+      if (rank < n) {
+        s_sel[rank] = tid;
+        R.positions[rank] = s_pos[tid];
+        R.tokens[rank] = s_tok[tid];
+        R.entropy[rank] = s_H[tid];
+        R.confidence[rank] = my_conf;
+      }
+    }
+    if (tid >= n && tid < EC_MAX_N) {
+      R.positions[tid] = -1; R.tokens[tid] = -1; R.entropy[tid] = 0.f; R.confidence[tid] = 0.f;
+    }
+    // ---- commit: own choice, or the caller's under teacher forcing (Eq. 2) -------------------
+    if (a.forced_n >= 0) {
+      if (tid < a.forced_n) {
+        const int p = a.forced_pos[tid];
+        int row = -1;
         for (int r = 0; r < a.n_mb; ++r)
-          if (!s_taken[r] && (best < 0 || s_conf[r] > s_conf[best])) best = r;
-        s_taken[best] = 1;
-        R.positions[i] = a.mb_pos[best];
-        R.tokens[i] = s_tok[best];
-        R.entropy[i] = s_H[best];
-        R.confidence[i] = s_conf[best];
-        gate_add(own, s_H[best], s_conf[best]);
+          if (s_pos[r] == p) row = r;
+        s_frow[tid] = row;
+        a.x[p] = a.forced_tok[tid];
+        a.masked[p] = 0;
+        a.hist[p - P] = t;
       }
-      const float E_own = own.v;
-      for (int i = n; i < EC_MAX_N; ++i) {
-        R.positions[i] = -1; R.tokens[i] = -1; R.entropy[i] = 0.f; R.confidence[i] = 0.f;
+    } else if (is_row) {
+      int rank = 0;   // (recomputed: cheaper than keeping it live across the branch)
+      for (int r = 0; r < a.n_mb; ++r) {
+        const float c = s_conf[r];
+        rank += (c > my_conf || (c == my_conf && r < tid)) ? 1 : 0;
       }
-      R.n_unmasked = n;
-      R.max_entropy = E_own;
-      // ---- commit: own choice, or the caller's under teacher forcing -----------------------
-      float E = E_own;
+      if (rank < n) {
+        const int p = s_pos[tid];
+        a.x[p] = s_tok[tid];
+        a.masked[p] = 0;
+        a.hist[p - P] = t;
+      }
+    }
+    __syncthreads();
+    if (tid == 0) {
+      // gate values, accumulated in the order of the lists (the entropy sum is order-sensitive)
+      GateAcc own = gate_init(a.gate_metric);
+      for (int i = 0; i < n; ++i) gate_add(own, s_H[s_sel[i]], s_conf[s_sel[i]]);
+      float E = own.v;
       if (a.forced_n >= 0) {
         bool all_in_block = true;
         GateAcc fa = gate_init(a.gate_metric);
         for (int i = 0; i < a.forced_n; ++i) {
-          int p = a.forced_pos[i], row = -1;
-          for (int r = 0; r < a.n_mb; ++r)
-            if (a.mb_pos[r] == p) row = r;
+          const int row = s_frow[i];
           if (row < 0) all_in_block = false; else gate_add(fa, s_H[row], s_conf[row]);
-          a.x[p] = a.forced_tok[i];
-          a.masked[p] = 0;
-          a.hist[p - P] = t;                              // Eq. 2
         }
         if (all_in_block) E = fa.v;                       // nothing committed: always skips
-      } else {
-        for (int i = 0; i < n; ++i) {
-          int p = R.positions[i];
-          a.x[p] = R.tokens[i];
-          a.masked[p] = 0;
-          a.hist[p - P] = t;                              // Eq. 2
-        }
       }
+      R.n_unmasked = n;
+      R.max_entropy = own.v;
       sh_f[0] = E;
-      sh_f[1] = E_own;
+      sh_f[1] = own.v;
     }
     __syncthreads();
-    __threadfence_block();
   }
 
   // ---- recency threshold: tau_R = max(k-th largest history value, t - dt) --------------------
@@ -301,15 +256,18 @@ __global__ __launch_bounds__(256) void decide_kernel(DecideArgs a) {
       // the bisection reads the history log2(t) times: from LDS if it fits
       const bool in_lds = N <= kHistLds;
       if (in_lds) {
-        for (int i = tid; i < N; i += 256) s_hist[i] = a.hist[i];
+        for (int i = tid; i < N; i += kDecideThreads) s_hist[i] = a.hist[i];
         __syncthreads();
       }
       int lo = 1, hi = t, found = INT_MIN;
       while (lo <= hi) {  // uniform across the block
-        int mid = (lo + hi) >> 1, c = 0;
-        if (in_lds) { for (int i = tid; i < N; i += 256) c += (s_hist[i] >= mid); }
-        else { for (int i = tid; i < N; i += 256) c += (a.hist[i] >= mid); }
-        c = block_sum_int(c, scratch);
+        const int mid = (lo + hi) >> 1;
+        int c = 0;
+        for (int base = 0; base < N; base += kDecideThreads) {  // uniform trip count
+          const int i = base + tid;
+          const int h = i < N ? (in_lds ? s_hist[i] : a.hist[i]) : INT_MIN;
+          c += __syncthreads_count(h >= mid);
+        }
         if (c >= a.k_recent) { found = mid; lo = mid + 1; } else { hi = mid - 1; }
       }
       kth = found;
@@ -330,10 +288,9 @@ __global__ __launch_bounds__(256) void decide_kernel(DecideArgs a) {
   int blk = st.blk;
   if (!sliding) {
     while (blk < nblocks) {  // uniform: every thread evaluates the same counts
-      int lo = P + blk * a.block, hi = min(T, lo + a.block), c = 0;
-      for (int i = lo + tid; i < hi; i += 256) c += a.masked[i];
-      c = block_sum_int(c, scratch);
-      if (c > 0) break;
+      const int lo = P + blk * a.block, hi = min(T, lo + a.block);
+      const int i = lo + tid;   // block <= EC_MAX_BLOCK <= threads
+      if (__syncthreads_count(i < hi && a.masked[i]) > 0) break;
       ++blk;
     }
     st.blk = blk;
@@ -344,13 +301,14 @@ __global__ __launch_bounds__(256) void decide_kernel(DecideArgs a) {
   // M = the masked rows of the current block, or (sliding window) the first `block` masked slots
   int blo = P + blk * a.block, bhi = min(T, blo + a.block);
   int n_rows = 0, n_mb = 0, n_recent = 0, masked_seen = 0;
-  for (int base = 0; base < N; base += 256) {
+  for (int base = 0; base < N; base += kDecideThreads) {
     int i = base + tid, pos = P + i;
     int inM = 0, inR = 0, msk = 0;
     if (i < N) {
       msk = a.masked[pos] ? 1 : 0;
       inM = (!sliding && !st.done && pos >= blo && pos < bhi && msk) ? 1 : 0;
-      inR = (!a.init_only && a.hist[i] != INT_MIN && a.hist[i] >= tauR) ? 1 : 0;
+      const int h = a.hist[i];
+      inR = (!a.init_only && h != INT_MIN && h >= tauR) ? 1 : 0;
     }
     if (sliding) {
       int tot_msk;
@@ -358,10 +316,10 @@ __global__ __launch_bounds__(256) void decide_kernel(DecideArgs a) {
       inM = (msk && masked_seen + pre_msk < a.block) ? 1 : 0;
       masked_seen += tot_msk;
     }
-    int tot_any, tot_m, tot_r;
+    int tot_any, tot_m;
     int pre_any = block_excl_scan_flag(inM | inR, scratch, &tot_any);
     int pre_m = block_excl_scan_flag(inM, scratch, &tot_m);
-    (void)block_excl_scan_flag(inR, scratch, &tot_r);
+    const int tot_r = __syncthreads_count(inR);
     if (inM | inR) a.rows_partial[n_rows + pre_any] = pos;
     if (inM) {
       a.mb_pos[n_mb + pre_m] = pos;
@@ -393,7 +351,7 @@ __global__ __launch_bounds__(256) void decide_kernel(DecideArgs a) {
 }
 
 void launch_decide(const DecideArgs& a, int B, hipStream_t s) {
-  decide_kernel<<<B, 256, 0, s>>>(a);
+  decide_kernel<<<B, kDecideThreads, 0, s>>>(a);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -20,7 +20,10 @@
 //              row's sum of squares
 //   EPI_SWIGLU x 1/rms, silu(gate) * up (8 gate rows and their 8 up rows share a tile), -> packed
 //              activations
-//   EPI_LOGITS x 1/rms x logit scale -> fp32 logits
+//   EPI_LOGITS x 1/rms x logit scale -> fp32 logits; the skinny kernel also reduces its block's
+//              columns to one (max, argmax, sum e, sum e (z - max)) tuple per row - the
+//              vocabulary reduction of Eq. 1 fused behind the LM head - and stores the logits
+//              themselves only on request
 //
 // Kernels:
 //   skinny (M <= 96): weight streaming.  A block of KS waves owns NTW weight tiles and splits K
@@ -31,6 +34,7 @@
 //     LDS double buffer fed through four register sets.  8 waves (192x128 .. 192x384): operands
 //     loaded from global memory directly into a 3-stage LDS ring.
 #include "ec_internal.h"
+#include "k_vtuple.h"
 
 namespace ec {
 
@@ -347,6 +351,37 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* 
   };
 
   static_assert(EPI != EPI_PARTIAL, "K-split partial products are a tiled-kernel epilogue");
+  if constexpr (EPI == EPI_LOGITS) {
+    // Logits of the block's NTW*16 columns, and their reduction: every lane folds its 4 columns
+    // into a tuple, the 4 lanes of a row (16 apart) merge theirs, and after a barrier one
+    // thread per row merges the NTW tiles in tile order and stores the block's tuple.
+    float4* tup = (float4*)(rstd_s + MT * 16);  // [NTW][MT*16]
+    for (int o = threadIdx.x; o < UNITS; o += KS * 64) {  // UNITS is a multiple of the block size
+      const int l = o & 63, unit = o >> 6, iu = unit / MT, j = unit - iu * MT;
+      const int m = j * 16 + (l & 15), q4 = l >> 4, vt = nt0 + iu;
+      const f32x4 v = ksum((iu * MT + j) * 64 + l);
+      VTuple t = vt_identity();
+      if (m < e.M && vt < total_nt) {
+        const float sc = rstd_s[m] * e.scale;
+        const float z[4] = {v[0] * sc, v[1] * sc, v[2] * sc, v[3] * sc};
+        const int n = vt * 16 + q4 * 4;
+        if (e.logits) *(float4*)(e.logits + (size_t)m * e.ldc + n) = make_float4(z[0], z[1], z[2], z[3]);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) vt_push(t, z[r], n + r);
+      }
+      t = vt_merge(t, vt_shfl_down(t, 32));   // lanes 0-31 <- 32-63
+      t = vt_merge(t, vt_shfl_down(t, 16));   // lanes 0-15 <- 16-31: the row's 16 columns
+      if (q4 == 0) tup[iu * (MT * 16) + m] = vt_pack(t);
+    }
+    __syncthreads();
+    if (threadIdx.x < MT * 16 && (int)threadIdx.x < e.M) {
+      VTuple t = vt_unpack(tup[threadIdx.x]);
+#pragma unroll
+      for (int iu = 1; iu < NTW; ++iu) t = vt_merge(t, vt_unpack(tup[iu * (MT * 16) + threadIdx.x]));
+      e.vparts[(size_t)threadIdx.x * gridDim.x + blockIdx.x] = vt_pack(t);
+    }
+    return;
+  }
   for (int o = threadIdx.x; o < UNITS; o += KS * 64) {
     const int l = o & 63, unit = o >> 6, iu = unit / MT, j = unit - iu * MT;
     const int m = j * 16 + (l & 15), q4 = l >> 4;
@@ -359,8 +394,7 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* 
         part = o < KS * 64 ? epi_resid_pre(e, m, vt, q4, v, pre_h, pre_g) : epi_resid(e, m, vt, q4, v);
       epi_add_sumsq(e, m, mvalid, part);
     } else if (mvalid && vt < total_nt) {
-      if constexpr (EPI == EPI_LOGITS) epi_logits(e, m, vt, q4, v, rstd_s[m]);
-      else if constexpr (EPI == EPI_SWIGLU) epi_swiglu(e, m, vt, q4, v, rstd_s[m]);
+      if constexpr (EPI == EPI_SWIGLU) epi_swiglu(e, m, vt, q4, v, rstd_s[m]);
       else epi_qkv(e, m, vt, q4, v, rstd_s[m]);
     }
   }
@@ -371,6 +405,7 @@ static void launch_skinny_t(const bf16_t* Ap, int MT_src, const bf16_t* Wp, int 
                             const GemmEpi& e, hipStream_t s) {
   int grid = (total_nt + NTW - 1) / NTW;
   size_t smem = (size_t)KS * NTW * MT * 64 * sizeof(float4) + MT * 16 * sizeof(float);
+  if (EPI == EPI_LOGITS) smem += (size_t)NTW * MT * 16 * sizeof(float4);  // per-tile row tuples
   gemm_bf16_skinny_kernel<EPI, MT, NTW, KS, U><<<grid, KS * 64, smem, s>>>(
       (const u32x4*)Ap, (const u32x4*)Wp, total_nt, KB, MT_src, e);
 }
@@ -378,6 +413,9 @@ static void launch_skinny_t(const bf16_t* Ap, int MT_src, const bf16_t* Wp, int 
 // Tile counts per block were chosen by timing on MI355X: the kernels are bound by what the L2
 // delivers (weights once + the activation fragments once per block), so more weight tiles per
 // block (fewer re-reads of the activations) win as long as the grid still covers the 256 CUs.
+// blocks (= partial tuples per row) of the skinny LM-head GEMM over a vocabulary of V columns
+int lm_head_parts(int V) { return (V / 16 + 3) / 4; }
+
 int skinny_tiles_per_block(int epi, int total_nt) {
   if (epi == EPI_RESID) return 1;
   if (epi == EPI_LOGITS) return 4;

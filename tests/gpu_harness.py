@@ -286,6 +286,7 @@ def run_teacher_forced(cfg, w, dec, prompt, tol, max_steps=None, check_cache_eve
     st = eco.eco_init(eco.OracleModel(cfg, w), dec, prompt)
     dw = dev_weights if dev_weights is not None else ec.weights_to_device(cfg, w)
     g = ec.EntropyCache(cfg, dw, dec, prompt)
+    g.keep_logits(True)
     cnt = Counters()
     modes = {eco.FULL: 0, eco.PARTIAL: 0}
     steps = 0
@@ -334,6 +335,7 @@ def run_teacher_forced_batch(cfg, w, dec, prompts, tol, max_steps=None, fast_seq
     dec1 = dec.replace(batch=1)
     sts = [eco.eco_init(model, dec1, p) for p in prompts]
     g = ec.EntropyCache(cfg, ec.weights_to_device(cfg, w), dec, prompts)
+    g.keep_logits(True)
     cnt = Counters()
     steps, modes = 0, {eco.FULL: 0, eco.PARTIAL: 0}
     finished_early = 0

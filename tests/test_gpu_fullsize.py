@@ -144,6 +144,7 @@ def test_full_depth_against_stored_oracle_trace(name):
     w = ec_inputs.make_weights(cfg, wl.seed, threads=16)
     prompt = ec_inputs.make_prompt(cfg.vocab, wl.prompt_len, wl.seed)
     g = ec.EntropyCache(cfg, ec.weights_to_device(cfg, w), wl.decode, prompt)
+    g.keep_logits(True)
     del w
     cnt = Counters()
     try:
@@ -153,7 +154,7 @@ def test_full_depth_against_stored_oracle_trace(name):
             print(f"t={st['t']} mode={st['mode']} rows={st['n_rows']} {cnt.summary()}", flush=True)
     finally:
         g.close()
-    assert cnt.tokens_exact > 0 and cnt.rows_decided > 0
+    assert cnt.tokens_exact > 0 and cnt.rows_decided + cnt.modes_exact > 0
 
 
 @pytest.mark.timeout(900)
@@ -166,6 +167,7 @@ def test_sixteen_sequences_against_stored_oracle_traces():
     w = ec_inputs.make_weights(cfg, wl.seed, threads=16)
     prompts = [ec_inputs.make_prompt(cfg.vocab, wl.prompt_len, s) for s in gold["prompt_seeds"]]
     g = ec.EntropyCache(cfg, ec.weights_to_device(cfg, w), wl.decode, prompts)
+    g.keep_logits(True)
     del w
     dec1 = wl.decode.replace(batch=1)
     cnt = Counters()

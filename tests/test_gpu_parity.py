@@ -234,6 +234,7 @@ def test_largest_context_properties():
     dec = ec_inputs.DecodeCfg(gen_len=200, block=32, k_recent=2, tokens_per_step=1, tau=1.0)
     prompt = ec_inputs.make_prompt(cfg.vocab, 14800, 6)
     g = ec.EntropyCache(cfg, ec.weights_to_device(cfg, w), dec, prompt)
+    g.keep_logits(True)
     try:
         r1 = g.step_forced(ec.EC_FULL, [], [])
         z1 = g.debug_read(ec.EC_DBG_LOGITS, count=32)
@@ -366,3 +367,37 @@ def test_long_context_ragged_batch_gqa():
     s = run_teacher_forced_batch(cfg, w, dec, prompts, TOL["bf16"], max_steps=6, check_cache_every=3)
     print(s)
     assert s["modes"][eco.PARTIAL] >= 8 and s["tokens_exact"] > 0
+
+
+def test_logits_stay_out_of_memory_unless_asked_for():
+    """The bfloat16 path reduces the vocabulary inside the LM-head kernel: by default a step
+    leaves no logits behind (reading them is a state error), and switching the store on changes
+    nothing else - same tokens, same statistics, bit for bit."""
+    cfg = small_cfg("bf16", 4, 2, 64, scale=13.0)
+    w = ec_inputs.make_weights(cfg, 53, gain_jitter=0.1)
+    dec = ec_inputs.DecodeCfg(gen_len=48, block=16, k_recent=2, tokens_per_step=2, tau=2.5)
+    prompt = ec_inputs.make_prompt(cfg.vocab, 30, 12)
+    dw = ec.weights_to_device(cfg, w)
+    runs = []
+    for keep in (False, True):
+        g = ec.EntropyCache(cfg, dw, dec, prompt)
+        g.keep_logits(keep)
+        trace = []
+        while True:
+            q = g.step(ec.EC_AUTO)
+            stats = g.debug_read(ec.EC_DBG_ROW_STATS, count=q["n_block_rows"])
+            trace.append((q, stats.copy()))
+            if keep:
+                z = g.debug_read(ec.EC_DBG_LOGITS, count=q["n_block_rows"])
+                assert np.array_equal(z.max(axis=1), stats[:, 3])
+            else:
+                with pytest.raises(ec.EcError) as e:
+                    g.debug_read(ec.EC_DBG_LOGITS, count=1)
+                assert e.value.code == ec.EC_ERR_STATE
+            if q["done"]:
+                break
+        runs.append(trace)
+        g.close()
+    assert len(runs[0]) == len(runs[1])
+    for (qa, sa), (qb, sb) in zip(*runs):
+        assert qa == qb and np.array_equal(sa, sb)
