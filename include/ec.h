@@ -267,6 +267,20 @@ size_t ec_row_entropy_workspace_bytes(int32_t rows, int32_t vocab);
 int ec_row_entropy(const float *logits, int32_t rows, int32_t vocab, size_t ld, float *stats,
                    void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* ec_row_entropy for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels
+ * and results (bit for bit) as ec_row_entropy, but the partial tuples live in a 160 KiB array
+ * that is part of the library's device image (one copy per GPU, held until the process ends):
+ * the call allocates nothing, on the device or through any library.  Limits as ec_row_entropy
+ * (rows <= EC_MAX_BLOCK, vocab <= 163840; anything beyond is EC_ERR_ARG).  The array keeps the
+ * last call's contents and every entry a call reads it has written before, so nothing needs
+ * clearing; all calls on one GPU share it, so two calls that overlap in time on the same GPU
+ * (different streams, different threads) race - serialise them.  The first call on a device
+ * looks up the array's device address (hipGetSymbolAddress); do that call outside a capture.
+ * Errors: EC_ERR_ARG, EC_ERR_HIP. */
+int ec_row_entropy_noalloc(const float *logits, int32_t rows, int32_t vocab, size_t ld,
+                           float *stats, void *hip_stream);
+
 /* Frees host-side state only; never frees weights or workspace.  NULL is allowed. */
 void ec_destroy(ec_ctx *ctx);
 

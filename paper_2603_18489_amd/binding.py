@@ -31,7 +31,7 @@ KERNEL_CLASS_NAMES = ["embed", "norm", "qkv", "rope_kv", "attn", "oproj", "gateu
 EXPORTS = ["ec_workspace_bytes", "ec_init", "ec_reset", "ec_step", "ec_step_forced", "ec_debug_keep_logits",
            "ec_step_forced_batch", "ec_generate", "ec_profile_enable", "ec_profile_read",
            "ec_debug_read", "ec_debug_read_seq", "ec_destroy", "ec_strerror", "ec_last_error",
-           "ec_row_entropy_workspace_bytes", "ec_row_entropy"]
+           "ec_row_entropy_workspace_bytes", "ec_row_entropy", "ec_row_entropy_noalloc"]
 
 
 class ec_model_cfg(C.Structure):
@@ -124,6 +124,8 @@ def load_library() -> C.CDLL:
     lib.ec_row_entropy_workspace_bytes.argtypes = [C.c_int32, C.c_int32]
     lib.ec_row_entropy.restype = C.c_int
     lib.ec_row_entropy.argtypes = [vp, C.c_int32, C.c_int32, C.c_size_t, vp, vp, C.c_size_t, vp]
+    lib.ec_row_entropy_noalloc.restype = C.c_int
+    lib.ec_row_entropy_noalloc.argtypes = [vp, C.c_int32, C.c_int32, C.c_size_t, vp, vp]
     lib.ec_destroy.restype = None
     lib.ec_destroy.argtypes = [vp]
     lib.ec_strerror.restype = C.c_char_p
@@ -196,6 +198,22 @@ def row_entropy(logits, stream=None):
         raise EcError(rc, lib.ec_last_error(None).decode())
     st.synchronize()     # the workspace is released on return
     return stats
+
+
+def row_entropy_noalloc(logits, stats, stream=None):
+    """ec_row_entropy_noalloc: `stats` is a caller-provided float32 CUDA tensor [rows, 4]; the
+    call itself allocates nothing.  Enqueued on `stream` (default: current), not synchronised."""
+    import torch
+    lib = load_library()
+    rows, vocab = logits.shape
+    assert logits.dtype == torch.float32 and logits.stride(1) == 1
+    assert stats.dtype == torch.float32 and stats.is_contiguous() and stats.shape == (rows, 4)
+    st = stream if stream is not None else torch.cuda.current_stream()
+    rc = lib.ec_row_entropy_noalloc(C.c_void_p(logits.data_ptr()), rows, vocab,
+                                    logits.stride(0) if rows > 1 else vocab,
+                                    C.c_void_p(stats.data_ptr()), C.c_void_p(st.cuda_stream))
+    if rc != EC_OK:
+        raise EcError(rc, lib.ec_last_error(None).decode())
 
 
 class EntropyCache:

@@ -2,6 +2,7 @@
 // per row (argmax token, confidence, entropy, max logit).  Same kernels as the denoising step
 // uses for a materialised logits matrix.
 #include <cstdio>
+#include <mutex>
 #include <string>
 
 #include "ec_internal.h"
@@ -37,6 +38,37 @@ int run(const float* logits, int rows, int vocab, size_t ld, float* stats, float
   return EC_OK;
 }
 
+// ---- scratch of the call that allocates nothing --------------------------------------------
+// Room for the partial tuples of the largest call: EC_MAX_BLOCK rows x 80 parts (vocabularies up
+// to 163840) x 16 bytes = 160 KiB.  Every GPU the library runs on holds its own copy of the array
+// at its own address until the process ends.  `scratch` is only the host-side handle of the
+// symbol: the device address comes from hipGetSymbolAddress, once per device.
+constexpr int kScratchParts = 80;
+constexpr size_t kScratchTuples = (size_t)kRowsMax * kScratchParts;
+static __device__ __align__(256) float4 scratch[kScratchTuples];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+float4* g_scratch_ptr[kMaxDevices] = {};
+
+// device address of `scratch` on the current device (looked up on the first call there)
+int scratch_of_current_device(float4** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return rs_fail(EC_ERR_HIP, std::string("hipGetDevice: ") + hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return rs_fail(EC_ERR_HIP, "device index out of range");
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p)
+      return rs_fail(EC_ERR_HIP, std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e));
+    g_scratch_ptr[dev] = (float4*)p;
+  }
+  *out = g_scratch_ptr[dev];
+  return EC_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -56,6 +88,18 @@ int ec_row_entropy(const float* logits, int32_t rows, int32_t vocab, size_t ld, 
   if (workspace_bytes < ec_row_entropy_workspace_bytes(rows, vocab))
     return rs_fail(EC_ERR_WORKSPACE, "workspace smaller than ec_row_entropy_workspace_bytes()");
   return run(logits, rows, vocab, ld, stats, (float4*)workspace, (hipStream_t)hip_stream);
+}
+
+int ec_row_entropy_noalloc(const float* logits, int32_t rows, int32_t vocab, size_t ld,
+                           float* stats, void* hip_stream) {
+  int rc = check_args(logits, rows, vocab, ld, stats);
+  if (rc != EC_OK) return rc;
+  if ((size_t)rows * vocab_reduce_parts(vocab) > kScratchTuples)
+    return rs_fail(EC_ERR_ARG, "rows x vocabulary parts exceed the library's static scratch");
+  float4* part = nullptr;
+  rc = scratch_of_current_device(&part);
+  if (rc != EC_OK) return rc;
+  return run(logits, rows, vocab, ld, stats, part, (hipStream_t)hip_stream);
 }
 
 }  // extern "C"
