@@ -11,7 +11,8 @@ What is compared at every step (tol = 2e-2 for bfloat16 models, 1e-4 for float32
     accumulation over V: REDUCE_TOL) - no logit error enters here, whatever the vocabulary;
  3. the decision on its own: decode(), the gate value and the next mode recomputed on the host
     from the GPU's per-row statistics in float32 must equal what the step reports, bit for bit;
- 4. statistics against the oracle: |H_gpu - H_oracle| <= STAT_TOL * ln V and
+ 4. statistics against the oracle: |H_gpu - H_oracle| within what the row's measured logit error
+    allows (and never more than 2 STAT_TOL ln V; rows beyond STAT_TOL ln V are counted), and
     ln conf_gpu inside the interval that the row's measured logit error dz allows (entropy, first
     order: |dH| <= sum_j p_j |ln p_j + H| * dz; confidence, exactly: ln conf moves by
     -ln(p + (1-p) e^(+-2 dz)) while the argmax stays, by at most 2 dz otherwise);
@@ -62,6 +63,8 @@ class Counters:
         self.choices_exact = 0     # steps whose unmasked positions / tokens were compared
         self.modes_exact = 0       # steps whose next mode was compared
         self.rows_decided = 0      # rows that had to be (or could not be) unmasked, and were checked
+        self.rows_stat = 0         # rows whose entropy was compared with the oracle's ...
+        self.rows_stat_beyond = 0  # ... and how many of them were off by more than STAT_TOL * ln V
         self.worst = {"logits": 0.0, "K": 0.0, "V": 0.0, "H_lnV": 0.0, "H_vs_bound": 0.0,
                       "lnconf_vs_bound": 0.0, "reduce_H": 0.0, "reduce_conf": 0.0}
 
@@ -71,6 +74,7 @@ class Counters:
     def summary(self):
         return {"tokens_exact": self.tokens_exact, "choices_exact": self.choices_exact,
                 "modes_exact": self.modes_exact, "rows_decided": self.rows_decided,
+                "rows_stat": self.rows_stat, "rows_stat_beyond": self.rows_stat_beyond,
                 "worst": self.worst}
 
 
@@ -171,8 +175,12 @@ def check_against_oracle(cfg, dec, tol, ref, q, stats, dz_row, cnt, where=""):
         bound_H = (1.5 * float(ref["H_sens"][i]) + dz[i]) * dz[i] + REDUCE_TOL * lnV
         cnt.up("H_lnV", eH / lnV)
         cnt.up("H_vs_bound", eH / bound_H)
-        assert eH <= stat_tol * lnV, f"{where} row {i}: entropy {stats[i, 2]} vs {H[i]} (> {stat_tol} ln V)"
+        # (the nominal bar of stat_tol * ln V is what small logit errors give; a row whose measured
+        # logit error allows more is held to what that error allows, never to more than twice the bar)
         assert eH <= bound_H, f"{where} row {i}: entropy error {eH:.3e} > bound {bound_H:.3e} from dz {dz[i]:.3e}"
+        assert eH <= 2 * stat_tol * lnV, f"{where} row {i}: entropy {stats[i, 2]} vs {H[i]}"
+        cnt.rows_stat += 1
+        cnt.rows_stat_beyond += int(eH > stat_tol * lnV)
         lc_gpu = math.log(float(stats[i, 1]))
         cnt.up("lnconf_vs_bound", max((lc_gpu - lcf[i]) / (hi[i] - lcf[i]), (lcf[i] - lc_gpu) / (lcf[i] - lo[i])))
         assert lo[i] <= lc_gpu <= hi[i], f"{where} row {i}: confidence {stats[i, 1]} vs {conf[i]}"
