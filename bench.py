@@ -1,14 +1,22 @@
 """Benchmark of the EntropyCache denoising step on one MI355X.
 
-A "step" is one denoising step of the whole hot path (forward in FULL or PARTIAL mode, LM head,
-vocabulary reduction, decision).  The timed region runs exactly --steps steps of free-running
-generation (EC_AUTO) on the synthetic LLaDA-8B-shaped workload, whose logit scale was calibrated
-beforehand so that the fraction of FULL steps is near the paper's recompute ratio; generations
-restart (untimed reset) when they finish.  Inputs are resident in HBM before timing starts.
+A "step" is one denoising step of the whole hot path (forward in FULL or PARTIAL mode, LM head
+with the fused vocabulary reduction, decision).  The workload is the synthetic LLaDA-8B-shaped
+model (32 layers, prompt 512 + 256 generated tokens, block 32, one token per step, k = 2,
+tau = 1.0); its logit scale is calibrated beforehand so that the fraction of FULL steps of a
+free-running generation is near the paper's recompute ratio.  Inputs are resident in HBM before
+any timing starts.
 
-Prints ONE JSON line: whole-job generated tokens/s plus per-mode step rates, the roofline of the
-dominant kernel (from HIP events recorded on the library's stream), and the CPU oracle timed on
-a bounded sample of the same workload.
+The timed region runs exactly --steps consecutive free-running (EC_AUTO) steps of that
+generation.  The generation is deterministic, so its sequence of modes is known from an earlier
+pass: the window starts at the step from which --steps steps hold the same share of FULL steps
+as the whole generation does (a window at the very start would hold hardly any), and the steps
+before it run untimed.  A complete generation is timed beside it (`whole_generation`).
+
+Prints ONE JSON line: whole-job generated tokens/s, per-mode step rates, the roofline of the
+dominant kernel (HIP events recorded on the library's stream), the same step measurements for
+the other workloads (Dream-7B shape, long chain-of-thought shape, 16 sequences), and the CPU
+oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
@@ -30,9 +38,9 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def algorithmic_bytes(cfg, T, rows, n_mb):
-    """HBM bytes one PARTIAL step must move: every matrix once, the KV cache read once per layer,
-    the new K/V rows written.  Activations are left out (< 0.1 %)."""
+def algorithmic_bytes(cfg, T, rows):
+    """HBM bytes one PARTIAL step of one sequence must move: every matrix once, the KV cache read
+    once per layer, the new K/V rows written.  Activations are left out (< 0.1 %)."""
     import ec_inputs
     es = 2 if cfg.dtype == "bf16" else 4
     kv = cfg.n_layers * 2 * T * cfg.n_kv_heads * cfg.head_dim * es
@@ -50,28 +58,35 @@ def full_step_flops(cfg, T, n_mb):
 
 
 def gateup_bytes(cfg, rows):
+    """Algorithmic bytes of one gate/up launch: both matrices once, the rows' operand in, the
+    rows' SwiGLU output out (bf16)."""
     es = 2 if cfg.dtype == "bf16" else 4
-    return 2 * cfg.d_ffn * cfg.d_model * es + rows * cfg.d_model * es + rows * 2 * cfg.d_ffn * 4
+    return 2 * cfg.d_ffn * cfg.d_model * es + rows * cfg.d_model * es + rows * cfg.d_ffn * es
 
 
-def run_generation(g, prompt, mode_fn=None, max_steps=None, timed=False):
-    """Runs steps until done (or max_steps); returns (steps, full, tokens, seconds)."""
+def run_generation(g, prompt, mode_fn=None, max_steps=None, first_untimed=0):
+    """Runs steps until done (or max_steps).  The first `first_untimed` steps run before the
+    clock starts (synchronised on both sides).  Returns (modes of all steps, tokens of the timed
+    steps, seconds of the timed steps)."""
     import torch
     import paper_2603_18489_amd as ec
     g.reset(prompt)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    steps = full = toks = 0
+    modes = []
+    toks = 0
+    t0 = None
     while True:
-        mode = ec.EC_AUTO if mode_fn is None else mode_fn(steps)
+        if len(modes) == first_untimed:
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+        mode = ec.EC_AUTO if mode_fn is None else mode_fn(len(modes))
         r = g.step(mode)
-        steps += 1
-        full += int(r["mode_run"] == ec.EC_FULL)
-        toks += r["n_unmasked"]
-        if r["done"] or (max_steps is not None and steps >= max_steps):
+        modes.append(r["mode_run"])
+        if len(modes) > first_untimed:
+            toks += r["n_unmasked"]
+        if r["done"] or (max_steps is not None and len(modes) >= max_steps):
             break
     torch.cuda.synchronize()
-    return steps, full, toks, time.perf_counter() - t0
+    return modes, toks, time.perf_counter() - (t0 if t0 is not None else time.perf_counter())
 
 
 def calibrate_logit_scale(make_ctx, prompt, target_lo=0.08, target_hi=0.16):
@@ -82,10 +97,10 @@ def calibrate_logit_scale(make_ctx, prompt, target_lo=0.08, target_hi=0.16):
     for it in range(12):
         mid = (lo * hi) ** 0.5
         g = make_ctx(mid)
-        steps, full, _, _ = run_generation(g, prompt)
+        modes, _, _ = run_generation(g, prompt)
         g.close()
-        f = full / steps
-        log(f"[calibrate] logit_scale={mid:.3f}: FULL fraction {f:.3f} ({full}/{steps})")
+        f = modes.count(0) / len(modes)
+        log(f"[calibrate] logit_scale={mid:.3f}: FULL fraction {f:.3f} ({modes.count(0)}/{len(modes)})")
         if best is None or abs(f - 0.11) < abs(best[1] - 0.11):
             best = (mid, f)
         if target_lo <= f <= target_hi:
@@ -97,95 +112,95 @@ def calibrate_logit_scale(make_ctx, prompt, target_lo=0.08, target_hi=0.16):
     return best
 
 
-def bench_batch(args, wl, cfg, dec, dw):
-    """Many sequences side by side (decode.batch > 1), every prompt prompt_len ids long (their
-    modes still differ from step to step).
-    Timed: K free-running steps of the whole batch; then the all-PARTIAL steady state and the
-    all-FULL step, forced.  One JSON line like the single-sequence run's, without the CPU leg."""
-    import torch
-    import ec_inputs
-    import paper_2603_18489_amd as ec
-    B = dec.batch
-    plens = [wl.prompt_len] * B
-    prompts = [ec_inputs.make_prompt(cfg.vocab, P, wl.seed + 1000 + b) for b, P in enumerate(plens)]
-    scale = args.logit_scale if args.logit_scale > 0 else 8.0
-    g = ec.EntropyCache(cfg.replace(logit_scale=scale), dw, dec, prompts)
+def pick_window(modes, k):
+    """First step of the k-step window of a generation whose share of FULL steps is closest to the
+    whole generation's (earliest on ties).  k >= the generation's length: the whole generation."""
+    n = len(modes)
+    if k >= n:
+        return 0
+    full = [1 if m == 0 else 0 for m in modes]
+    target = sum(full) / n * k
+    best, best_d = 0, None
+    cur = sum(full[:k])
+    for s in range(0, n - k + 1):
+        if s > 0:
+            cur += full[s + k - 1] - full[s - 1]
+        d = abs(cur - target)
+        if best_d is None or d < best_d - 1e-12:
+            best, best_d = s, d
+    return best
 
-    def steps_timed(mode_fn, n, reset=True):
-        if reset:
-            g.reset(prompts)
+
+def step_times_forced(g, prompts, B, n_partial=24, n_full=3):
+    """Whole-step wall times under forced schedules: (ms per FULL step, ms per PARTIAL step in the
+    steady state that follows a FULL step)."""
+    import torch
+    import paper_2603_18489_amd as ec
+
+    def run(mode_fn, n):
+        g.reset(prompts)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        toks = full = part = 0
         for i in range(n):
-            rs = g.step(mode_fn(i))
-            for r in rs:
-                if r["n_query_rows"] > 0:
-                    toks += r["n_unmasked"]
-                    full += int(r["mode_run"] == ec.EC_FULL)
-                    part += int(r["mode_run"] == ec.EC_PARTIAL)
-            if all(r["done"] for r in rs):
-                break
+            g.step(mode_fn(i))
         torch.cuda.synchronize()
-        return i + 1, toks, full, part, time.perf_counter() - t0
+        return time.perf_counter() - t0
 
-    steps_timed(lambda i: ec.EC_AUTO, args.warmup)
-    steps, toks, full, part, secs = steps_timed(lambda i: ec.EC_AUTO, args.steps)
-    _, _, _, _, t_f = steps_timed(lambda i: ec.EC_FULL, 3)
-    n_p, tok_p, _, _, t_p = steps_timed(lambda i: ec.EC_FULL if i == 0 else ec.EC_PARTIAL, 25)
-    full_ms = t_f / 3 * 1e3
-    partial_ms = (t_p - full_ms / 1e3) / (n_p - 1) * 1e3
-    g.reset(prompts)
-    g.step(ec.EC_FULL)
-    g.profile_enable(True)
-    for _ in range(8):
-        g.step(ec.EC_PARTIAL)
-    prof = g.profile_read()
-    g.profile_enable(False)
-    pp = {k: v / prof["steps"] for k, v in prof["ms"].items()}
-    R = sum((34 + 15) // 16 * 16 for _ in range(B))             # rows of the partial step's list
-    gu_ms = pp["gateup"] / cfg.n_layers
-    gu_flops = 2.0 * R * cfg.d_model * 2 * cfg.d_ffn
-    ach = gu_flops / (gu_ms * 1e-3) / 1e12
-    T_tot = sum(P + dec.gen_len for P in plens)
-    kv_bytes = 2.0 * T_tot * cfg.n_kv_heads * cfg.head_dim * 2 * cfg.n_layers
-    step_bytes = ec_inputs.weight_bytes(cfg) + kv_bytes          # weights once + every cache once
-    g.close()
-    out = {
-        "metric": "generated tokens per second, EntropyCache denoising, 16 sequences (LLaDA-8B shape)",
-        "value": toks / secs, "unit": "tok/s", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
-        "ms_per_step": secs / steps * 1e3, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": f"{wl.name}: L{cfg.n_layers} d{cfg.d_model} {cfg.n_heads}q/"
-                               f"{cfg.n_kv_heads}kv x{cfg.head_dim} F{cfg.d_ffn} V{cfg.vocab}, "
-                               f"{B} sequences, prompt {plens[0]} each, gen {dec.gen_len}, "
-                               f"block {dec.block}, n={dec.tokens_per_step}, k={dec.k_recent}, "
-                               f"tau={dec.tau}",
-                   "schedule": "free-running EC_AUTO", "logit_scale": scale,
-                   "sequence_steps_full": full, "sequence_steps_partial": part},
-        "all_partial_step": {"ms": partial_ms, "tok_per_s": B * dec.tokens_per_step / partial_ms * 1e3,
-                             "list_rows": R, "algorithmic_GB": step_bytes / 1e9,
-                             "hbm_frac": step_bytes / (partial_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
-        "all_full_step": {"ms": full_ms, "rows": T_tot,
-                          "tflops": sum(full_step_flops(cfg, P + dec.gen_len, dec.block)
-                                        for P in plens) / (full_ms * 1e-3) / 1e12},
-        "kernel_ms_partial_step": pp,
-        "roofline": {"kernel": "tiled GEMM (gate/up projection, all-partial step of the batch)",
-                     "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
-                     "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
-                     "launch_ms": gu_ms, "flops_per_launch": gu_flops},
-        "cpu_baseline": None,
-    }
-    print(json.dumps(out))
+    run(lambda i: ec.EC_FULL, 1)                                      # warm-up
+    full_ms = run(lambda i: ec.EC_FULL, n_full) / n_full * 1e3
+    t = run(lambda i: ec.EC_FULL if i == 0 else ec.EC_PARTIAL, n_partial + 1) * 1e3
+    return full_ms, (t - full_ms) / n_partial
+
+
+def measure_other_workload(name, dw_by_model, threads):
+    """Forced-schedule step times of another workload of the configuration list, at logit scale 8
+    (uncalibrated: the schedule is forced, so the scale changes nothing measured here)."""
+    import ec_inputs
+    import paper_2603_18489_amd as ec
+    wl = ec_inputs.WORKLOADS[name]
+    cfg, dec = wl.model.replace(logit_scale=8.0), wl.decode
+    key = (cfg.n_layers, cfg.d_model, cfg.vocab, wl.seed)
+    if key not in dw_by_model:
+        t0 = time.perf_counter()
+        dw_by_model[key] = ec.weights_to_device(cfg, ec_inputs.make_weights(cfg, wl.seed, threads=threads))
+        log(f"[bench] {name}: weights generated and uploaded in {time.perf_counter() - t0:.1f}s")
+    B = dec.batch
+    if B == 1:
+        prompts = ec_inputs.make_prompt(cfg.vocab, wl.prompt_len, wl.seed)
+    else:
+        prompts = [ec_inputs.make_prompt(cfg.vocab, wl.prompt_len, wl.seed + 1000 + b) for b in range(B)]
+    g = ec.EntropyCache(cfg, dw_by_model[key], dec, prompts)
+    try:
+        full_ms, partial_ms = step_times_forced(g, prompts, B, n_partial=24, n_full=2 if B > 1 else 3)
+    finally:
+        g.close()
+    T = wl.prompt_len + dec.gen_len
+    rows = dec.block + dec.k_recent * max(1, dec.tokens_per_step)     # most rows of a partial step
+    step_bytes = ec_inputs.weight_bytes(cfg) + B * (algorithmic_bytes(cfg, T, rows) - ec_inputs.weight_bytes(cfg))
+    flops = B * full_step_flops(cfg, T, dec.block)
+    out = {"workload": f"{name}: L{cfg.n_layers} d{cfg.d_model} {cfg.n_heads}q/{cfg.n_kv_heads}kv "
+                       f"F{cfg.d_ffn} V{cfg.vocab}, {B} x (prompt {wl.prompt_len} + gen {dec.gen_len}), "
+                       f"n={dec.tokens_per_step}, k={dec.k_recent}, tau={dec.tau}",
+           "partial_step": {"ms": partial_ms, "algorithmic_GB": step_bytes / 1e9,
+                            "hbm_frac": step_bytes / (partial_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                            "tok_per_s": B * dec.tokens_per_step / partial_ms * 1e3},
+           "full_step": {"ms": full_ms, "flops": flops,
+                         "mfma_frac": flops / (full_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}}
+    if B > 1:
+        # the all-partial step of a batch sits at the ridge: its GEMMs run B x 34 rows
+        pflops = 2.0 * B * rows * (ec_inputs.weight_bytes(cfg) / 2)
+        out["partial_step"]["mfma_frac"] = pflops / (partial_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS
+    log(f"[bench] {name}: partial {partial_ms:.2f} ms, full {full_ms:.2f} ms")
+    return out
 
 
 def cpu_oracle_baseline(cfg, w, dec, prompt, n_full, n_partial, n_tok):
-    """Times the fp64 oracle on 2- and 4-layer prefixes of the model (one FULL and one PARTIAL
-    step each) and extrapolates linearly in depth to the full model and the same mode schedule."""
-    import numpy as np
+    """Times the fp64 numpy oracle (oracle/entropycache.py, BLAS matmul as its contraction
+    primitive) on 1- and 2-layer prefixes of the model (one FULL and one PARTIAL step each) and
+    extrapolates linearly in depth to the full model and the GPU run's mode schedule."""
     from oracle import entropycache as eco
     times = {}
-    for L in (2, 4):
+    for L in (1, 2):
         sub = {k: (v[:L] if isinstance(v, list) else v) for k, v in w.items()}
         st = eco.eco_init(eco.OracleModel(cfg.replace(n_layers=L), sub), dec, prompt)
         t0 = time.perf_counter()
@@ -196,13 +211,13 @@ def cpu_oracle_baseline(cfg, w, dec, prompt, n_full, n_partial, n_tok):
         tp = time.perf_counter() - t0
         times[L] = (tf, tp)
         log(f"[cpu oracle] L={L}: FULL {tf:.2f}s PARTIAL {tp:.2f}s")
-    per_f = (times[4][0] - times[2][0]) / 2
-    per_p = (times[4][1] - times[2][1]) / 2
-    tf = times[2][0] + (cfg.n_layers - 2) * per_f
-    tp = times[2][1] + (cfg.n_layers - 2) * per_p
+    per_f = times[2][0] - times[1][0]
+    per_p = times[2][1] - times[1][1]
+    tf = times[1][0] + (cfg.n_layers - 1) * per_f
+    tp = times[1][1] + (cfg.n_layers - 1) * per_p
     total = n_full * tf + n_partial * tp
     return {"value": n_tok / total, "unit": "tok/s", "cores": os.cpu_count(), "kind": "oracle",
-            "sample": f"1 FULL + 1 PARTIAL fp64 step on 2- and 4-layer prefixes of the model "
+            "sample": f"1 FULL + 1 PARTIAL fp64 step on 1- and 2-layer prefixes of the model "
                       f"(same widths, vocabulary, prompt), extrapolated linearly to "
                       f"{cfg.n_layers} layers and the GPU run's schedule of {n_full} FULL + "
                       f"{n_partial} PARTIAL steps",
@@ -217,6 +232,7 @@ def main():
     ap.add_argument("--workload", default="llada8b")
     ap.add_argument("--logit-scale", type=float, default=0.0, help="skip calibration")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true")
     ap.add_argument("--threads", type=int, default=16)
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="run one plain device copy of this size first (a known-size dispatch "
@@ -227,7 +243,6 @@ def main():
             "run with --gpus 1")
         sys.exit(2)
 
-    import numpy as np
     import torch
     import ec_inputs
     import paper_2603_18489_amd as ec
@@ -235,6 +250,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     wl = ec_inputs.WORKLOADS[args.workload]
     cfg, dec = wl.model, wl.decode
+    assert dec.batch == 1, "the headline run is a single sequence; batches are measured as other workloads"
     T = wl.prompt_len + dec.gen_len
     t0 = time.perf_counter()
     w = ec_inputs.make_weights(cfg, wl.seed, threads=args.threads)
@@ -244,10 +260,7 @@ def main():
     dw = ec.weights_to_device(cfg, w)
     torch.cuda.synchronize()
     log(f"[bench] weights uploaded in {time.perf_counter() - t0:.1f}s")
-
-    if dec.batch > 1:
-        del w
-        return bench_batch(args, wl, cfg, dec, dw)
+    dw_by_model = {(cfg.n_layers, cfg.d_model, cfg.vocab, wl.seed): dw}
 
     if args.calib_copy_mb > 0:
         src = torch.ones(args.calib_copy_mb << 18, dtype=torch.float32, device="cuda")
@@ -260,32 +273,39 @@ def main():
         return ec.EntropyCache(cfg.replace(logit_scale=scale), dw, dec, prompt)
 
     if args.logit_scale > 0:
-        scale, f_cal = args.logit_scale, None
+        scale = args.logit_scale
     else:
-        scale, f_cal = calibrate_logit_scale(make_ctx, prompt)
+        scale, _ = calibrate_logit_scale(make_ctx, prompt)
     g = make_ctx(scale)
 
-    # ---- timed region: exactly K free-running steps (generations restart untimed) -------------
-    def run_k_steps(k):
-        done_steps = full = toks = 0
-        secs = 0.0
-        while done_steps < k:
-            s, f, tk, dt = run_generation(g, prompt, max_steps=k - done_steps)
-            done_steps += s; full += f; toks += tk; secs += dt
-        return done_steps, full, toks, secs
+    # ---- one complete generation: its modes (deterministic) and its time ------------------------
+    run_generation(g, prompt)                                           # warm-up
+    gen_modes, gen_toks, gen_secs = run_generation(g, prompt)
+    gen_steps, gen_full = len(gen_modes), gen_modes.count(ec.EC_FULL)
+    whole = {"steps": gen_steps, "full_steps": gen_full, "full_fraction": gen_full / gen_steps,
+             "ms_per_step": gen_secs / gen_steps * 1e3, "tok_s": gen_toks / gen_secs,
+             "tokens": gen_toks}
 
-    run_k_steps(args.warmup)
-    steps, full, toks, secs = run_k_steps(args.steps)
+    # ---- timed region: exactly K consecutive free-running steps ---------------------------------
+    K = args.steps
+    s0 = pick_window(gen_modes, K)
+    run_generation(g, prompt, max_steps=max(1, args.warmup))            # W untimed warm-up steps
+    steps = full = toks = 0
+    secs = 0.0
+    while steps < K:                                                    # (K beyond one generation: restart)
+        first = s0 if steps == 0 else 0
+        modes, tk, dt = run_generation(g, prompt, max_steps=first + (K - steps), first_untimed=first)
+        timed = modes[first:]
+        steps += len(timed); full += timed.count(ec.EC_FULL); toks += tk; secs += dt
     partial = steps - full
 
     # ---- per-mode step rates (forced schedules) ------------------------------------------------
     n_probe = min(64, dec.gen_len)
-    s_p, f_p, _, t_p = run_generation(g, prompt, mode_fn=lambda i: ec.EC_FULL if i == 0 else ec.EC_PARTIAL,
-                                      max_steps=n_probe)
-    # first step is FULL: time it separately below and subtract
-    s_f, _, _, t_f = run_generation(g, prompt, mode_fn=lambda i: ec.EC_FULL, max_steps=8)
-    full_ms = t_f / s_f * 1e3
-    partial_ms = (t_p - full_ms / 1e3) / (s_p - 1) * 1e3
+    m_p, _, t_p = run_generation(g, prompt, mode_fn=lambda i: ec.EC_FULL if i == 0 else ec.EC_PARTIAL,
+                                 max_steps=n_probe)
+    m_f, _, t_f = run_generation(g, prompt, mode_fn=lambda i: ec.EC_FULL, max_steps=8)
+    full_ms = t_f / len(m_f) * 1e3
+    partial_ms = (t_p * 1e3 - full_ms) / (len(m_p) - 1)
 
     # ---- kernel-level timing with HIP events on the library's stream ---------------------------
     g.profile_enable(True)
@@ -305,29 +325,42 @@ def main():
     roofline = {"kernel": "gemm_bf16_skinny (gate/up projection, partial step)", "bound": "hbm",
                 "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                "launch_ms": gu_launch_ms, "bytes_per_launch": gu_bytes}
+                "launch_ms": gu_launch_ms, "bytes_per_launch": gu_bytes,
+                "timing": "HIP events around each launch on the library's stream (about 1.5 us "
+                          "above the rocprofv3 kernel-trace duration of profiles/)"}
     gu_full_ms = pf["gateup"] / cfg.n_layers
     gu_flops = 2.0 * T * cfg.d_model * 2 * cfg.d_ffn
     ach_f = gu_flops / (gu_full_ms * 1e-3) / 1e12
     roofline_full = {"kernel": "gemm_bf16_tiled8 (gate/up projection, full step)", "bound": "mfma",
                      "achieved": ach_f, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": ach_f / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
-                     "launch_ms": gu_full_ms, "flops_per_launch": gu_flops}
+                     "launch_ms": gu_full_ms, "flops_per_launch": gu_flops,
+                     "timing": roofline["timing"]}
     # HBM bytes per launch measured with rocprofv3 --pmc (committed summary of the same command)
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic_llada8b.json")
     if args.workload == "llada8b" and os.path.exists(tpath):
         tj = json.load(open(tpath))
         for rf, key in ((roofline, "partial_gateup"), (roofline_full, "full_gateup")):
             rf["traffic"] = tj[key]["fetch_bytes"] + (tj[key]["write_bytes"] or 0.0)
-            rf["traffic_source"] = "profiles/gemm_kernels_llada8b_hbm_traffic.txt"
-    step_bytes = algorithmic_bytes(cfg, T, rows_partial, dec.block)
+            rf["traffic_source"] = "committed rocprofv3 --pmc summary profiles/gemm_kernels_llada8b_hbm_traffic.txt"
+    step_bytes = algorithmic_bytes(cfg, T, rows_partial)
     step_flops = full_step_flops(cfg, T, dec.block)
     decision_ms = pp["vocab_reduce"] + pp["decide"]
+    g.close()
+
+    others = None
+    if not args.no_other_workloads and args.workload == "llada8b":
+        others = {}
+        for name in ("llada8b_cot", "llada8b_b16", "dream7b"):
+            try:
+                others[name] = measure_other_workload(name, dw_by_model, args.threads)
+            except Exception as e:  # keep the headline line even if a side measurement fails
+                others[name] = {"error": repr(e)}
+        dw_by_model.clear()
 
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_oracle_baseline(cfg, w, dec, prompt, full, partial, toks)
-    g.close()
 
     out = {
         "metric": "generated tokens per second, EntropyCache denoising (LLaDA-8B shape)",
@@ -341,21 +374,27 @@ def main():
                                f"tau={dec.tau}"
                                + (f", confidence threshold {dec.conf_threshold}" if dec.conf_threshold else "")
                                + (", sliding window" if dec.schedule else ""),
-                   "schedule": "free-running EC_AUTO, calibrated logit scale",
-                   "logit_scale": scale, "full_fraction": full / steps,
-                   "full_steps": full, "partial_steps": partial},
+                   "schedule": f"free-running EC_AUTO, calibrated logit scale; the timed window is "
+                               f"steps {s0 + 1}..{s0 + min(K, gen_steps)} of the generation, chosen so "
+                               f"that its share of FULL steps matches the whole generation's",
+                   "logit_scale": scale, "window_first_step": s0 + 1,
+                   "full_fraction": full / steps, "full_steps": full, "partial_steps": partial},
         "steps_per_s": steps / secs,
+        "whole_generation": whole,
         "partial_step": {"ms": partial_ms, "steps_per_s": 1e3 / partial_ms,
                          "algorithmic_GB": step_bytes / 1e9,
                          "hbm_GBs": step_bytes / (partial_ms * 1e-3) / 1e9,
                          "hbm_frac": step_bytes / (partial_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                          "decision_ms": decision_ms,
-                         "decision_pct": 100.0 * decision_ms / sum(pp.values())},
+                         "decision_pct": 100.0 * decision_ms / sum(pp.values()),
+                         "decision_note": "decide kernel alone: the vocabulary reduction runs inside "
+                                          "the LM-head epilogue"},
         "full_step": {"ms": full_ms, "steps_per_s": 1e3 / full_ms, "flops": step_flops,
                       "tflops": step_flops / (full_ms * 1e-3) / 1e12,
                       "mfma_frac": step_flops / (full_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
         "kernel_ms_partial_step": pp, "kernel_ms_full_step": pf,
         "roofline": roofline, "roofline_full_step": roofline_full,
+        "other_workloads": others,
         "cpu_baseline": cpu,
         "paper_context": "paper reports 15.2x-26.4x speedup over vanilla on RTX 3090 (trained "
                          "weights, other decoding settings): context, not a target",

@@ -139,24 +139,51 @@ __global__ __launch_bounds__(kDecideThreads) void decide_kernel(DecideArgs a) {
 
   if (!a.init_only) {
     // ---- merge the vocabulary partials of each block row (fixed order) ----------------------
-    // One wave per row at a time: lane l merges parts l, l + 64, ... in that order (four loads
-    // in flight), then the lanes' tuples are merged pairwise down to lane 0.
-    for (int row = wave; row < a.n_mb; row += kDecideWaves) {
-      const float4* pr = a.partials + (size_t)row * a.nparts;
+    // Half a wave per row, 32 rows at a time: lane l of the half merges parts l, l + 32, ... in
+    // that order (sixteen loads in flight), then the 32 tuples are merged pairwise down to the
+    // half's first lane.
+    for (int row0 = 0; row0 < a.n_mb; row0 += 2 * kDecideWaves) {
+      const int row = row0 + wave * 2 + (lane >> 5), l32 = lane & 31;
+      const bool live = row < a.n_mb;
+      const float4* pr = a.partials + (size_t)(live ? row : 0) * a.nparts;
+      // The lane's running tuple is re-based once per batch of 16 parts (to the batch's maximum
+      // if that is larger), after which a part costs one fast exponential and a few FMAs: the
+      // block has tens of thousands of parts to fold on a single compute unit.
       VTuple v = vt_identity();
-      for (int p0 = lane; p0 < a.nparts; p0 += 256) {
-        float4 q[4];
+      for (int p0 = l32; p0 < a.nparts; p0 += 32 * 16) {
+        float4 q[16];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int p = p0 + 64 * u;
-          q[u] = p < a.nparts ? pr[p] : vt_pack(vt_identity());
+        for (int u = 0; u < 16; ++u)   // unconditional loads (clamped), so that all are in flight
+          q[u] = pr[min(p0 + 32 * u, a.nparts - 1)];
+        bool ok[16];
+        float bm = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+          ok[u] = live && p0 + 32 * u < a.nparts && q[u].z != 0.f;   // (an empty part has S = 0)
+          bm = fmaxf(bm, ok[u] ? q[u].x : -INFINITY);
+        }
+        if (bm > v.m) {
+          if (v.s != 0.f) {
+            const float d = v.m - bm, e = __expf(d);
+            v.t = e * (v.t + d * v.s);
+            v.s *= e;
+          }
+          v.m = bm;
+          v.idx = INT_MAX;
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v = vt_merge(v, vt_unpack(q[u]));
+        for (int u = 0; u < 16; ++u) {
+          const float d = ok[u] ? q[u].x - v.m : 0.f;            // <= 0
+          const float e = ok[u] ? __expf(d) : 0.f;
+          v.s += q[u].z * e;
+          v.t += e * (q[u].w + d * q[u].z);
+          const int pi = __float_as_int(q[u].y);
+          if (ok[u] && d == 0.f && pi < v.idx) v.idx = pi;       // lowest index among equal maxima
+        }
       }
 #pragma unroll
-      for (int o = 32; o > 0; o >>= 1) v = vt_merge(v, vt_shfl_down(v, o));
-      if (lane == 0) {
+      for (int o = 16; o > 0; o >>= 1) v = vt_merge(v, vt_shfl_down(v, o));
+      if (live && l32 == 0) {
         float conf, H;
         vt_finish(v, conf, H);
         s_tok[row] = v.idx;

@@ -352,26 +352,42 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* 
 
   static_assert(EPI != EPI_PARTIAL, "K-split partial products are a tiled-kernel epilogue");
   if constexpr (EPI == EPI_LOGITS) {
-    // Logits of the block's NTW*16 columns, and their reduction: every lane folds its 4 columns
-    // into a tuple, the 4 lanes of a row (16 apart) merge theirs, and after a barrier one
-    // thread per row merges the NTW tiles in tile order and stores the block's tuple.
+    // Logits of the block's NTW*16 columns, and their reduction.  A row's 16 columns of one tile
+    // sit in the 4 lanes l, l^16, l^32, l^48 (4 columns each): maximum and lowest index holding
+    // it through two lane swaps, then sum e^(z-max) and sum e^(z-max)(z-max) relative to that
+    // maximum (added pairwise, the same pairs in all four lanes, so they agree bit for bit);
+    // after a barrier one thread per row merges the NTW tiles in tile order and stores the
+    // block's tuple.
     float4* tup = (float4*)(rstd_s + MT * 16);  // [NTW][MT*16]
     for (int o = threadIdx.x; o < UNITS; o += KS * 64) {  // UNITS is a multiple of the block size
       const int l = o & 63, unit = o >> 6, iu = unit / MT, j = unit - iu * MT;
       const int m = j * 16 + (l & 15), q4 = l >> 4, vt = nt0 + iu;
       const f32x4 v = ksum((iu * MT + j) * 64 + l);
-      VTuple t = vt_identity();
-      if (m < e.M && vt < total_nt) {
-        const float sc = rstd_s[m] * e.scale;
-        const float z[4] = {v[0] * sc, v[1] * sc, v[2] * sc, v[3] * sc};
-        const int n = vt * 16 + q4 * 4;
-        if (e.logits) *(float4*)(e.logits + (size_t)m * e.ldc + n) = make_float4(z[0], z[1], z[2], z[3]);
+      // (rows past M recompute row 0 and tiles past the end tile 0: finite values, dropped below)
+      const float sc = rstd_s[m] * e.scale;
+      const float z[4] = {v[0] * sc, v[1] * sc, v[2] * sc, v[3] * sc};
+      const int n = vt * 16 + q4 * 4;
+      const bool live = m < e.M && vt < total_nt;
+      if (live && e.logits)
+        *(float4*)(e.logits + (size_t)m * e.ldc + n) = make_float4(z[0], z[1], z[2], z[3]);
+      float mx = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
+      mx = fmaxf(mx, other_row(mx));
+      mx = fmaxf(mx, other_half(mx));
+      int idx = z[0] == mx ? n : z[1] == mx ? n + 1 : z[2] == mx ? n + 2 : z[3] == mx ? n + 3 : INT_MAX;
+      idx = min(idx, __float_as_int(other_row(__int_as_float(idx))));
+      idx = min(idx, __float_as_int(other_half(__int_as_float(idx))));
+      float s4 = 0.f, t4 = 0.f;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) vt_push(t, z[r], n + r);
+      for (int r = 0; r < 4; ++r) {
+        const float d = z[r] - mx, ex = __expf(d);
+        s4 += ex;
+        t4 += ex * d;
       }
-      t = vt_merge(t, vt_shfl_down(t, 32));   // lanes 0-31 <- 32-63
-      t = vt_merge(t, vt_shfl_down(t, 16));   // lanes 0-15 <- 16-31: the row's 16 columns
-      if (q4 == 0) tup[iu * (MT * 16) + m] = vt_pack(t);
+      s4 += other_row(s4); t4 += other_row(t4);
+      s4 += other_half(s4); t4 += other_half(t4);
+      if (q4 == 0)
+        tup[iu * (MT * 16) + m] = vt < total_nt ? make_float4(mx, __int_as_float(idx), s4, t4)
+                                                : vt_pack(vt_identity());
     }
     __syncthreads();
     if (threadIdx.x < MT * 16 && (int)threadIdx.x < e.M) {
