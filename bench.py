@@ -15,8 +15,8 @@ before it run untimed.  A complete generation is timed beside it (`whole_generat
 
 Prints ONE JSON line: whole-job generated tokens/s, per-mode step rates, the roofline of the
 dominant kernel (HIP events recorded on the library's stream), the same step measurements for
-the other workloads (Dream-7B shape, long chain-of-thought shape, 16 sequences), and the CPU
-oracle timed on a bounded sample of the same workload.
+the other workloads (Dream-7B shape, long chain-of-thought shape, 16 sequences, and the LLaDA-8B
+shape with e4m3-coded matrices), and the CPU oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
@@ -42,7 +42,7 @@ def algorithmic_bytes(cfg, T, rows):
     """HBM bytes one PARTIAL step of one sequence must move: every matrix once, the KV cache read
     once per layer, the new K/V rows written.  Activations are left out (< 0.1 %)."""
     import ec_inputs
-    es = 2 if cfg.dtype == "bf16" else 4
+    es = 4 if cfg.dtype == "f32" else 2
     kv = cfg.n_layers * 2 * T * cfg.n_kv_heads * cfg.head_dim * es
     kv_w = cfg.n_layers * 2 * rows * cfg.n_kv_heads * cfg.head_dim * es
     return ec_inputs.weight_bytes(cfg) + kv + kv_w
@@ -60,8 +60,9 @@ def full_step_flops(cfg, T, n_mb):
 def gateup_bytes(cfg, rows):
     """Algorithmic bytes of one gate/up launch: both matrices once, the rows' operand in, the
     rows' SwiGLU output out (bf16)."""
-    es = 2 if cfg.dtype == "bf16" else 4
-    return 2 * cfg.d_ffn * cfg.d_model * es + rows * cfg.d_model * es + rows * cfg.d_ffn * es
+    es = 4 if cfg.dtype == "f32" else 2
+    ws = {"f32": 4, "bf16": 2, "fp8w": 1}[cfg.dtype]
+    return 2 * cfg.d_ffn * cfg.d_model * ws + rows * cfg.d_model * es + rows * cfg.d_ffn * es
 
 
 def run_generation(g, prompt, mode_fn=None, max_steps=None, first_untimed=0):
@@ -159,7 +160,7 @@ def measure_other_workload(name, dw_by_model, threads):
     import paper_2603_18489_amd as ec
     wl = ec_inputs.WORKLOADS[name]
     cfg, dec = wl.model.replace(logit_scale=8.0), wl.decode
-    key = (cfg.n_layers, cfg.d_model, cfg.vocab, wl.seed)
+    key = (cfg.n_layers, cfg.d_model, cfg.vocab, wl.seed, cfg.dtype)
     if key not in dw_by_model:
         t0 = time.perf_counter()
         dw_by_model[key] = ec.weights_to_device(cfg, ec_inputs.make_weights(cfg, wl.seed, threads=threads))
@@ -260,7 +261,7 @@ def main():
     dw = ec.weights_to_device(cfg, w)
     torch.cuda.synchronize()
     log(f"[bench] weights uploaded in {time.perf_counter() - t0:.1f}s")
-    dw_by_model = {(cfg.n_layers, cfg.d_model, cfg.vocab, wl.seed): dw}
+    dw_by_model = {(cfg.n_layers, cfg.d_model, cfg.vocab, wl.seed, cfg.dtype): dw}
 
     if args.calib_copy_mb > 0:
         src = torch.ones(args.calib_copy_mb << 18, dtype=torch.float32, device="cuda")
@@ -351,7 +352,7 @@ def main():
     others = None
     if not args.no_other_workloads and args.workload == "llada8b":
         others = {}
-        for name in ("llada8b_cot", "llada8b_b16", "dream7b"):
+        for name in ("llada8b_cot", "llada8b_b16", "dream7b", "llada8b_fp8"):
             try:
                 others[name] = measure_other_workload(name, dw_by_model, args.threads)
             except Exception as e:  # keep the headline line even if a side measurement fails

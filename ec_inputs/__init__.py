@@ -35,7 +35,10 @@ class ModelCfg:
     rms_eps: float = 1e-5
     rope_base: float = 10000.0
     logit_scale: float = 1.0
-    dtype: str = "f32"  # "f32" | "bf16": storage type of weights (and of the GPU's KV cache)
+    # storage type of the weights: "f32", "bf16", or "fp8w" = matrices as 8-bit e4m3 codes with one
+    # float32 scale per output row (QuantMatrix), everything else (embedding, norm gains) bfloat16.
+    # The GPU's activations and KV cache are float32 for "f32" and bfloat16 otherwise.
+    dtype: str = "f32"
 
     def replace(self, **kw) -> "ModelCfg":
         return dataclasses.replace(self, **kw)
@@ -107,6 +110,14 @@ WORKLOADS: Dict[str, Workload] = {
     "llada8b_b16": Workload("llada8b_b16", _llada(),
                             DecodeCfg(gen_len=512, block=32, k_recent=2, tokens_per_step=1,
                                       tau=1.0, batch=16), 1024, 2),
+    # the LLaDA-8B shape with its matrices stored as e4m3 codes + per-row scales: half the bytes
+    # to stream per partial step (beyond the paper: its method is orthogonal to the weight format)
+    "llada8b_fp8": Workload("llada8b_fp8", _llada(dtype="fp8w"),
+                            DecodeCfg(gen_len=256, block=32, k_recent=2, tokens_per_step=1, tau=1.0),
+                            512, 2),
+    "llada8b_fp8_l2": Workload("llada8b_fp8_l2", _llada(dtype="fp8w", n_layers=2),
+                               DecodeCfg(gen_len=256, block=32, k_recent=2, tokens_per_step=1,
+                                         tau=1.0), 512, 2),
     # reduced-depth twins (same widths and vocabulary, 2 layers) for whole-generation parity
     "llada8b_l2": Workload("llada8b_l2", _llada(n_layers=2),
                            DecodeCfg(gen_len=256, block=32, k_recent=2, tokens_per_step=1,
@@ -125,6 +136,48 @@ def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
     u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
     bias = ((u >> 16) & 1) + np.uint32(0x7FFF)
     return ((u + bias) >> 16).astype(np.uint16)
+
+
+def f32_to_e4m3_bits(x: np.ndarray) -> np.ndarray:
+    """float32 -> 8-bit e4m3 code (1 sign, 4 exponent bits with bias 7, 3 mantissa bits, no
+    infinities, S.1111.111 = NaN), round to nearest with ties to even, saturating at +-448."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    u = x.view(np.uint32)
+    sign = ((u >> np.uint32(24)) & np.uint32(0x80)).astype(np.uint8)
+    a = u & np.uint32(0x7FFFFFFF)
+    # normal range (|x| >= 2^-6): round the float32 mantissa to 3 bits, ties to even
+    r = a + np.uint32(0x7FFFF) + ((a >> np.uint32(20)) & np.uint32(1))
+    e = (r >> np.uint32(23)).astype(np.int32) - 127 + 7
+    m = ((r >> np.uint32(20)) & np.uint32(7)).astype(np.int32)
+    code = (e << 3) | m
+    # below the smallest normal the grid is uniform with step 2^-9 (8 steps reach 2^-6 = code 8)
+    sub = np.rint(np.minimum(np.abs(x), np.float32(1.0)) * np.float32(512.0)).astype(np.int32)
+    code = np.where(np.abs(x) < np.float32(2.0 ** -6), sub, code)
+    code = np.minimum(code, 0x7E)                       # saturate (also infinities)
+    return (code.astype(np.uint8) | sign)
+
+
+class QuantMatrix:
+    """A matrix stored as e4m3 codes [out, in] with one float32 scale per output row: its value
+    is scale[row] * e4m3(codes[row, col])."""
+    __slots__ = ("codes", "scale")
+
+    def __init__(self, codes: np.ndarray, scale: np.ndarray):
+        self.codes, self.scale = codes, scale
+
+    ndim = 2
+
+    @property
+    def shape(self):
+        return self.codes.shape
+
+
+def quantize_rows_e4m3(w: np.ndarray) -> QuantMatrix:
+    """Per-row scale = max |w| / 448 (the largest e4m3 magnitude), codes = e4m3(w / scale)."""
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    amax = np.abs(w).max(axis=1)
+    scale = np.where(amax > 0, amax / np.float32(448.0), np.float32(1.0)).astype(np.float32)
+    return QuantMatrix(f32_to_e4m3_bits(w / scale[:, None]), scale)
 
 
 # ----------------------------------------------------------------------------------------------
@@ -183,12 +236,21 @@ def make_weights(cfg: ModelCfg, seed: int, std: float = 0.02, gain_jitter: float
     """
     d, hq, hkv, hd, f, v = (cfg.d_model, cfg.n_heads, cfg.n_kv_heads, cfg.head_dim, cfg.d_ffn,
                             cfg.vocab)
-    dt = cfg.dtype
+    quant = cfg.dtype == "fp8w"
+    dt = "bf16" if quant else cfg.dtype
     w: Dict[str, object] = {}
     with ThreadPoolExecutor(max_workers=max(1, threads)) as pool:
         def nt(name, shape):
-            return normal_tensor(seed, name, shape, std, dt, pool)
-        w["tok_emb"] = nt("tok_emb", (v, d))
+            if not quant:
+                return normal_tensor(seed, name, shape, std, dt, pool)
+            # the same float32 draws, then e4m3 codes with per-row scales (row blocks in parallel)
+            x = normal_tensor(seed, name, shape, std, "f32", pool)
+            step = max(1, (1 << 22) // shape[1])
+            parts = list(pool.map(lambda lo: quantize_rows_e4m3(x[lo:lo + step]),
+                                  range(0, shape[0], step)))
+            return QuantMatrix(np.concatenate([p.codes for p in parts]),
+                               np.concatenate([p.scale for p in parts]))
+        w["tok_emb"] = normal_tensor(seed, "tok_emb", (v, d), std, dt, pool)
         w["lm_head"] = nt("lm_head", (v, d))
         w["final_norm"] = _gain(seed, "final_norm", d, gain_jitter, dt)
         per_layer: Dict[str, List[np.ndarray]] = {k: [] for k in (
@@ -218,5 +280,5 @@ def weight_bytes(cfg: ModelCfg) -> int:
     d, hq, hkv, hd, f, v = (cfg.d_model, cfg.n_heads, cfg.n_kv_heads, cfg.head_dim, cfg.d_ffn,
                             cfg.vocab)
     per_layer = (hq + 2 * hkv) * hd * d + d * hq * hd + 3 * f * d
-    esz = 2 if cfg.dtype == "bf16" else 4
+    esz = {"bf16": 2, "fp8w": 1}.get(cfg.dtype, 4)
     return (cfg.n_layers * per_layer + v * d) * esz

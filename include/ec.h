@@ -28,10 +28,11 @@
  *  - batch sequences generate side by side and independently (own prompt, mask set, history,
  *    flag, block, cache): a step concatenates the rows each sequence recomputes, so the weights
  *    stream once for all of them; the results equal those of running each sequence alone.
- *    batch > 1 needs the bfloat16 path.  Per-sequence arguments and results are arrays of
+ *    batch > 1 needs the bfloat16 path (EC_BF16 or EC_FP8W).  Per-sequence arguments and results are arrays of
  *    batch entries in sequence order.
  *  - All matrices are row-major [out_features, in_features] in the model's storage type
- *    (float32 or bfloat16).  Norm gains are vectors of the same type.
+ *    (float32, bfloat16, or under EC_FP8W one e4m3 byte per element plus a float32 scale per
+ *    row).  Norm gains and the embedding are float32 (EC_F32) or bfloat16.
  */
 #ifndef EC_H
 #define EC_H
@@ -49,7 +50,13 @@ extern "C" {
 
 typedef struct ec_ctx ec_ctx; /* opaque */
 
-enum { EC_F32 = 0, EC_BF16 = 1 };
+/* Storage type of the model.  EC_FP8W: the matrices (q, k, v, o, gate, up, down, LM head) are
+ * 8-bit e4m3 codes (1 sign, 4 exponent bits with bias 7, 3 mantissa bits, no infinities) with one
+ * float32 scale per output row - value = scale[row] * e4m3(code) - while the embedding, the norm
+ * gains, the activations fed to GEMMs and the KV cache are bfloat16 as under EC_BF16.  It halves
+ * the bytes a PARTIAL step streams; the arithmetic (bf16 MFMA on the exactly widened codes, fp32
+ * accumulation, scales applied to the sums) is otherwise that of EC_BF16. */
+enum { EC_F32 = 0, EC_BF16 = 1, EC_FP8W = 2 };
 /* EC_AUTO: follow the flag set by the previous step; the first step is always FULL. */
 enum { EC_FULL = 0, EC_PARTIAL = 1, EC_AUTO = 2 };
 enum {
@@ -66,8 +73,8 @@ enum {
  * absolute positions, grouped-query attention without mask, SwiGLU MLP, no biases, untied
  * embedding and LM head.  logit_scale multiplies the LM-head output (1.0 = the model as is).
  * Supported (EC_ERR_CONFIG otherwise): head_dim 64 or 128; n_heads a multiple of n_kv_heads;
- * d_model and d_ffn multiples of 8 (bfloat16: of 32, and vocab a multiple of 16); vocab at most
- * 163840; prompt + generation at most 15000 positions per sequence.
+ * d_model and d_ffn multiples of 8 (bfloat16: of 32, EC_FP8W: of 64, and vocab a multiple of 16);
+ * vocab at most 163840; prompt + generation at most 15000 positions per sequence.
  * bfloat16 path: the sum of squares of a row of the residual stream is kept in 44.20 fixed point
  * (exact to 5e-7 per 16 features, which is all a row needs down to sums of squares of ~1e-3); it
  * saturates at about 4e12 (|h| of ~3e4 at d_model 4096) instead of overflowing - such a row's
@@ -75,7 +82,7 @@ enum {
 typedef struct {
   int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab, mask_id;
   float rms_eps, rope_base, logit_scale;
-  int32_t dtype; /* EC_F32 | EC_BF16: storage type of weights, activations fed to GEMMs, KV cache */
+  int32_t dtype; /* EC_F32 | EC_BF16 | EC_FP8W */
 } ec_model_cfg;
 
 /* DEVICE pointers, BORROWED.  Per-layer entries are HOST arrays of n_layers DEVICE pointers. */
@@ -92,6 +99,16 @@ typedef struct {
   const void *const *w_gate;    /* [L] of [d_ffn, d_model]          */
   const void *const *w_up;      /* [L] of [d_ffn, d_model]          */
   const void *const *w_down;    /* [L] of [d_model, d_ffn]          */
+  /* EC_FP8W only (ignored otherwise, may be NULL): float32 scales, one per output row of the
+   * matrix of the same name */
+  const float *lm_head_scale;         /* [vocab]                    */
+  const float *const *wq_scale;       /* [L] of [n_heads*head_dim]  */
+  const float *const *wk_scale;       /* [L] of [n_kv_heads*head_dim] */
+  const float *const *wv_scale;
+  const float *const *wo_scale;       /* [L] of [d_model]           */
+  const float *const *w_gate_scale;   /* [L] of [d_ffn]             */
+  const float *const *w_up_scale;
+  const float *const *w_down_scale;   /* [L] of [d_model]           */
 } ec_weights;
 
 /* Decoding parameters: generation length N, block (window) size w, recent-token budget k,

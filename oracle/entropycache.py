@@ -8,8 +8,9 @@ no closed-form result to fall back on: every step is carried out as stated, with
 fusion or reordering.  numpy's matmul / einsum serve as the contraction primitive.
 
 Only tests, the smoke check and the bench's cpu_baseline leg may import this module.  It shares
-no code with the HIP path.  Weights arrive in their storage type (float32, or bfloat16 bit
-patterns as uint16) and are up-cast exactly; all activations are float64.
+no code with the HIP path.  Weights arrive in their storage type (float32, bfloat16 bit patterns
+as uint16, or 8-bit e4m3 codes with a float32 scale per row) and are up-cast exactly; all
+activations are float64.
 
 Readings taken where the paper is silent or inconsistent (each is listed in the design notes):
   * entropy uses the natural logarithm, 0*ln 0 := 0 (Eq. 1);
@@ -59,8 +60,31 @@ NEG_INF = -math.inf
 # ----------------------------------------------------------------------------------------------
 # storage decoding
 # ----------------------------------------------------------------------------------------------
-def to_f64(w: np.ndarray) -> np.ndarray:
-    """Exact up-cast of a stored tensor: float32/float64 as is, uint16 = bfloat16 bit pattern."""
+def e4m3_values() -> np.ndarray:
+    """The 256 values of the 8-bit e4m3 format (1 sign bit, 4 exponent bits with bias 7, 3
+    mantissa bits; exponent 0 = subnormals m/8 * 2^-6; no infinities; S.1111.111 = NaN), written
+    out from the format's definition."""
+    v = np.empty(256, dtype=np.float64)
+    for c in range(256):
+        sgn, e, m = c >> 7, (c >> 3) & 15, c & 7
+        if e == 15 and m == 7:
+            x = math.nan
+        elif e == 0:
+            x = (m / 8.0) * 2.0 ** -6
+        else:
+            x = (1.0 + m / 8.0) * 2.0 ** (e - 7)
+        v[c] = -x if sgn else x
+    return v
+
+
+_E4M3 = e4m3_values()
+
+
+def to_f64(w) -> np.ndarray:
+    """Exact up-cast of a stored tensor: float32/float64 as is, uint16 = bfloat16 bit pattern, an
+    object with `codes` (uint8 e4m3) and `scale` (float32 per row) = scale[row] * e4m3(code)."""
+    if hasattr(w, "codes"):
+        return _E4M3[w.codes] * w.scale.astype(np.float64)[:, None]
     if w.dtype == np.uint16:
         return (w.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
     return w.astype(np.float64)

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(HERE, "libec.so")
 EC_MAX_N = 32
 EC_MAX_BLOCK = 128
 EC_MAX_BATCH = 64
-EC_F32, EC_BF16 = 0, 1
+EC_F32, EC_BF16, EC_FP8W = 0, 1, 2
 EC_FULL, EC_PARTIAL, EC_AUTO = 0, 1, 2
 EC_GATE_MAX_ENTROPY, EC_GATE_ENTROPY_SUM, EC_GATE_MAX_CONFIDENCE = 0, 1, 2
 EC_SCHED_BLOCKS, EC_SCHED_SLIDING = 0, 1
@@ -41,10 +41,15 @@ class ec_model_cfg(C.Structure):
                [("dtype", C.c_int32)]
 
 
+QUANT_MATRICES = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")
+
+
 class ec_weights(C.Structure):
     _fields_ = [("tok_emb", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p)] + \
                [(n, C.POINTER(C.c_void_p)) for n in ("attn_norm", "wq", "wk", "wv", "wo",
-                                                      "mlp_norm", "w_gate", "w_up", "w_down")]
+                                                      "mlp_norm", "w_gate", "w_up", "w_down")] + \
+               [("lm_head_scale", C.c_void_p)] + \
+               [(n + "_scale", C.POINTER(C.c_void_p)) for n in QUANT_MATRICES]
 
 
 class ec_decode_cfg(C.Structure):
@@ -145,7 +150,7 @@ class EcError(RuntimeError):
 def model_cfg_struct(cfg) -> ec_model_cfg:
     return ec_model_cfg(cfg.n_layers, cfg.d_model, cfg.n_heads, cfg.n_kv_heads, cfg.head_dim,
                         cfg.d_ffn, cfg.vocab, cfg.mask_id, cfg.rms_eps, cfg.rope_base,
-                        cfg.logit_scale, EC_BF16 if cfg.dtype == "bf16" else EC_F32)
+                        cfg.logit_scale, {"f32": EC_F32, "bf16": EC_BF16, "fp8w": EC_FP8W}[cfg.dtype])
 
 
 def decode_cfg_struct(dec) -> ec_decode_cfg:
@@ -163,7 +168,9 @@ def _i32p(a: np.ndarray):
 
 
 def weights_to_device(cfg, w: Dict[str, object], device="cuda:0") -> Dict[str, object]:
-    """Uploads host weights (float32, or uint16 bfloat16 bit patterns) as torch device tensors."""
+    """Uploads host weights (float32, uint16 bfloat16 bit patterns, or matrices as e4m3 codes +
+    float32 row scales) as torch device tensors; a quantised matrix `name` becomes the uint8 tensor
+    `name` and the float32 tensor `name_scale`."""
     import torch
 
     def up(a: np.ndarray):
@@ -173,7 +180,13 @@ def weights_to_device(cfg, w: Dict[str, object], device="cuda:0") -> Dict[str, o
 
     out: Dict[str, object] = {}
     for k, v in w.items():
-        out[k] = [up(x) for x in v] if isinstance(v, list) else up(v)
+        items = v if isinstance(v, list) else [v]
+        if hasattr(items[0], "codes"):
+            codes, scales = [up(x.codes) for x in items], [up(x.scale) for x in items]
+            out[k] = codes if isinstance(v, list) else codes[0]
+            out[k + "_scale"] = scales if isinstance(v, list) else scales[0]
+        else:
+            out[k] = [up(x) for x in v] if isinstance(v, list) else up(v)
     return out
 
 
@@ -244,6 +257,12 @@ class EntropyCache:
             arr = (C.c_void_p * L)(*[t.data_ptr() for t in dev_weights[name]])
             self._ptr_arrays[name] = arr
             setattr(ws, name, C.cast(arr, C.POINTER(C.c_void_p)))
+        if cfg.dtype == "fp8w":
+            ws.lm_head_scale = dev_weights["lm_head_scale"].data_ptr()
+            for name in QUANT_MATRICES:
+                arr = (C.c_void_p * L)(*[t.data_ptr() for t in dev_weights[name + "_scale"]])
+                self._ptr_arrays[name + "_scale"] = arr
+                setattr(ws, name + "_scale", C.cast(arr, C.POINTER(C.c_void_p)))
         self._ws = ws
         plen = _i32(self.Ps)
         need = self.lib.ec_workspace_bytes(C.byref(self._mc), C.byref(self._dc), _i32p(plen))
@@ -325,7 +344,7 @@ class EntropyCache:
             out = np.empty((n, cfg.vocab), dtype=np.float32)
         elif what in (EC_DBG_KCACHE, EC_DBG_VCACHE):
             out = np.empty((T, cfg.n_kv_heads, cfg.head_dim),
-                           dtype=np.uint16 if cfg.dtype == "bf16" else np.float32)
+                           dtype=np.float32 if cfg.dtype == "f32" else np.uint16)
         elif what == EC_DBG_X:
             out = np.empty(T, dtype=np.int32)
         elif what == EC_DBG_MASKED:

@@ -35,6 +35,9 @@ struct Carver {
 // and up interleaved tile by tile, down.
 struct PackedLayer {
   bf16_t *wqkv, *wo, *wgu, *wd;  // fragment order, tiles grouped by the matrix' skinny block width
+  // EC_FP8W: the same matrices as e4m3 fragment pairs, and their row scales in packed row order
+  uint8_t *qqkv = nullptr, *qo = nullptr, *qgu = nullptr, *qd = nullptr;
+  float *sqkv = nullptr, *so = nullptr, *sgu = nullptr, *sd = nullptr;
 };
 
 struct Buffers {
@@ -58,11 +61,14 @@ struct Buffers {
   size_t ksplit_floats;
   int* attn_tickets;   // [256] arrival counters of the key slices, zero between launches
   std::vector<PackedLayer> pl; bf16_t* lm_head_p;
+  uint8_t* lm_head_q = nullptr; float* lm_head_s = nullptr;  // EC_FP8W
 };
 
-size_t esize(int dtype) { return dtype == EC_BF16 ? 2 : 4; }
+// bytes of an activation / KV-cache element (EC_FP8W computes like EC_BF16)
+size_t esize(int dtype) { return dtype == EC_F32 ? 4 : 2; }
+bool bf16_path(int dtype) { return dtype != EC_F32; }
 // keys held per cache slab: the packed bf16 cache is padded to whole 32-key blocks
-int kv_keys(int dtype, int T) { return dtype == EC_BF16 ? (T + 31) / 32 * 32 : T; }
+int kv_keys(int dtype, int T) { return bf16_path(dtype) ? (T + 31) / 32 * 32 : T; }
 
 // elements of a packed [N, K] matrix whose tiles are grouped for the GEMM with epilogue `epi`
 size_t packed_elems(int epi, size_t N, size_t K) {
@@ -128,7 +134,7 @@ void carve(Carver& c, const ec_model_cfg& m, const ec_decode_cfg& d, const Geome
   b.u_lm = c.take<char>(BL16 * m.d_model * es);
   b.logits = c.take<float>(BL * m.vocab);
   {  // partial tuples of the vocabulary reduction: from the LM-head epilogue or from vocab_reduce
-    const size_t np_fused = m.dtype == EC_BF16 ? (size_t)lm_head_parts(m.vocab) : 0;
+    const size_t np_fused = bf16_path(m.dtype) ? (size_t)lm_head_parts(m.vocab) : 0;
     const size_t np_plain = (size_t)vocab_reduce_parts(m.vocab);
     b.partials = c.take<float4>(BL * (np_fused > np_plain ? np_fused : np_plain));
   }
@@ -137,7 +143,7 @@ void carve(Carver& c, const ec_model_cfg& m, const ec_decode_cfg& d, const Geome
   b.sumsq = nullptr;
   b.ksplit_part = nullptr; b.ksplit_floats = 0; b.attn_tickets = nullptr;
   b.sumsq_stride = (int)R;
-  if (m.dtype == EC_BF16) {
+  if (bf16_path(m.dtype)) {
     b.sumsq = c.take<unsigned long long>((size_t)(2 * m.n_layers + 1) * kSumSlots * R);
     b.ksplit_floats = (size_t)kMaxKSplit * R * m.d_model;
     b.ksplit_part = c.take<float>(b.ksplit_floats);
@@ -149,13 +155,28 @@ void carve(Carver& c, const ec_model_cfg& m, const ec_decode_cfg& d, const Geome
       p.wo = c.take<bf16_t>(packed_elems(EPI_RESID, m.d_model, nq));
       p.wgu = c.take<bf16_t>(packed_elems(EPI_SWIGLU, 2 * m.d_ffn, m.d_model));
       p.wd = c.take<bf16_t>(packed_elems(EPI_RESID, m.d_model, m.d_ffn));
+      if (m.dtype == EC_FP8W) {  // one byte per element, one scale per (padded) packed row
+        p.qqkv = c.take<uint8_t>(packed_elems(EPI_QKV, nq + 2 * nkv, m.d_model));
+        p.qo = c.take<uint8_t>(packed_elems(EPI_RESID, m.d_model, nq));
+        p.qgu = c.take<uint8_t>(packed_elems(EPI_SWIGLU, 2 * m.d_ffn, m.d_model));
+        p.qd = c.take<uint8_t>(packed_elems(EPI_RESID, m.d_model, m.d_ffn));
+        p.sqkv = c.take<float>(packed_elems(EPI_QKV, nq + 2 * nkv, 1));
+        p.so = c.take<float>(packed_elems(EPI_RESID, m.d_model, 1));
+        p.sgu = c.take<float>(packed_elems(EPI_SWIGLU, 2 * m.d_ffn, 1));
+        p.sd = c.take<float>(packed_elems(EPI_RESID, m.d_model, 1));
+      }
     }
     b.lm_head_p = c.take<bf16_t>(packed_elems(EPI_LOGITS, m.vocab, m.d_model));
+    if (m.dtype == EC_FP8W) {
+      b.lm_head_q = c.take<uint8_t>(packed_elems(EPI_LOGITS, m.vocab, m.d_model));
+      b.lm_head_s = c.take<float>(packed_elems(EPI_LOGITS, m.vocab, 1));
+    }
   }
 }
 
 const char* check_config(const ec_model_cfg* m, const ec_decode_cfg* d, const int32_t* prompt_lens) {
-  if (m->dtype != EC_F32 && m->dtype != EC_BF16) return "dtype must be EC_F32 or EC_BF16";
+  if (m->dtype != EC_F32 && m->dtype != EC_BF16 && m->dtype != EC_FP8W)
+    return "dtype must be EC_F32, EC_BF16 or EC_FP8W";
   if (m->n_layers < 1 || m->d_model < 1 || m->n_heads < 1 || m->n_kv_heads < 1 || m->d_ffn < 1 ||
       m->vocab < 2)
     return "model sizes must be positive";
@@ -166,12 +187,14 @@ const char* check_config(const ec_model_cfg* m, const ec_decode_cfg* d, const in
   if (!(m->rms_eps >= 0.f) || !(m->rope_base > 1.f) || !(m->logit_scale > 0.f))
     return "rms_eps >= 0, rope_base > 1 and logit_scale > 0 are required";
   if (m->d_model % 8 || m->d_ffn % 8) return "d_model and d_ffn must be multiples of 8";
-  if (m->dtype == EC_BF16) {
+  if (bf16_path(m->dtype)) {
     if (m->d_model % 32 || m->d_ffn % 32 || m->vocab % 16)
       return "bf16 path: d_model, d_ffn must be multiples of 32 and vocab a multiple of 16";
   }
+  if (m->dtype == EC_FP8W && (m->d_model % 64 || m->d_ffn % 64))
+    return "EC_FP8W: d_model and d_ffn must be multiples of 64";
   if (d->batch < 1 || d->batch > EC_MAX_BATCH) return "batch must be in [1, EC_MAX_BATCH]";
-  if (d->batch > 1 && m->dtype != EC_BF16) return "batch > 1 needs the bfloat16 path";
+  if (d->batch > 1 && !bf16_path(m->dtype)) return "batch > 1 needs the bfloat16 path";
   if (d->gen_len < 1) return "gen_len must be positive";
   if (d->block < 1 || d->block > EC_MAX_BLOCK) return "block must be in [1, EC_MAX_BLOCK]";
   if (d->tokens_per_step < 1 || d->tokens_per_step > EC_MAX_N)
@@ -207,6 +230,7 @@ struct ec_ctx {
   ec_decode_cfg d;
   ec_weights w;  // device pointers; per-layer arrays copied into the vectors below
   std::vector<const void*> attn_norm, wq, wk, wv, wo, mlp_norm, w_gate, w_up, w_down;
+  std::vector<const float*> wq_s, wk_s, wv_s, wo_s, w_gate_s, w_up_s, w_down_s;  // EC_FP8W
   Geometry g;
   int B, N;
   hipStream_t stream;
@@ -430,8 +454,8 @@ int forward_bf16(ec_ctx* c, const StepPlan& sp) {
       GemmEpi e{}; e.M = M; e.MT = MT; e.sumsq_in = sums(2 * l); e.d_in = d; e.eps = m.rms_eps;
       e.sum_stride = b.sumsq_stride; e.rowinfo = b.rowinfo; e.cs = b.rope_cs; e.Hq = m.n_heads;
       e.Hkv = m.n_kv_heads; e.hd = hd; e.q_out = q; e.kc = kc; e.vc = vc;
-      e.w_grp = skinny_tiles_per_block(EPI_QKV, nqkv / 16);
-      launch_gemm_bf16(EPI_QKV, u, R, b.pl[l].wqkv, nqkv, d, e, s); }
+      e.w_grp = skinny_tiles_per_block(EPI_QKV, nqkv / 16); e.wscale = b.pl[l].sqkv;
+      launch_gemm_bf16(EPI_QKV, u, R, b.pl[l].wqkv, b.pl[l].qqkv, nqkv, d, e, s); }
     { Scope p(c, EC_K_ATTN);
       launch_attention_mfma(q, kc, vc, R, b.rowinfo, sp.single ? nullptr : b.tileinfo,
                             sp.single ? nullptr : b.pairs, sp.npairs, sp.one_seq, sp.has_small,
@@ -441,39 +465,39 @@ int forward_bf16(ec_ctx* c, const StepPlan& sp) {
       GemmEpi e{}; e.M = M; e.MT = MT; e.h = b.h; e.d = d; e.gain_next = G(c->mlp_norm[l]);
       e.a_next = u; e.sumsq_out = sums(2 * l + 1); e.sum_stride = b.sumsq_stride;
       e.partial = b.ksplit_part; e.max_ksplit = kMaxKSplit;
-      e.w_grp = skinny_tiles_per_block(EPI_RESID, d / 16);
-      launch_gemm_bf16(EPI_RESID, attn, R, b.pl[l].wo, d, nq, e, s); }
+      e.w_grp = skinny_tiles_per_block(EPI_RESID, d / 16); e.wscale = b.pl[l].so;
+      launch_gemm_bf16(EPI_RESID, attn, R, b.pl[l].wo, b.pl[l].qo, d, nq, e, s); }
     { Scope p(c, EC_K_GATEUP);
       GemmEpi e{}; e.M = M; e.MT = MT; e.sumsq_in = sums(2 * l + 1); e.d_in = d; e.eps = m.rms_eps;
       e.sum_stride = b.sumsq_stride; e.act = act;
-      e.w_grp = skinny_tiles_per_block(EPI_SWIGLU, 2 * F / 16);
-      launch_gemm_bf16(EPI_SWIGLU, u, R, b.pl[l].wgu, 2 * F, d, e, s); }
+      e.w_grp = skinny_tiles_per_block(EPI_SWIGLU, 2 * F / 16); e.wscale = b.pl[l].sgu;
+      launch_gemm_bf16(EPI_SWIGLU, u, R, b.pl[l].wgu, b.pl[l].qgu, 2 * F, d, e, s); }
     { Scope p(c, EC_K_DOWN);
       GemmEpi e{}; e.M = M; e.MT = MT; e.h = b.h; e.d = d;
       e.gain_next = G(l + 1 < L ? c->attn_norm[l + 1] : c->w.final_norm);
       e.a_next = u; e.sumsq_out = sums(2 * l + 2); e.sum_stride = b.sumsq_stride;
       e.partial = b.ksplit_part; e.max_ksplit = kMaxKSplit;
-      e.w_grp = skinny_tiles_per_block(EPI_RESID, d / 16);
-      launch_gemm_bf16(EPI_RESID, act, R, b.pl[l].wd, d, F, e, s); }
+      e.w_grp = skinny_tiles_per_block(EPI_RESID, d / 16); e.wscale = b.pl[l].sd;
+      launch_gemm_bf16(EPI_RESID, act, R, b.pl[l].wd, b.pl[l].qd, d, F, e, s); }
   }
   // logits only for the blocks' masked rows: the LM head gathers them from `u`
   { Scope p(c, EC_K_LMHEAD);
     GemmEpi e{}; e.M = sp.n_lm; e.MT = (sp.n_lm + 15) / 16; e.row_sel = b.lm_sel;
     e.sumsq_in = sums(2 * L); e.d_in = d; e.eps = m.rms_eps; e.sum_stride = b.sumsq_stride;
     e.scale = m.logit_scale; e.logits = b.logits; e.ldc = m.vocab;
-    e.w_grp = skinny_tiles_per_block(EPI_LOGITS, m.vocab / 16);
+    e.w_grp = skinny_tiles_per_block(EPI_LOGITS, m.vocab / 16); e.wscale = b.lm_head_s;
     if (sp.n_lm <= kLmSkinnyRows) {
       // the epilogue reduces the vocabulary itself; the logits go to memory only on request
       e.vparts = b.partials;
       if (!c->keep_logits) e.logits = nullptr;
       c->fused_reduce = true; c->step_nparts = lm_head_parts(m.vocab);
       c->logits_stored = c->keep_logits;
-      launch_gemm_bf16(EPI_LOGITS, u, R, b.lm_head_p, m.vocab, d, e, s);
+      launch_gemm_bf16(EPI_LOGITS, u, R, b.lm_head_p, b.lm_head_q, m.vocab, d, e, s);
     } else {  // many sequences: gather the rows once, then one pass over the LM head
       c->fused_reduce = false; c->step_nparts = vocab_reduce_parts(m.vocab);
       c->logits_stored = true;
       launch_gather_rows_packed(u, R, b.lm_sel, sp.n_lm, d, (bf16_t*)b.u_lm, s);
-      launch_gemm_bf16(EPI_LOGITS, (bf16_t*)b.u_lm, sp.n_lm, b.lm_head_p, m.vocab, d, e, s);
+      launch_gemm_bf16(EPI_LOGITS, (bf16_t*)b.u_lm, sp.n_lm, b.lm_head_p, b.lm_head_q, m.vocab, d, e, s);
     } }
   return EC_OK;
 }
@@ -691,6 +715,16 @@ static int init_impl(ec_ctx** out, const ec_model_cfg* model, const ec_weights* 
         !weights->wo[l] || !weights->mlp_norm[l] || !weights->w_gate[l] || !weights->w_up[l] ||
         !weights->w_down[l])
       return fail(nullptr, EC_ERR_ARG, "a per-layer weight pointer is NULL");
+  if (model->dtype == EC_FP8W) {
+    if (!weights->lm_head_scale || !weights->wq_scale || !weights->wk_scale || !weights->wv_scale ||
+        !weights->wo_scale || !weights->w_gate_scale || !weights->w_up_scale || !weights->w_down_scale)
+      return fail(nullptr, EC_ERR_ARG, "EC_FP8W: a scale pointer is NULL");
+    for (int l = 0; l < model->n_layers; ++l)
+      if (!weights->wq_scale[l] || !weights->wk_scale[l] || !weights->wv_scale[l] ||
+          !weights->wo_scale[l] || !weights->w_gate_scale[l] || !weights->w_up_scale[l] ||
+          !weights->w_down_scale[l])
+        return fail(nullptr, EC_ERR_ARG, "EC_FP8W: a per-layer scale pointer is NULL");
+  }
   size_t need = ec_workspace_bytes(model, decode, prompt_lens);
   if (!workspace) return fail(nullptr, EC_ERR_WORKSPACE, "workspace is NULL");
   if (((uintptr_t)workspace) % kAlign) return fail(nullptr, EC_ERR_WORKSPACE, "workspace is not 256-byte aligned");
@@ -711,6 +745,15 @@ static int init_impl(ec_ctx** out, const ec_model_cfg* model, const ec_weights* 
   c->w_gate.assign(weights->w_gate, weights->w_gate + L);
   c->w_up.assign(weights->w_up, weights->w_up + L);
   c->w_down.assign(weights->w_down, weights->w_down + L);
+  if (model->dtype == EC_FP8W) {
+    c->wq_s.assign(weights->wq_scale, weights->wq_scale + L);
+    c->wk_s.assign(weights->wk_scale, weights->wk_scale + L);
+    c->wv_s.assign(weights->wv_scale, weights->wv_scale + L);
+    c->wo_s.assign(weights->wo_scale, weights->wo_scale + L);
+    c->w_gate_s.assign(weights->w_gate_scale, weights->w_gate_scale + L);
+    c->w_up_s.assign(weights->w_up_scale, weights->w_up_scale + L);
+    c->w_down_s.assign(weights->w_down_scale, weights->w_down_scale + L);
+  }
   c->g = g; c->B = B; c->N = decode->gen_len;
   c->stream = (hipStream_t)hip_stream;
   Carver cv(workspace);
@@ -736,7 +779,7 @@ static int init_impl(ec_ctx** out, const ec_model_cfg* model, const ec_weights* 
 
   // one-time device set-up: RoPE table, re-tiled bf16 matrices, finite padding keys
   launch_rope_table(c->b.rope_cs, g.tmax, c->m.head_dim, c->m.rope_base, c->stream);
-  if (c->m.dtype == EC_BF16) {
+  if (bf16_path(c->m.dtype)) {
     size_t kvbytes = (size_t)L * 2 * c->b.kv_plane * 2;
     e = hipMemsetAsync(c->b.kv, 0, kvbytes, c->stream);
     if (e == hipSuccess) e = hipMemsetAsync(c->b.attn_tickets, 0, 256 * sizeof(int), c->stream);
@@ -749,21 +792,49 @@ static int init_impl(ec_ctx** out, const ec_model_cfg* model, const ec_weights* 
     const int nq = c->m.n_heads * c->m.head_dim, nkv = c->m.n_kv_heads * c->m.head_dim;
     const int hd = c->m.head_dim;
     auto Bp = [](const void* p) { return (const bf16_t*)p; };
+    auto Qp = [](const void* p) { return (const uint8_t*)p; };
+    const bool quant = c->m.dtype == EC_FP8W;
+    const int glm = skinny_tiles_per_block(EPI_LOGITS, c->m.vocab / 16);
     for (int l = 0; l < L; ++l) {
       PackedLayer& p = c->b.pl[l];
       const int gq = skinny_tiles_per_block(EPI_QKV, (nq + 2 * nkv) / 16);
       const int go = skinny_tiles_per_block(EPI_RESID, d / 16);
       const int gg = skinny_tiles_per_block(EPI_SWIGLU, 2 * F / 16);
-      launch_repack_weight(Bp(c->wq[l]), nq, d, p.wqkv, REPACK_ROPE_HALVES, hd, gq, 0, c->stream);
-      launch_repack_weight(Bp(c->wk[l]), nkv, d, p.wqkv, REPACK_ROPE_HALVES, hd, gq, nq, c->stream);
-      launch_repack_weight(Bp(c->wv[l]), nkv, d, p.wqkv, REPACK_PLAIN, hd, gq, nq + nkv, c->stream);
-      launch_repack_weight(Bp(c->wo[l]), d, nq, p.wo, REPACK_PLAIN, hd, go, 0, c->stream);
-      launch_repack_weight(Bp(c->w_gate[l]), F, d, p.wgu, REPACK_LO8, hd, gg, 0, c->stream);
-      launch_repack_weight(Bp(c->w_up[l]), F, d, p.wgu, REPACK_HI8, hd, gg, 0, c->stream);
-      launch_repack_weight(Bp(c->w_down[l]), d, F, p.wd, REPACK_PLAIN, hd, go, 0, c->stream);
+      if (!quant) {
+        launch_repack_weight(Bp(c->wq[l]), nq, d, p.wqkv, REPACK_ROPE_HALVES, hd, gq, 0, c->stream);
+        launch_repack_weight(Bp(c->wk[l]), nkv, d, p.wqkv, REPACK_ROPE_HALVES, hd, gq, nq, c->stream);
+        launch_repack_weight(Bp(c->wv[l]), nkv, d, p.wqkv, REPACK_PLAIN, hd, gq, nq + nkv, c->stream);
+        launch_repack_weight(Bp(c->wo[l]), d, nq, p.wo, REPACK_PLAIN, hd, go, 0, c->stream);
+        launch_repack_weight(Bp(c->w_gate[l]), F, d, p.wgu, REPACK_LO8, hd, gg, 0, c->stream);
+        launch_repack_weight(Bp(c->w_up[l]), F, d, p.wgu, REPACK_HI8, hd, gg, 0, c->stream);
+        launch_repack_weight(Bp(c->w_down[l]), d, F, p.wd, REPACK_PLAIN, hd, go, 0, c->stream);
+        continue;
+      }
+      // e4m3 codes: fragment pairs for the weight-streaming kernels, exact bf16 fragments for
+      // the tiled ones, and the row scales in the packed matrices' row order
+      struct Part { const void* w; const float* sc; int N, K; uint8_t* q; bf16_t* p; float* s; int mode, grp, row0; };
+      const Part parts[] = {
+          {c->wq[l], c->wq_s[l], nq, d, p.qqkv, p.wqkv, p.sqkv, REPACK_ROPE_HALVES, gq, 0},
+          {c->wk[l], c->wk_s[l], nkv, d, p.qqkv, p.wqkv, p.sqkv, REPACK_ROPE_HALVES, gq, nq},
+          {c->wv[l], c->wv_s[l], nkv, d, p.qqkv, p.wqkv, p.sqkv, REPACK_PLAIN, gq, nq + nkv},
+          {c->wo[l], c->wo_s[l], d, nq, p.qo, p.wo, p.so, REPACK_PLAIN, go, 0},
+          {c->w_gate[l], c->w_gate_s[l], F, d, p.qgu, p.wgu, p.sgu, REPACK_LO8, gg, 0},
+          {c->w_up[l], c->w_up_s[l], F, d, p.qgu, p.wgu, p.sgu, REPACK_HI8, gg, 0},
+          {c->w_down[l], c->w_down_s[l], d, F, p.qd, p.wd, p.sd, REPACK_PLAIN, go, 0}};
+      for (const Part& t : parts) {
+        launch_repack_weight_e4m3(Qp(t.w), t.N, t.K, t.q, t.p, t.mode, hd, t.grp, t.row0, c->stream);
+        launch_repack_rows_f32(t.sc, t.N, t.s, t.mode, hd, t.row0, c->stream);
+      }
     }
-    launch_repack_weight(Bp(c->w.lm_head), c->m.vocab, d, c->b.lm_head_p, REPACK_PLAIN, hd,
-                         skinny_tiles_per_block(EPI_LOGITS, c->m.vocab / 16), 0, c->stream);
+    if (!quant) {
+      launch_repack_weight(Bp(c->w.lm_head), c->m.vocab, d, c->b.lm_head_p, REPACK_PLAIN, hd, glm, 0,
+                           c->stream);
+    } else {
+      launch_repack_weight_e4m3(Qp(c->w.lm_head), c->m.vocab, d, c->b.lm_head_q, c->b.lm_head_p,
+                                REPACK_PLAIN, hd, glm, 0, c->stream);
+      launch_repack_rows_f32(c->w.lm_head_scale, c->m.vocab, c->b.lm_head_s, REPACK_PLAIN, hd, 0,
+                             c->stream);
+    }
   }
   e = hipGetLastError();
   if (e != hipSuccess) return bail(EC_ERR_HIP, std::string("set-up kernels: ") + hipGetErrorString(e));
@@ -877,7 +948,7 @@ int ec_debug_read_seq(ec_ctx* ctx, int seq, int what, int layer, void* host_dst,
       if (layer < 0 || layer >= ctx->m.n_layers) return fail(ctx, EC_ERR_ARG, "layer out of range");
       src = kv_ptr(ctx, layer, what == EC_DBG_VCACHE) + (size_t)ctx->g.kv_off[seq] * es;
       avail = (size_t)T * kvrow;
-      if (ctx->m.dtype == EC_BF16) {
+      if (bf16_path(ctx->m.dtype)) {
         // the packed cache is put back into [T, Hkv, hd] order in a scratch activation buffer
         launch_unpack_cache((const bf16_t*)src, what == EC_DBG_VCACHE, T, ctx->g.tpad[seq],
                             ctx->m.n_kv_heads, ctx->m.head_dim, (bf16_t*)ctx->b.qkv, ctx->stream);

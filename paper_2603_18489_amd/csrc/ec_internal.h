@@ -121,6 +121,8 @@ struct GemmEpi {
                                        // to the sum of squares of the normed input (44.20)
   int sum_stride;
   int w_grp;  // tiles per group of the weight matrix' layout (k_common.h)
+  const float* wscale;            // nullable: per-row scales of a matrix that came as e4m3 codes,
+                                  // in the packed matrix' row order; multiply the K-reduced sums
   int d_in;                       // its length
   float eps;
   float scale;                    // EPI_LOGITS
@@ -180,8 +182,18 @@ void launch_gather_rows_packed(const bf16_t* src, int M_src, const int* sel, int
 void launch_unpack_cache(const bf16_t* packed, int is_v, int T, int Tpad, int Hkv, int hd,
                          bf16_t* out, hipStream_t s);
 // A: packed activations holding M_src rows; W: packed [N/16 tiles][K/32]; see GemmEpi.
-void launch_gemm_bf16(int epi, const bf16_t* Ap, int M_src, const bf16_t* Wp, int N, int K,
-                      const GemmEpi& e, hipStream_t s);
+// Wq: nullable, the same matrix as packed e4m3 codes (then e.wscale holds its row scales): the
+// weight-streaming kernels (few rows) read it instead of Wp.
+void launch_gemm_bf16(int epi, const bf16_t* Ap, int M_src, const bf16_t* Wp, const void* Wq,
+                      int N, int K, const GemmEpi& e, hipStream_t s);
+// e4m3 source: Wq receives the codes as 1 KiB fragment pairs (64 k per weight tile and step),
+// Wp the same values as bf16 fragments (exact); either may be NULL.  mode / hd / grp / row0 as
+// launch_repack_weight.
+void launch_repack_weight_e4m3(const uint8_t* W, int N, int K, uint8_t* Wq, bf16_t* Wp, int mode,
+                               int hd, int grp, int row0, hipStream_t s);
+// dst[row0 + packed row of n] = src[n]: a per-row vector in the packed matrix' row order
+void launch_repack_rows_f32(const float* src, int N, float* dst, int mode, int hd, int row0,
+                            hipStream_t s);
 // q row-major [M, Hq*hd]; packed caches of one layer; out packed bf16 (K = Hq*hd).
 // part / tickets: scratch for splitting the keys over blocks when there are few query rows
 // (part_floats floats; 256 counters, zero on entry and again on exit); null = never split.

@@ -85,6 +85,15 @@ __device__ __forceinline__ size_t packed_w_index(int n, int k, int KB, int grp) 
   return (packed_w_frag(nt, kb, KB, grp) * 64 + g * 16 + r) * 8 + e;
 }
 
+// e4m3 weights W[N, K] (one byte each): a fragment PAIR covers 16 rows x 64 k in 1 KiB; lane
+// g*16 + r holds row r, its first 8 bytes k = kb2*64 + g*8 .. +7 (the MFMA operand of k-block
+// 2*kb2) and its last 8 bytes k = kb2*64 + 32 + g*8 .. +7 (k-block 2*kb2 + 1).  Pairs are ordered
+// like the bf16 fragments, with KB2 = K/64 steps.  Returns a byte index.
+__device__ __forceinline__ size_t packed_w8_index(int n, int k, int KB2, int grp) {
+  int kb2 = k >> 6, half = (k >> 5) & 1, g = (k >> 3) & 3, e = k & 7, nt = n >> 4, r = n & 15;
+  return (packed_w_frag(nt, kb2, KB2, grp) * 64 + g * 16 + r) * 16 + half * 8 + e;
+}
+
 // ---- packed bf16 KV cache (one kv head = one contiguous slab of Tpad * HD elements) -----------
 // K: fragments are MFMA "A" operands of S^T = K Q^T.  A 32-key block holds two 16-row tiles;
 //    tile t, row i is key (i/4)*8 + t*4 + (i%4) of the block, so that after the two tiles'

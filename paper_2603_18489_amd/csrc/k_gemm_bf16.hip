@@ -46,6 +46,17 @@ __device__ __forceinline__ bf16x8 v4_as_bf16x8(u32x4 v) {
   c.u = v;
   return c.b;
 }
+// 8 e4m3 codes (two dwords, lowest byte first) -> 8 bf16 values, exactly (every e4m3 value is a
+// bf16 value): four v_cvt_scalef32_pk_bf16_fp8 with scale 1
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ bf16x8 e4m3x8_as_bf16x8(uint32_t a, uint32_t b) {
+  union { bf16x2_t h[4]; bf16x8 v; } c;
+  c.h[0] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(a, 1.0f, false);
+  c.h[1] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(a, 1.0f, true);
+  c.h[2] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(b, 1.0f, false);
+  c.h[3] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(b, 1.0f, true);
+  return c.v;
+}
 __device__ __forceinline__ uint32_t pack2(float a, float b) { return pack2_bf16(a, b); }
 // x * sigmoid(x) with the hardware exp2 and reciprocal (about 1 ulp each; the result is rounded
 // to bf16 anyway).  exp overflow gives rcp(inf) = 0, the right limit.
@@ -196,11 +207,16 @@ __device__ __forceinline__ void epi_qkv(const GemmEpi& e, int m, int vt, int q4,
 // ---------------------------------------------------------------------------------------------
 // skinny: grid = ceil(n-tiles / NTW) blocks of KS*64 threads
 // ---------------------------------------------------------------------------------------------
-template <int EPI, int MT, int NTW, int KS, int U>
+// W8: the weights are e4m3 codes (k_common.h: packed_w8_index), one 1 KiB fragment pair covering
+// 64 k per weight tile and k-step; a lane's 16 bytes are turned into two bf16 MFMA operands in
+// registers (exact), so a k-step is two MFMAs per (weight tile, m-tile) on two activation
+// fragments, KB counts 64-wide steps, and the per-row scales multiply the K-reduced sums.
+template <int EPI, int MT, int NTW, int KS, int U, bool W8 = false>
 __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* __restrict__ Ap,
                                                                    const u32x4* __restrict__ Wp,
                                                                    int total_nt, int KB,
                                                                    int MT_src, GemmEpi e) {
+  constexpr int AW = W8 ? 2 : 1;   // activation fragments per k-step
   extern __shared__ float4 red[];  // [KS][NTW*MT][64]
   // the wave index is made a scalar so that everything derived from it (the K slice) is
   // provably wave-uniform: MFMA ignores the EXEC mask, so it must never sit under a condition
@@ -225,7 +241,7 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* 
     int m = j * 16 + (lane & 15);
     int row = m < e.M ? m : 0;
     if constexpr (EPI == EPI_LOGITS) row = (m < e.M && e.row_sel) ? e.row_sel[m] : row;
-    ap[j] = Ap + ((size_t)kb_lo * MT_src + (row >> 4)) * 64 + (lane >> 4) * 16 + (row & 15);
+    ap[j] = Ap + ((size_t)kb_lo * AW * MT_src + (row >> 4)) * 64 + (lane >> 4) * 16 + (row & 15);
   }
 
   constexpr bool NORMED = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LOGITS);
@@ -246,25 +262,38 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* 
   const int nkb = kb_hi - kb_lo;
   const int last = nkb > 0 ? nkb - 1 : 0;
   const u32x4 zero4 = {0u, 0u, 0u, 0u};
-  u32x4 wa[U][NTW], aa[U][MT], wb[U][NTW], ab[U][MT];
+  u32x4 wa[U][NTW], aa[U][MT * AW], wb[U][NTW], ab[U][MT * AW];
 #define EC_SK_LOAD(WSET, ASET, IT0)                                                        \
   _Pragma("unroll") for (int u = 0; u < U; ++u) {                                          \
     const int it_ = (IT0) + u < last ? (IT0) + u : last;                                   \
     _Pragma("unroll") for (int i = 0; i < NTW; ++i) WSET[u][i] = wp[i][(size_t)it_ * wstep];  \
     _Pragma("unroll") for (int j = 0; j < MT; ++j)                                         \
-        ASET[u][j] = ap[j][(size_t)it_ * MT_src * 64];                                     \
+      _Pragma("unroll") for (int h = 0; h < AW; ++h)                                       \
+        ASET[u][j * AW + h] = ap[j][((size_t)it_ * AW + h) * MT_src * 64];                 \
   }
 #define EC_SK_ZERO_TAIL(ASET, IT0)                                                         \
   _Pragma("unroll") for (int u = 0; u < U; ++u) {                                          \
     const bool in_ = (IT0) + u < nkb;                                                      \
-    _Pragma("unroll") for (int j = 0; j < MT; ++j) ASET[u][j] = in_ ? ASET[u][j] : zero4;  \
+    _Pragma("unroll") for (int j = 0; j < MT * AW; ++j) ASET[u][j] = in_ ? ASET[u][j] : zero4;  \
   }
 #define EC_SK_MMA(WSET, ASET)                                                              \
   _Pragma("unroll") for (int u = 0; u < U; ++u)                                            \
-    _Pragma("unroll") for (int i = 0; i < NTW; ++i)                                        \
-      _Pragma("unroll") for (int j = 0; j < MT; ++j)                                       \
-        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                               \
-            v4_as_bf16x8(WSET[u][i]), v4_as_bf16x8(ASET[u][j]), acc[i][j], 0, 0, 0);
+    _Pragma("unroll") for (int i = 0; i < NTW; ++i) {                                      \
+      if constexpr (W8) {                                                                  \
+        const bf16x8 lo_ = e4m3x8_as_bf16x8(WSET[u][i][0], WSET[u][i][1]);                 \
+        const bf16x8 hi_ = e4m3x8_as_bf16x8(WSET[u][i][2], WSET[u][i][3]);                 \
+        _Pragma("unroll") for (int j = 0; j < MT; ++j) {                                   \
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                             \
+              lo_, v4_as_bf16x8(ASET[u][j * AW]), acc[i][j], 0, 0, 0);                     \
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                             \
+              hi_, v4_as_bf16x8(ASET[u][j * AW + AW - 1]), acc[i][j], 0, 0, 0);            \
+        }                                                                                  \
+      } else {                                                                             \
+        _Pragma("unroll") for (int j = 0; j < MT; ++j)                                     \
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                             \
+              v4_as_bf16x8(WSET[u][i]), v4_as_bf16x8(ASET[u][j]), acc[i][j], 0, 0, 0);     \
+      }                                                                                    \
+    }
   EC_SK_LOAD(wa, aa, 0)
   // The rows' sum-of-squares counters are fetched behind the first operand loads and turned
   // into 1/rms after the main loop, so neither the loop nor the epilogue waits on them.  All
@@ -282,6 +311,13 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* 
     const int mm = m < e.M ? m : 0, n = (vt < total_nt ? vt : 0) * 16 + (l >> 4) * 4;
     pre_h = *(const float4*)(e.h + (size_t)mm * e.d + n);
     pre_g = *(const u32x2*)(e.gain_next + n);
+  }
+  // W8: the block's per-row weight scales, fetched here and parked in LDS behind the main loop
+  float* wsc_s = rstd_s + MT * 16 + (EPI == EPI_LOGITS ? NTW * MT * 16 * 4 : 0);  // [NTW*16]
+  float wsc_reg = 1.f;
+  if constexpr (W8) {
+    const int n_ = nt0 * 16 + (int)threadIdx.x;
+    wsc_reg = e.wscale[(threadIdx.x < NTW * 16 && n_ < total_nt * 16) ? n_ : 0];
   }
   unsigned long long ssq[kSumSlots];
   if constexpr (NORMED) {
@@ -338,14 +374,22 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* 
     }
     if (threadIdx.x < MT * 16) rstd_s[threadIdx.x] = rstd_from_sum(e, fx);
   }
+  if constexpr (W8) {
+    if (threadIdx.x < NTW * 16) wsc_s[threadIdx.x] = wsc_reg;
+  }
   __syncthreads();
 
-  auto ksum = [&](int idx) {
+  // sum over the KS waves of the lane's 4 output features of weight tile iu (times their scales)
+  auto ksum = [&](int idx, int iu, int q4) {
     float4 s = red[idx];
 #pragma unroll
     for (int w = 1; w < KS; ++w) {
       float4 v = red[w * NTW * MT * 64 + idx];
       s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
+    if constexpr (W8) {
+      const float4 c = *(const float4*)(wsc_s + iu * 16 + q4 * 4);
+      s.x *= c.x; s.y *= c.y; s.z *= c.z; s.w *= c.w;
     }
     return (f32x4){s.x, s.y, s.z, s.w};
   };
@@ -362,7 +406,7 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* 
     for (int o = threadIdx.x; o < UNITS; o += KS * 64) {  // UNITS is a multiple of the block size
       const int l = o & 63, unit = o >> 6, iu = unit / MT, j = unit - iu * MT;
       const int m = j * 16 + (l & 15), q4 = l >> 4, vt = nt0 + iu;
-      const f32x4 v = ksum((iu * MT + j) * 64 + l);
+      const f32x4 v = ksum((iu * MT + j) * 64 + l, iu, q4);
       // (rows past M recompute row 0 and tiles past the end tile 0: finite values, dropped below)
       const float sc = rstd_s[m] * e.scale;
       const float z[4] = {v[0] * sc, v[1] * sc, v[2] * sc, v[3] * sc};
@@ -403,7 +447,7 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* 
     const int m = j * 16 + (l & 15), q4 = l >> 4;
     const bool mvalid = m < e.M;
     const int vt = nt0 + iu;
-    f32x4 v = ksum((iu * MT + j) * 64 + l);
+    f32x4 v = ksum((iu * MT + j) * 64 + l, iu, q4);
     if constexpr (EPI == EPI_RESID) {
       float part = 0.f;
       if (mvalid && vt < total_nt)
@@ -416,13 +460,14 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* 
   }
 }
 
-template <int EPI, int MT, int NTW, int KS, int U = 4>
-static void launch_skinny_t(const bf16_t* Ap, int MT_src, const bf16_t* Wp, int total_nt, int KB,
+template <int EPI, int MT, int NTW, int KS, int U = 4, bool W8 = false>
+static void launch_skinny_t(const bf16_t* Ap, int MT_src, const void* Wp, int total_nt, int KB,
                             const GemmEpi& e, hipStream_t s) {
   int grid = (total_nt + NTW - 1) / NTW;
   size_t smem = (size_t)KS * NTW * MT * 64 * sizeof(float4) + MT * 16 * sizeof(float);
   if (EPI == EPI_LOGITS) smem += (size_t)NTW * MT * 16 * sizeof(float4);  // per-tile row tuples
-  gemm_bf16_skinny_kernel<EPI, MT, NTW, KS, U><<<grid, KS * 64, smem, s>>>(
+  if (W8) smem += NTW * 16 * sizeof(float);                               // weight scales
+  gemm_bf16_skinny_kernel<EPI, MT, NTW, KS, U, W8><<<grid, KS * 64, smem, s>>>(
       (const u32x4*)Ap, (const u32x4*)Wp, total_nt, KB, MT_src, e);
 }
 
@@ -438,6 +483,26 @@ int skinny_tiles_per_block(int epi, int total_nt) {
   if (total_nt >= 6 * 256) return 6;
   if (total_nt >= 3 * 256) return 3;
   return total_nt >= 2 * 256 ? 2 : 1;
+}
+
+// e4m3 weights: KB counts 64-wide k-steps; fewer steps per register set, because a step holds
+// two activation fragments per m-tile
+template <int EPI, int MT>
+static void launch_skinny_mt_w8(const bf16_t* Ap, int MT_src, const void* Wq, int total_nt,
+                                int KB, const GemmEpi& e, hipStream_t s) {
+  if constexpr (EPI == EPI_LOGITS) {
+    launch_skinny_t<EPI, MT, 4, 4, 2, true>(Ap, MT_src, Wq, total_nt, KB, e, s);
+  } else if constexpr (EPI == EPI_RESID) {
+    launch_skinny_t<EPI, MT, 1, 8, (MT > 3 ? 1 : 2), true>(Ap, MT_src, Wq, total_nt, KB, e, s);
+  } else {
+    constexpr int U6 = MT > 2 ? 1 : 2, U8 = MT > 3 ? 1 : 2;
+    switch (skinny_tiles_per_block(EPI, total_nt)) {
+      case 6: launch_skinny_t<EPI, MT, 6, 4, U6, true>(Ap, MT_src, Wq, total_nt, KB, e, s); break;
+      case 3: launch_skinny_t<EPI, MT, 3, 8, U8, true>(Ap, MT_src, Wq, total_nt, KB, e, s); break;
+      case 2: launch_skinny_t<EPI, MT, 2, 8, U8, true>(Ap, MT_src, Wq, total_nt, KB, e, s); break;
+      default: launch_skinny_t<EPI, MT, 1, 8, U8, true>(Ap, MT_src, Wq, total_nt, KB, e, s); break;
+    }
+  }
 }
 
 template <int EPI, int MT>
@@ -633,6 +698,25 @@ __device__ __forceinline__ void tiled_epilogue(const GemmEpi& e, f32x4 (&acc)[WT
   }
 }
 
+// Per-row weight scales (matrices that came as e4m3 codes, expanded to bf16 for these kernels):
+// the lane's 4 accumulator values of weight tile i are output features (nt_base + i)*16 + q4*4 ..
+template <int WTM, int WTN>
+__device__ __forceinline__ void scale_acc(const GemmEpi& e, f32x4 (&acc)[WTN][WTM], int nt_base,
+                                          int total_nt, int lane) {
+  const int q4 = lane >> 4;
+#pragma unroll
+  for (int i = 0; i < WTN; ++i) {
+    const int vt = nt_base + i < total_nt ? nt_base + i : 0;
+    const float4 c = *(const float4*)(e.wscale + (size_t)vt * 16 + q4 * 4);
+#pragma unroll
+    for (int j = 0; j < WTM; ++j) {
+      f32x4 a = acc[i][j];
+      a[0] *= c.x; a[1] *= c.y; a[2] *= c.z; a[3] *= c.w;
+      acc[i][j] = a;
+    }
+  }
+}
+
 // Which (n-block, m-block) a thread block works on.  Blocks go to the 8 XCDs round-robin by
 // their linear index, and each XCD has its own L2: the m-blocks that share an n-block's weight
 // tiles should meet in one L2.  gridDim.x a multiple of 8 gives that by itself.  Otherwise the
@@ -751,6 +835,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_tiled4_kernel(const u32x4* __re
   }
 #undef EC_TILED_STEP
 
+  if (e.wscale) scale_acc<WTM, WTN>(e, acc, nt0 + wn * WTN, total_nt, lane);
   tiled_epilogue<EPI, WTM, WTN>(e, acc, mt0 + wm * WTM, nt0 + wn * WTN, total_nt, lane, blockIdx.z);
 }
 #undef EC_TILED_GLOAD
@@ -919,6 +1004,7 @@ void gemm_bf16_tiled8_kernel(
   }
   wait_vmcnt<0>();  // drain the clamped tail loads before the LDS goes away
 
+  if (e.wscale) scale_acc<WTM, WTN>(e, acc, nt0 + wn * WTN, total_nt, lane);
   // (the read-ahead QKV epilogue needs registers that only the smaller wave tiles leave free)
   tiled_epilogue<EPI, WTM, WTN, (WTM * WTN <= 18)>(e, acc, mt0 + wm * WTM, nt0 + wn * WTN, total_nt, lane,
                                                    blockIdx.z);
@@ -1014,9 +1100,20 @@ static void launch_tiled_pick(const bf16_t* Ap, int MT, const bf16_t* Wp, int to
 }
 
 template <int EPI>
-static void launch_epi(const bf16_t* Ap, int M_src, const bf16_t* Wp, int N, int K,
+static void launch_epi(const bf16_t* Ap, int M_src, const bf16_t* Wp, const void* Wq, int N, int K,
                        const GemmEpi& e, hipStream_t s) {
   const int total_nt = N / 16, KB = K / 32, MT = (e.M + 15) / 16, MT_src = (M_src + 15) / 16;
+  if (Wq && MT <= 6 && !(EPI == EPI_LOGITS && MT > 4)) {  // weight streaming from e4m3 codes
+    switch (MT) {
+      case 1: launch_skinny_mt_w8<EPI, 1>(Ap, MT_src, Wq, total_nt, K / 64, e, s); break;
+      case 2: launch_skinny_mt_w8<EPI, 2>(Ap, MT_src, Wq, total_nt, K / 64, e, s); break;
+      case 3: launch_skinny_mt_w8<EPI, 3>(Ap, MT_src, Wq, total_nt, K / 64, e, s); break;
+      case 4: launch_skinny_mt_w8<EPI, 4>(Ap, MT_src, Wq, total_nt, K / 64, e, s); break;
+      case 5: launch_skinny_mt_w8<EPI, 5>(Ap, MT_src, Wq, total_nt, K / 64, e, s); break;
+      default: launch_skinny_mt_w8<EPI, 6>(Ap, MT_src, Wq, total_nt, K / 64, e, s); break;
+    }
+    return;
+  }
   // Up to 96 rows (a block of 32 plus the paper's default budget of 64 recent tokens) the GEMMs
   // are weight-streaming: 3.7 ms a step at 64 rows, 4.5 ms at 96, against 7.8 ms through the
   // tiled kernels.
@@ -1043,18 +1140,18 @@ static void launch_epi(const bf16_t* Ap, int M_src, const bf16_t* Wp, int N, int
   }
 }
 
-void launch_gemm_bf16(int epi, const bf16_t* Ap, int M_src, const bf16_t* Wp, int N, int K,
-                      const GemmEpi& e, hipStream_t s) {
+void launch_gemm_bf16(int epi, const bf16_t* Ap, int M_src, const bf16_t* Wp, const void* Wq,
+                      int N, int K, const GemmEpi& e, hipStream_t s) {
   if (e.M <= 0) return;
   switch (epi) {
-    case EPI_QKV: launch_epi<EPI_QKV>(Ap, M_src, Wp, N, K, e, s); break;
-    case EPI_RESID: launch_epi<EPI_RESID>(Ap, M_src, Wp, N, K, e, s); break;
-    case EPI_SWIGLU: launch_epi<EPI_SWIGLU>(Ap, M_src, Wp, N, K, e, s); break;
+    case EPI_QKV: launch_epi<EPI_QKV>(Ap, M_src, Wp, Wq, N, K, e, s); break;
+    case EPI_RESID: launch_epi<EPI_RESID>(Ap, M_src, Wp, Wq, N, K, e, s); break;
+    case EPI_SWIGLU: launch_epi<EPI_SWIGLU>(Ap, M_src, Wp, Wq, N, K, e, s); break;
     default:
       // Up to 64 rows the skinny kernel gathers the rows row_sel names out of Ap itself.  More
       // rows go through the tiled kernels, which read their rows in place: the caller hands
       // over the gathered rows then (row_sel still names the rows whose 1/rms applies).
-      launch_epi<EPI_LOGITS>(Ap, M_src, Wp, N, K, e, s);
+      launch_epi<EPI_LOGITS>(Ap, M_src, Wp, Wq, N, K, e, s);
       break;
   }
 }

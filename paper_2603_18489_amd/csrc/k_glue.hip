@@ -203,6 +203,8 @@ void launch_swiglu_f32(const float* gu, int M, int F, float* act, hipStream_t s)
 //                       rotary partner c + hd/2 to row 8 + c%8 of the same tile
 //   REPACK_LO8 / HI8    (n/8)*16 + n%8  /  (n/8)*16 + 8 + n%8  (two matrices, 8 rows each per tile)
 // ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ int repack_row(int n, int mode, int hd);
+
 __global__ __launch_bounds__(256) void repack_weight_kernel(const bf16_t* __restrict__ W, int N,
                                                             int K, bf16_t* __restrict__ Wp,
                                                             int mode, int hd, int grp, int row0) {
@@ -211,18 +213,63 @@ __global__ __launch_bounds__(256) void repack_weight_kernel(const bf16_t* __rest
   if (i >= total) return;
   int n = (int)(i / (K / 8));
   int k = (int)(i % (K / 8)) * 8;
-  int dn = n;
+  const int dn = repack_row(n, mode, hd);
+  uint4 v = *(const uint4*)(W + (size_t)n * K + k);
+  *(uint4*)(Wp + packed_w_index(row0 + dn, k, K / 32, grp)) = v;
+}
+
+// destination row (before row0) of source row n under a re-tiling mode
+__device__ __forceinline__ int repack_row(int n, int mode, int hd) {
   if (mode == REPACK_ROPE_HALVES) {
     int head = n / hd, c = n - head * hd, half = hd >> 1;
     int cc = c < half ? c : c - half;
-    dn = head * hd + (cc >> 3) * 16 + (c < half ? 0 : 8) + (cc & 7);
-  } else if (mode == REPACK_LO8) {
-    dn = (n >> 3) * 16 + (n & 7);
-  } else if (mode == REPACK_HI8) {
-    dn = (n >> 3) * 16 + 8 + (n & 7);
+    return head * hd + (cc >> 3) * 16 + (c < half ? 0 : 8) + (cc & 7);
   }
-  uint4 v = *(const uint4*)(W + (size_t)n * K + k);
-  *(uint4*)(Wp + packed_w_index(row0 + dn, k, K / 32, grp)) = v;
+  if (mode == REPACK_LO8) return (n >> 3) * 16 + (n & 7);
+  if (mode == REPACK_HI8) return (n >> 3) * 16 + 8 + (n & 7);
+  return n;
+}
+
+// The same re-tiling from e4m3 codes: 8 consecutive k per thread go to the fragment pairs as they
+// are (8 bytes) and, widened exactly to bf16, to the bf16 fragments (16 bytes).
+__global__ __launch_bounds__(256) void repack_weight_e4m3_kernel(
+    const uint8_t* __restrict__ W, int N, int K, uint8_t* __restrict__ Wq, bf16_t* __restrict__ Wp,
+    int mode, int hd, int grp, int row0) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;  // over N * K/8 groups of 8
+  size_t total = (size_t)N * (K / 8);
+  if (i >= total) return;
+  int n = (int)(i / (K / 8));
+  int k = (int)(i % (K / 8)) * 8;
+  const int dn = row0 + repack_row(n, mode, hd);
+  const uint2 v = *(const uint2*)(W + (size_t)n * K + k);
+  if (Wq) *(uint2*)(Wq + packed_w8_index(dn, k, K / 64, grp)) = v;
+  if (Wp) {
+    typedef float f2 __attribute__((ext_vector_type(2)));
+    const f2 a = __builtin_amdgcn_cvt_pk_f32_fp8(v.x, false), b = __builtin_amdgcn_cvt_pk_f32_fp8(v.x, true);
+    const f2 c = __builtin_amdgcn_cvt_pk_f32_fp8(v.y, false), d = __builtin_amdgcn_cvt_pk_f32_fp8(v.y, true);
+    uint4 o = make_uint4(pack2_bf16(a[0], a[1]), pack2_bf16(b[0], b[1]), pack2_bf16(c[0], c[1]),
+                         pack2_bf16(d[0], d[1]));
+    *(uint4*)(Wp + packed_w_index(dn, k, K / 32, grp)) = o;
+  }
+}
+
+void launch_repack_weight_e4m3(const uint8_t* W, int N, int K, uint8_t* Wq, bf16_t* Wp, int mode,
+                               int hd, int grp, int row0, hipStream_t s) {
+  size_t total = (size_t)N * (K / 8);
+  repack_weight_e4m3_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(W, N, K, Wq, Wp, mode,
+                                                                            hd, grp, row0);
+}
+
+__global__ __launch_bounds__(256) void repack_rows_f32_kernel(const float* __restrict__ src, int N,
+                                                              float* __restrict__ dst, int mode,
+                                                              int hd, int row0) {
+  int n = blockIdx.x * 256 + threadIdx.x;
+  if (n < N) dst[row0 + repack_row(n, mode, hd)] = src[n];
+}
+
+void launch_repack_rows_f32(const float* src, int N, float* dst, int mode, int hd, int row0,
+                            hipStream_t s) {
+  repack_rows_f32_kernel<<<(N + 255) / 256, 256, 0, s>>>(src, N, dst, mode, hd, row0);
 }
 
 void launch_repack_weight(const bf16_t* W, int N, int K, bf16_t* Wp, int mode, int hd, int grp,

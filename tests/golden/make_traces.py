@@ -33,7 +33,7 @@ TRACES = {
     "dream7b": dict(workload="dream7b", scale=8.0, modes=[F, P_, P_, P_, F, P_]),
     "llada8b_cot": dict(workload="llada8b_cot", scale=8.0, modes=[F, P_, P_, P_, F, P_]),
     # batch: the 2-layer twin, every sequence follows its own entropy flag
-    "llada8b_b16": dict(workload="llada8b_b16", scale=8.0, n_layers=2, steps=6),
+    "llada8b_b16": dict(workload="llada8b_b16", scale=4.5, n_layers=2, steps=6),
 }
 N_TOP, N_RAND = 16, 256
 N_KV_POS = {1: 64, 16: 8}          # sampled cache positions per step, by batch size

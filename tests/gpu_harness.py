@@ -161,7 +161,7 @@ def check_against_oracle(cfg, dec, tol, ref, q, stats, dz_row, cnt, where=""):
     conf, H = np.asarray(ref["conf"]), np.asarray(ref["H"])
     dz = np.asarray(dz_row, dtype=np.float64)
     gaps = np.asarray(ref["top2gap"])
-    stat_tol = STAT_TOL if cfg.dtype == "bf16" else tol
+    stat_tol = STAT_TOL if cfg.dtype != "f32" else tol
     # Interval that a row's log-confidence can lie in, given |dz| <= dz_i on every logit: with p
     # the oracle's confidence and the argmax unchanged, ln conf moves by -ln(p + (1-p) e^(+-2 dz));
     # in any case by at most 2 dz.

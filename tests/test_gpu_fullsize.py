@@ -39,6 +39,7 @@ def periodic_full(period):
 @pytest.mark.parametrize("name,steps,period,scale", [
     ("llada8b_l2", 72, 12, 8.0),        # 34-row partial steps, 768-row full steps, block change at 32/64
     ("dream7b_l2", 36, 12, 8.0),        # GQA 28/4, 2 tokens per step, T = 1280
+    ("llada8b_fp8_l2", 36, 12, 8.0),    # matrices as e4m3 codes + row scales
 ])
 def test_two_layer_twins(name, steps, period, scale):
     wl = ec_inputs.WORKLOADS[name]

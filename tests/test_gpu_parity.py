@@ -14,7 +14,7 @@ from tests.gpu_harness import run_teacher_forced, run_teacher_forced_batch, rele
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"f32": 1e-4, "bf16": 2e-2}
+TOL = {"f32": 1e-4, "bf16": 2e-2, "fp8w": 2e-2}
 
 
 def small_cfg(dtype, hq=4, hkv=4, hd=64, d=256, f=768, vocab=4096, layers=2, scale=16.0):
@@ -401,3 +401,32 @@ def test_logits_stay_out_of_memory_unless_asked_for():
     assert len(runs[0]) == len(runs[1])
     for (qa, sa), (qb, sb) in zip(*runs):
         assert qa == qb and np.array_equal(sa, sb)
+
+
+@pytest.mark.parametrize("hq,hkv,hd,P,N,block,k,n,tau,f", [
+    (4, 4, 64, 64, 64, 32, 2, 1, 3.0, 768),
+    (4, 2, 128, 50, 70, 32, 4, 2, 2.5, 1280),    # GQA, head_dim 128, ragged last block
+    (8, 2, 64, 100, 33, 32, 2, 3, 1e9, 768),     # 133 rows in FULL steps: tiled kernels + scales
+    (4, 2, 64, 40, 128, 32, 64, 1, 1e9, 6208),   # up to 96 rows; 776 gate/up tiles in groups of 3
+])
+def test_e4m3_weight_models_whole_generation(hq, hkv, hd, P, N, block, k, n, tau, f):
+    """Matrices stored as e4m3 codes with per-row scales (EC_FP8W): partial steps stream the
+    codes and widen them in registers, full steps run on their exact bf16 expansion; both apply
+    the row scales to the sums.  The oracle decodes the same codes exactly."""
+    cfg = small_cfg("fp8w", hq, hkv, hd, d=hq * hd if hq * hd >= 256 else 256, f=f)
+    w = ec_inputs.make_weights(cfg, 7, gain_jitter=0.1)
+    dec = ec_inputs.DecodeCfg(gen_len=N, block=block, k_recent=k, tokens_per_step=n, tau=tau)
+    prompt = ec_inputs.make_prompt(cfg.vocab, P, 3)
+    s = run_teacher_forced(cfg, w, dec, prompt, TOL["fp8w"])
+    print(s)
+    assert s["modes"][eco.PARTIAL] >= 1 and s["tokens_exact"] > 0 and s["modes_exact"] > 0
+
+
+def test_e4m3_weight_batch():
+    cfg = small_cfg("fp8w", 4, 2, 128, d=512)
+    w = ec_inputs.make_weights(cfg, 13, gain_jitter=0.1)
+    dec = ec_inputs.DecodeCfg(gen_len=36, block=32, k_recent=3, tokens_per_step=1, tau=2.5, batch=4)
+    prompts = [ec_inputs.make_prompt(cfg.vocab, P, 20 + i) for i, P in enumerate((70, 9, 33, 150))]
+    s = run_teacher_forced_batch(cfg, w, dec, prompts, TOL["fp8w"], max_steps=12)
+    print(s)
+    assert s["modes"][eco.PARTIAL] >= 1 and s["tokens_exact"] > 0

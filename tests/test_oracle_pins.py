@@ -185,3 +185,77 @@ def test_recent_set_examples():
     assert eco.recent_set([1, 2, 3, 4, 5, 6], 4, 6, 1) == [4, 5]      # step bound (5) wins
     # ties with the k-th entry are all included
     assert eco.recent_set([7, 7, 7, 2], 2, 7, 7) == [0, 1, 2]
+
+
+# ---- e4m3 weight storage (matrices as 8-bit codes with per-row scales) ------------------------
+def test_e4m3_decode_matches_the_format_and_a_library():
+    """The oracle's table against values the format fixes by definition (bias 7, 3 mantissa
+    bits, subnormals, no infinities) and against torch's float8_e4m3fn."""
+    import torch
+    v = eco.e4m3_values()
+    assert v[0x00] == 0.0 and v[0x38] == 1.0 and v[0x40] == 2.0 and v[0x3C] == 1.5
+    assert v[0x01] == 2.0 ** -9 and v[0x07] == 7 * 2.0 ** -9 and v[0x08] == 2.0 ** -6
+    assert v[0x7E] == 448.0 and np.isnan(v[0x7F]) and np.isnan(v[0xFF])
+    assert np.array_equal(v[0x80:0xFF], -v[0x00:0x7F])
+    assert np.all(np.diff(v[:0x7F]) > 0)                       # monotonic in the code
+    t = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    assert np.array_equal(np.nan_to_num(t, nan=7e9), np.nan_to_num(v, nan=7e9))
+
+
+def test_e4m3_encoder_rounds_to_nearest_even_and_saturates():
+    """The input generator's encoder: brute-force nearest representable value (ties to the even
+    code), exact round trip of every code, saturation, and torch's conversion."""
+    import torch
+    import ec_inputs
+    v = eco.e4m3_values()
+    codes = np.array([c for c in range(256) if not np.isnan(v[c])], dtype=np.uint8)
+    back = ec_inputs.f32_to_e4m3_bits(v[codes].astype(np.float32))
+    assert np.array_equal(back[codes != 0x80], codes[codes != 0x80])     # (-0 keeps its sign too)
+    assert back[list(codes).index(0x80)] == 0x80
+    rng = np.random.default_rng(3)
+    x = np.concatenate([rng.standard_normal(20000) * s for s in (0.004, 0.3, 20.0, 300.0)]
+                       ).astype(np.float32)
+    pos = v[:0x7F]
+    mids = (pos[:-1] + pos[1:]) / 2                                       # ties listed exactly
+    x = np.concatenate([x, mids.astype(np.float32), -mids.astype(np.float32),
+                        np.float32([448.0, 449.0, 1e9, -1e9, np.inf, 464.0, 0.0])])
+    got = ec_inputs.f32_to_e4m3_bits(x)
+    for xi, ci in zip(x.astype(np.float64), got):
+        a = min(abs(xi), 448.0)
+        d = np.abs(pos - a)
+        best = np.flatnonzero(d == d.min())
+        want = best[0] if len(best) == 1 else [b for b in best if b % 2 == 0][0]
+        assert (ci & 0x7F) == want and (ci >> 7) == int(np.signbit(xi)), (xi, ci, want)
+    ref = torch.from_numpy(np.clip(x, -448, 448)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(got, ref)
+
+
+def test_quantised_model_is_exactly_its_dequantised_model():
+    """A model stored as e4m3 codes + row scales must behave, in the oracle, exactly like the
+    float model holding scale * value (decoded here through torch, not through the oracle)."""
+    import torch
+    import ec_inputs
+    cfg = ec_inputs.ModelCfg(n_layers=2, d_model=64, n_heads=2, n_kv_heads=1, head_dim=32,
+                             d_ffn=128, vocab=80, mask_id=79, logit_scale=3.0, dtype="fp8w")
+    w = ec_inputs.make_weights(cfg, 5, std=0.3, gain_jitter=0.2, threads=1)
+    assert w["wq"][0].codes.dtype == np.uint8 and w["wq"][0].scale.shape == (64,)
+    # per-row scale maps the row's largest magnitude onto 448, the largest e4m3 value
+    assert np.all((w["w_up"][1].codes & 0x7F).max(axis=1) == 0x7E)
+
+    def deq(m):
+        t = torch.from_numpy(m.codes).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+        return t * m.scale.astype(np.float64)[:, None]
+    wf = {k: ([deq(x) if hasattr(x, "codes") else eco.to_f64(x) for x in v] if isinstance(v, list)
+              else (deq(v) if hasattr(v, "codes") else eco.to_f64(v))) for k, v in w.items()}
+    dec = ec_inputs.DecodeCfg(gen_len=8, block=4, k_recent=2, tokens_per_step=1, tau=1.0)
+    prompt = np.arange(5, dtype=np.int32)
+    a = eco.eco_init(eco.OracleModel(cfg, w), dec, prompt)
+    b = eco.eco_init(eco.OracleModel(cfg.replace(dtype="f32"), wf), dec, prompt)
+    for mode in (eco.FULL, eco.PARTIAL, eco.PARTIAL):
+        ra, rb = eco.eco_step(a, mode), eco.eco_step(b, mode)
+        assert np.array_equal(ra["logits"], rb["logits"]) and ra["positions"] == rb["positions"]
+    assert np.array_equal(a.Kc, b.Kc)
+    # and quantisation moved every weight by at most half a grid step of its row
+    x = ec_inputs.normal_tensor(5, "wq.0", (64, 64), 0.3, "f32")
+    err = np.abs(deq(w["wq"][0]) - x)
+    assert np.all(err <= 0.5 * 32.0 * w["wq"][0].scale[:, None] + 1e-12)   # step <= 32 below 448
