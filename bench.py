@@ -197,11 +197,11 @@ def measure_other_workload(name, dw_by_model, threads):
 
 def cpu_oracle_baseline(cfg, w, dec, prompt, n_full, n_partial, n_tok):
     """Times the fp64 numpy oracle (oracle/entropycache.py, BLAS matmul as its contraction
-    primitive) on 1- and 2-layer prefixes of the model (one FULL and one PARTIAL step each) and
+    primitive) on 2- and 6-layer prefixes of the model (one FULL and two PARTIAL steps each) and
     extrapolates linearly in depth to the full model and the GPU run's mode schedule."""
     from oracle import entropycache as eco
     times = {}
-    for L in (1, 2):
+    for L in (2, 6):
         sub = {k: (v[:L] if isinstance(v, list) else v) for k, v in w.items()}
         st = eco.eco_init(eco.OracleModel(cfg.replace(n_layers=L), sub), dec, prompt)
         t0 = time.perf_counter()
@@ -209,16 +209,17 @@ def cpu_oracle_baseline(cfg, w, dec, prompt, n_full, n_partial, n_tok):
         tf = time.perf_counter() - t0
         t0 = time.perf_counter()
         eco.eco_step(st, eco.PARTIAL, keep_logits=False)
-        tp = time.perf_counter() - t0
+        eco.eco_step(st, eco.PARTIAL, keep_logits=False)
+        tp = (time.perf_counter() - t0) / 2
         times[L] = (tf, tp)
         log(f"[cpu oracle] L={L}: FULL {tf:.2f}s PARTIAL {tp:.2f}s")
-    per_f = times[2][0] - times[1][0]
-    per_p = times[2][1] - times[1][1]
-    tf = times[1][0] + (cfg.n_layers - 1) * per_f
-    tp = times[1][1] + (cfg.n_layers - 1) * per_p
+    per_f = (times[6][0] - times[2][0]) / 4
+    per_p = (times[6][1] - times[2][1]) / 4
+    tf = times[2][0] + (cfg.n_layers - 2) * per_f
+    tp = times[2][1] + (cfg.n_layers - 2) * per_p
     total = n_full * tf + n_partial * tp
     return {"value": n_tok / total, "unit": "tok/s", "cores": os.cpu_count(), "kind": "oracle",
-            "sample": f"1 FULL + 1 PARTIAL fp64 step on 1- and 2-layer prefixes of the model "
+            "sample": f"1 FULL + 2 PARTIAL fp64 steps on 2- and 6-layer prefixes of the model "
                       f"(same widths, vocabulary, prompt), extrapolated linearly to "
                       f"{cfg.n_layers} layers and the GPU run's schedule of {n_full} FULL + "
                       f"{n_partial} PARTIAL steps",

@@ -762,7 +762,7 @@ __device__ __forceinline__ void tiled_block_xy(int& bx, int& by) {
         acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf_[i], af_[j], acc[i][j], 0, 0, 0); \
   }
 
-template <int EPI, int WTM, int WTN>
+template <int EPI, int WTM, int WTN, bool WS>
 __global__ __launch_bounds__(256) void gemm_bf16_tiled4_kernel(const u32x4* __restrict__ Ap,
                                                               const u32x4* __restrict__ Wp,
                                                               int total_nt, int KB_all, int MT,
@@ -835,19 +835,19 @@ __global__ __launch_bounds__(256) void gemm_bf16_tiled4_kernel(const u32x4* __re
   }
 #undef EC_TILED_STEP
 
-  if (e.wscale) scale_acc<WTM, WTN>(e, acc, nt0 + wn * WTN, total_nt, lane);
+  if constexpr (WS) scale_acc<WTM, WTN>(e, acc, nt0 + wn * WTN, total_nt, lane);
   tiled_epilogue<EPI, WTM, WTN>(e, acc, mt0 + wm * WTM, nt0 + wn * WTN, total_nt, lane, blockIdx.z);
 }
 #undef EC_TILED_GLOAD
 #undef EC_TILED_LSTORE
 #undef EC_TILED_COMPUTE
 
-template <int EPI, int WTM, int WTN>
+template <int EPI, int WTM, int WTN, bool WS>
 static void launch_tiled4_t(const bf16_t* Ap, int MT, const bf16_t* Wp, int total_nt, int KB,
                            const GemmEpi& e, hipStream_t s, int ksplit) {
   dim3 grid((total_nt + 2 * WTN - 1) / (2 * WTN), (MT + 2 * WTM - 1) / (2 * WTM), ksplit);
-  gemm_bf16_tiled4_kernel<EPI, WTM, WTN><<<grid, 256, 0, s>>>((const u32x4*)Ap, (const u32x4*)Wp,
-                                                             total_nt, KB, MT, e);
+  gemm_bf16_tiled4_kernel<EPI, WTM, WTN, WS><<<grid, 256, 0, s>>>((const u32x4*)Ap, (const u32x4*)Wp,
+                                                                 total_nt, KB, MT, e);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -871,7 +871,7 @@ constexpr int tiled8_waves_per_eu() {
   // four-wave blocks: two to a CU (256 registers each) unless the read-ahead needs more
   return WM * WN == 4 ? (PIPE ? 1 : 2) : (EPI == EPI_PARTIAL && WTM * WTN <= 18 ? 4 : 2);
 }
-template <int EPI, int WM, int WN, int WTM, int WTN, int NSTAGE, bool PIPE = false>
+template <int EPI, int WM, int WN, int WTM, int WTN, int NSTAGE, bool PIPE, bool WS>
 __global__ __launch_bounds__(WM * WN * 64)
 __attribute__((amdgpu_waves_per_eu(tiled8_waves_per_eu<EPI, WM, WN, WTM, WTN, PIPE>(),
                                    tiled8_waves_per_eu<EPI, WM, WN, WTM, WTN, PIPE>())))
@@ -1004,18 +1004,18 @@ void gemm_bf16_tiled8_kernel(
   }
   wait_vmcnt<0>();  // drain the clamped tail loads before the LDS goes away
 
-  if (e.wscale) scale_acc<WTM, WTN>(e, acc, nt0 + wn * WTN, total_nt, lane);
+  if constexpr (WS) scale_acc<WTM, WTN>(e, acc, nt0 + wn * WTN, total_nt, lane);
   // (the read-ahead QKV epilogue needs registers that only the smaller wave tiles leave free)
   tiled_epilogue<EPI, WTM, WTN, (WTM * WTN <= 18)>(e, acc, mt0 + wm * WTM, nt0 + wn * WTN, total_nt, lane,
                                                    blockIdx.z);
 }
 
-template <int EPI, int WM, int WN, int WTM, int WTN, int NSTAGE, bool PIPE = false>
+template <int EPI, bool WS, int WM, int WN, int WTM, int WTN, int NSTAGE, bool PIPE = false>
 static void launch_tiled8_t(const bf16_t* Ap, int MT, const bf16_t* Wp, int total_nt, int KB,
                             const GemmEpi& e, hipStream_t s, int ksplit) {
   constexpr int NF = WM * WTM + WN * WTN;
   const size_t smem = ((size_t)NSTAGE * NF + 1) * 1024;
-  auto kern = gemm_bf16_tiled8_kernel<EPI, WM, WN, WTM, WTN, NSTAGE, PIPE>;
+  auto kern = gemm_bf16_tiled8_kernel<EPI, WM, WN, WTM, WTN, NSTAGE, PIPE, WS>;
   static bool attr_set = false;
   if (!attr_set && smem > 48 * 1024) {
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -1084,19 +1084,28 @@ static TilePick pick_tile(int MT, int total_nt, int KB, int max_ksplit, int M, i
   return best;
 }
 
+// WS: the matrix carries per-row scales (it came as e4m3 codes): a variant of its own, so that
+// the kernels of plain bf16 models are compiled exactly as they were tuned
+template <int EPI, bool WS>
+static void launch_tiled_pick_ws(const bf16_t* Ap, int MT, const bf16_t* Wp, int total_nt, int KB,
+                                 const GemmEpi& e, hipStream_t s, int tile, int ksplit) {
+  switch (tile) {
+    case 0: launch_tiled8_t<EPI, WS, 2, 4, 6, 6, 3>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
+    case 1: launch_tiled8_t<EPI, WS, 2, 4, 6, 4, 3, true>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
+    case 2: launch_tiled8_t<EPI, WS, 2, 4, 6, 3, 3>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
+    case 3: launch_tiled8_t<EPI, WS, 2, 4, 6, 2, 3>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
+    case 4: launch_tiled4_t<EPI, 6, 6, WS>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
+    case 5: launch_tiled4_t<EPI, 6, 4, WS>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
+    case 6: launch_tiled4_t<EPI, 4, 4, WS>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
+    default: launch_tiled4_t<EPI, 3, 4, WS>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
+  }
+}
+
 template <int EPI>
 static void launch_tiled_pick(const bf16_t* Ap, int MT, const bf16_t* Wp, int total_nt, int KB,
                               const GemmEpi& e, hipStream_t s, int tile, int ksplit) {
-  switch (tile) {
-    case 0: launch_tiled8_t<EPI, 2, 4, 6, 6, 3>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
-    case 1: launch_tiled8_t<EPI, 2, 4, 6, 4, 3, true>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
-    case 2: launch_tiled8_t<EPI, 2, 4, 6, 3, 3>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
-    case 3: launch_tiled8_t<EPI, 2, 4, 6, 2, 3>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
-    case 4: launch_tiled4_t<EPI, 6, 6>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
-    case 5: launch_tiled4_t<EPI, 6, 4>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
-    case 6: launch_tiled4_t<EPI, 4, 4>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
-    default: launch_tiled4_t<EPI, 3, 4>(Ap, MT, Wp, total_nt, KB, e, s, ksplit); break;
-  }
+  if (e.wscale) launch_tiled_pick_ws<EPI, true>(Ap, MT, Wp, total_nt, KB, e, s, tile, ksplit);
+  else launch_tiled_pick_ws<EPI, false>(Ap, MT, Wp, total_nt, KB, e, s, tile, ksplit);
 }
 
 template <int EPI>
