@@ -14,7 +14,6 @@
 namespace ec {
 
 constexpr int VR_CHUNK = 2048;  // logits per block
-constexpr int kHistLds = 4096;   // generation lengths up to this keep the history in LDS
 
 int vocab_reduce_parts(int V) { return (V + VR_CHUNK - 1) / VR_CHUNK; }
 
@@ -109,9 +108,14 @@ __device__ __forceinline__ bool gate_skips(float v, float tau, int metric) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// decide: one block of kDecideThreads threads per sequence.
+// decide: one block of kDecideThreads threads per sequence.  Everything the block reads from
+// memory (state, history, mask set, the rows' partial tuples, the caller's forced tokens) is
+// requested up front; from then on it works in LDS and registers, so the kernel's latency is two
+// memory round trips plus arithmetic.
+// dynamic LDS: int hist[N4] | uint8 masked[N4], N4 = N rounded up to 4
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kDecideThreads) void decide_kernel(DecideArgs a) {
+  extern __shared__ int s_dyn[];
   {  // this block's sequence: move the pointers, take the per-sequence scalars
     const int b = blockIdx.x;
     const SeqDesc sd = a.seqs[b];
@@ -130,12 +134,24 @@ __global__ __launch_bounds__(kDecideThreads) void decide_kernel(DecideArgs a) {
   __shared__ int s_frow[EC_MAX_N];   // block rows of the caller's positions (-1: not in the block)
   __shared__ int scratch[kDecideWaves];
   __shared__ float sh_f[2];
-  __shared__ int s_hist[kHistLds];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  DevState st = *a.st;  // every thread holds a private copy; thread 0 writes it back
-  const int t = st.t;
-  const int P = a.P, N = a.N, T = a.T;
+  const int P = a.P, N = a.N;
+  int* s_hist = s_dyn;
+  uint8_t* s_msk = (uint8_t*)(s_dyn + ((N + 3) & ~3));
   const int nblocks = (N + a.block - 1) / a.block;
+
+  // ---- requests: state, history, mask set, block positions, forced tokens --------------------
+  DevState st = *a.st;  // every thread holds a private copy; thread 0 writes it back
+  for (int i = tid; i < N; i += kDecideThreads) {
+    s_hist[i] = a.hist[i];
+    s_msk[i] = a.masked[P + i];
+  }
+  int f_pos = -1, f_tok = -1;
+  if (!a.init_only) {
+    if (tid < a.n_mb) s_pos[tid] = a.mb_pos[tid];
+    if (tid < a.forced_n) { f_pos = a.forced_pos[tid]; f_tok = a.forced_tok[tid]; }
+  }
+  const int t = st.t;
 
   if (!a.init_only) {
     // ---- merge the vocabulary partials of each block row (fixed order) ----------------------
@@ -147,8 +163,7 @@ __global__ __launch_bounds__(kDecideThreads) void decide_kernel(DecideArgs a) {
       const bool live = row < a.n_mb;
       const float4* pr = a.partials + (size_t)(live ? row : 0) * a.nparts;
       // The lane's running tuple is re-based once per batch of 16 parts (to the batch's maximum
-      // if that is larger), after which a part costs one fast exponential and a few FMAs: the
-      // block has tens of thousands of parts to fold on a single compute unit.
+      // if that is larger), after which a part costs one fast exponential and a few FMAs.
       VTuple v = vt_identity();
       for (int p0 = l32; p0 < a.nparts; p0 += 32 * 16) {
         float4 q[16];
@@ -189,7 +204,6 @@ __global__ __launch_bounds__(kDecideThreads) void decide_kernel(DecideArgs a) {
         s_tok[row] = v.idx;
         s_conf[row] = conf;
         s_H[row] = H;
-        s_pos[row] = a.mb_pos[row];
         *(float4*)(a.row_stats + row * 4) = make_float4((float)v.idx, conf, H, v.m);
       }
     }
@@ -206,8 +220,9 @@ __global__ __launch_bounds__(kDecideThreads) void decide_kernel(DecideArgs a) {
       n = min(min(max(n, above), EC_MAX_N), a.n_mb);
     }
     ec_step_result& R = a.out->r;
+    int rank = EC_MAX_BLOCK;
     if (is_row) {
-      int rank = 0;
+      rank = 0;
       for (int r = 0; r < a.n_mb; ++r) {
         const float c = s_conf[r];
         rank += (c > my_conf || (c == my_conf && r < tid)) ? 1 : 0;
@@ -224,29 +239,25 @@ __global__ __launch_bounds__(kDecideThreads) void decide_kernel(DecideArgs a) {
       R.positions[tid] = -1; R.tokens[tid] = -1; R.entropy[tid] = 0.f; R.confidence[tid] = 0.f;
     }
     // ---- commit: own choice, or the caller's under teacher forcing (Eq. 2) -------------------
+    // (to memory, and to the LDS copies the rest of the kernel works on)
+    int c_pos = -1, c_tok = 0;
     if (a.forced_n >= 0) {
       if (tid < a.forced_n) {
-        const int p = a.forced_pos[tid];
         int row = -1;
         for (int r = 0; r < a.n_mb; ++r)
-          if (s_pos[r] == p) row = r;
+          if (s_pos[r] == f_pos) row = r;
         s_frow[tid] = row;
-        a.x[p] = a.forced_tok[tid];
-        a.masked[p] = 0;
-        a.hist[p - P] = t;
+        c_pos = f_pos; c_tok = f_tok;
       }
-    } else if (is_row) {
-      int rank = 0;   // (recomputed: cheaper than keeping it live across the branch)
-      for (int r = 0; r < a.n_mb; ++r) {
-        const float c = s_conf[r];
-        rank += (c > my_conf || (c == my_conf && r < tid)) ? 1 : 0;
-      }
-      if (rank < n) {
-        const int p = s_pos[tid];
-        a.x[p] = s_tok[tid];
-        a.masked[p] = 0;
-        a.hist[p - P] = t;
-      }
+    } else if (rank < n) {
+      c_pos = s_pos[tid]; c_tok = s_tok[tid];
+    }
+    if (c_pos >= 0) {
+      a.x[c_pos] = c_tok;
+      a.masked[c_pos] = 0;
+      a.hist[c_pos - P] = t;
+      s_msk[c_pos - P] = 0;
+      s_hist[c_pos - P] = t;
     }
     __syncthreads();
     if (tid == 0) {
@@ -268,8 +279,8 @@ __global__ __launch_bounds__(kDecideThreads) void decide_kernel(DecideArgs a) {
       sh_f[0] = E;
       sh_f[1] = own.v;
     }
-    __syncthreads();
   }
+  __syncthreads();   // the LDS copies of history and mask set are complete (and committed to)
 
   // ---- recency threshold: tau_R = max(k-th largest history value, t - dt) --------------------
   // History values are step indices in [1, t] or "never": the k-th largest is the largest v with
@@ -280,20 +291,13 @@ __global__ __launch_bounds__(kDecideThreads) void decide_kernel(DecideArgs a) {
     if (a.mode_run == EC_FULL) t_lastfull = t;
     int kth = INT_MIN;
     if (a.k_recent > 0) {
-      // the bisection reads the history log2(t) times: from LDS if it fits
-      const bool in_lds = N <= kHistLds;
-      if (in_lds) {
-        for (int i = tid; i < N; i += kDecideThreads) s_hist[i] = a.hist[i];
-        __syncthreads();
-      }
       int lo = 1, hi = t, found = INT_MIN;
       while (lo <= hi) {  // uniform across the block
         const int mid = (lo + hi) >> 1;
         int c = 0;
         for (int base = 0; base < N; base += kDecideThreads) {  // uniform trip count
           const int i = base + tid;
-          const int h = i < N ? (in_lds ? s_hist[i] : a.hist[i]) : INT_MIN;
-          c += __syncthreads_count(h >= mid);
+          c += __syncthreads_count(i < N && s_hist[i] >= mid);
         }
         if (c >= a.k_recent) { found = mid; lo = mid + 1; } else { hi = mid - 1; }
       }
@@ -315,9 +319,9 @@ __global__ __launch_bounds__(kDecideThreads) void decide_kernel(DecideArgs a) {
   int blk = st.blk;
   if (!sliding) {
     while (blk < nblocks) {  // uniform: every thread evaluates the same counts
-      const int lo = P + blk * a.block, hi = min(T, lo + a.block);
+      const int lo = blk * a.block, hi = min(N, lo + a.block);
       const int i = lo + tid;   // block <= EC_MAX_BLOCK <= threads
-      if (__syncthreads_count(i < hi && a.masked[i]) > 0) break;
+      if (__syncthreads_count(i < hi && s_msk[i]) > 0) break;
       ++blk;
     }
     st.blk = blk;
@@ -326,15 +330,15 @@ __global__ __launch_bounds__(kDecideThreads) void decide_kernel(DecideArgs a) {
 
   // ---- row lists of the next step: M and M u R, ascending ---------------------------------------
   // M = the masked rows of the current block, or (sliding window) the first `block` masked slots
-  int blo = P + blk * a.block, bhi = min(T, blo + a.block);
+  const int blo = blk * a.block, bhi = min(N, blo + a.block);   // in generation slots
   int n_rows = 0, n_mb = 0, n_recent = 0, masked_seen = 0;
   for (int base = 0; base < N; base += kDecideThreads) {
-    int i = base + tid, pos = P + i;
+    const int i = base + tid, pos = P + i;
     int inM = 0, inR = 0, msk = 0;
     if (i < N) {
-      msk = a.masked[pos] ? 1 : 0;
-      inM = (!sliding && !st.done && pos >= blo && pos < bhi && msk) ? 1 : 0;
-      const int h = a.hist[i];
+      msk = s_msk[i] ? 1 : 0;
+      inM = (!sliding && !st.done && i >= blo && i < bhi && msk) ? 1 : 0;
+      const int h = s_hist[i];
       inR = (!a.init_only && h != INT_MIN && h >= tauR) ? 1 : 0;
     }
     if (sliding) {
@@ -378,7 +382,14 @@ __global__ __launch_bounds__(kDecideThreads) void decide_kernel(DecideArgs a) {
 }
 
 void launch_decide(const DecideArgs& a, int B, hipStream_t s) {
-  decide_kernel<<<B, kDecideThreads, 0, s>>>(a);
+  const size_t smem = (size_t)((a.N + 3) & ~3) * 5;   // history (int) + mask set (byte)
+  static size_t attr_bytes = 48 * 1024;
+  if (smem > attr_bytes) {
+    (void)hipFuncSetAttribute((const void*)decide_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)smem);
+    attr_bytes = smem;
+  }
+  decide_kernel<<<B, kDecideThreads, smem, s>>>(a);
 }
 
 // ---------------------------------------------------------------------------------------------
