@@ -195,6 +195,18 @@ def measure_other_workload(name, dw_by_model, threads):
     return out
 
 
+def blas_threads():
+    """Threads numpy's BLAS runs its matmul on (the oracle's only parallel step)."""
+    try:
+        from threadpoolctl import threadpool_info
+        n = [p["num_threads"] for p in threadpool_info() if p.get("user_api") == "blas"]
+        if n:
+            return max(n)
+    except Exception:
+        pass
+    return int(os.environ.get("OMP_NUM_THREADS", os.cpu_count()))
+
+
 def cpu_oracle_baseline(cfg, w, dec, prompt, n_full, n_partial, n_tok):
     """Times the fp64 numpy oracle (oracle/entropycache.py, BLAS matmul as its contraction
     primitive) on 2- and 6-layer prefixes of the model (one FULL and two PARTIAL steps each) and
@@ -218,7 +230,7 @@ def cpu_oracle_baseline(cfg, w, dec, prompt, n_full, n_partial, n_tok):
     tf = times[2][0] + (cfg.n_layers - 2) * per_f
     tp = times[2][1] + (cfg.n_layers - 2) * per_p
     total = n_full * tf + n_partial * tp
-    return {"value": n_tok / total, "unit": "tok/s", "cores": os.cpu_count(), "kind": "oracle",
+    return {"value": n_tok / total, "unit": "tok/s", "cores": blas_threads(), "kind": "oracle",
             "sample": f"1 FULL + 2 PARTIAL fp64 steps on 2- and 6-layer prefixes of the model "
                       f"(same widths, vocabulary, prompt), extrapolated linearly to "
                       f"{cfg.n_layers} layers and the GPU run's schedule of {n_full} FULL + "
