@@ -235,7 +235,8 @@ struct ec_ctx {
   int B, N;
   hipStream_t stream;
   Buffers b;
-  StepOut* host_out = nullptr;   // pinned [B]
+  StepOut* host_out = nullptr;   // pinned [B]: the decision kernel writes its results here
+  StepOut* host_out_dev = nullptr;  // the same memory as the device addresses it
   int* host_stage = nullptr;     // pinned: prompts / forced lists on their way to the device
   SeqDesc* host_seqs = nullptr;  // pinned [B]
   int4* host_pairs = nullptr;    // pinned [rmax/16 + B]
@@ -308,12 +309,14 @@ char* kv_ptr(ec_ctx* c, int layer, int which) {
 }
 
 void fill_decide_args(ec_ctx* c, DecideArgs& a) {
-  a.seqs = c->b.seqs;
+  // one sequence: its descriptor travels in the kernel arguments, no table upload
+  a.seqs = c->B == 1 ? nullptr : c->b.seqs;
+  a.seq0 = c->host_seqs[0];
   a.partials = c->b.partials; a.nparts = c->step_nparts;
   a.forced_pos = c->b.forced_pos; a.forced_tok = c->b.forced_tok;
   a.x = c->b.x; a.masked = c->b.masked; a.hist = c->b.hist; a.st = c->b.st;
   a.mb_pos = c->b.mb_pos; a.rows_partial = c->b.rows_partial; a.mb_idx = c->b.mb_idx;
-  a.row_stats = c->b.row_stats; a.out = c->b.out;
+  a.row_stats = c->b.row_stats; a.out = c->host_out_dev;
   a.N = c->N; a.block = c->d.block; a.k_recent = c->d.k_recent;
   a.n_tok = c->d.tokens_per_step; a.tau = c->d.tau;
   a.conf_threshold = c->d.conf_threshold; a.gate_metric = c->d.gate_metric;
@@ -345,17 +348,16 @@ int upload_and_init_state(ec_ctx* c, const int32_t* prompt_ids) {
     c->host_seqs[b] = base_desc(c, b);
     c->host_seqs[b].mode = EC_FULL;  // takes part in the list building below
   }
-  EC_HIP(c, hipMemcpyAsync(c->b.seqs, c->host_seqs, (size_t)B * sizeof(SeqDesc),
-                           hipMemcpyHostToDevice, c->stream));
+  if (B > 1)
+    EC_HIP(c, hipMemcpyAsync(c->b.seqs, c->host_seqs, (size_t)B * sizeof(SeqDesc),
+                             hipMemcpyHostToDevice, c->stream));
   c->logits_stored = false;
   DecideArgs a{};
   fill_decide_args(c, a);
   a.init_only = 1;
   launch_decide(a, B, c->stream);
   EC_HIP(c, hipGetLastError());
-  EC_HIP(c, hipMemcpyAsync(c->host_out, c->b.out, (size_t)B * sizeof(StepOut),
-                           hipMemcpyDeviceToHost, c->stream));
-  EC_HIP(c, hipStreamSynchronize(c->stream));
+  EC_HIP(c, hipStreamSynchronize(c->stream));   // (the results sit in host_out once the kernel ended)
   c->steps_run = 0; c->all_done = 0;
   c->next_mode.assign(B, EC_FULL); c->has_full.assign(B, 0); c->done.assign(B, 0);
   c->n_mb.assign(B, 0); c->n_rows_partial.assign(B, 0);
@@ -443,7 +445,7 @@ int forward_bf16(ec_ctx* c, const StepPlan& sp) {
 
   { Scope p(c, EC_K_EMBED);
     StepLists sl{};
-    sl.seqs = b.seqs; sl.B = c->B; sl.R = R; sl.n_lm = sp.n_lm; sl.x = b.x;
+    sl.seqs = c->B == 1 ? nullptr : b.seqs; sl.seq0 = c->host_seqs[0]; sl.B = c->B; sl.R = R; sl.n_lm = sp.n_lm; sl.x = b.x;
     sl.rows_partial = b.rows_partial; sl.mb_pos = b.mb_pos; sl.mb_idx = b.mb_idx;
     sl.block = c->d.block; sl.rowinfo = b.rowinfo; sl.tileinfo = b.tileinfo; sl.lm_sel = b.lm_sel;
     launch_step_prologue_bf16(sl, G(c->w.tok_emb), d, G(c->attn_norm[0]), b.h, u, b.sumsq,
@@ -583,8 +585,9 @@ int run_step(ec_ctx* c, const int32_t* modes, int modes_n, const int32_t* forced
   if (!sp.single && sp.npairs > 0)
     EC_HIP(c, hipMemcpyAsync(c->b.pairs, c->host_pairs, (size_t)sp.npairs * sizeof(int4),
                              hipMemcpyHostToDevice, c->stream));
-  EC_HIP(c, hipMemcpyAsync(c->b.seqs, c->host_seqs, (size_t)B * sizeof(SeqDesc),
-                           hipMemcpyHostToDevice, c->stream));
+  if (B > 1)
+    EC_HIP(c, hipMemcpyAsync(c->b.seqs, c->host_seqs, (size_t)B * sizeof(SeqDesc),
+                             hipMemcpyHostToDevice, c->stream));
   if (forced_n) {
     EC_HIP(c, hipMemcpyAsync(c->b.forced_pos, c->host_stage, (size_t)B * EC_MAX_N * sizeof(int),
                              hipMemcpyHostToDevice, c->stream));
@@ -605,8 +608,7 @@ int run_step(ec_ctx* c, const int32_t* modes, int modes_n, const int32_t* forced
   fill_decide_args(c, a);
   { Scope p(c, EC_K_DECIDE); launch_decide(a, B, c->stream); }
   EC_HIP(c, hipGetLastError());
-  EC_HIP(c, hipMemcpyAsync(c->host_out, c->b.out, (size_t)B * sizeof(StepOut),
-                           hipMemcpyDeviceToHost, c->stream));
+  // the decision kernel wrote the results straight into pinned host memory
   EC_HIP(c, hipStreamSynchronize(c->stream));
   if (c->prof_on) prof_collect(c);
 
@@ -767,8 +769,11 @@ static int init_impl(ec_ctx** out, const ec_model_cfg* model, const ec_weights* 
     delete c;
     return fail(nullptr, code, msg);
   };
-  hipError_t e = hipHostMalloc((void**)&c->host_out, (size_t)B * sizeof(StepOut), hipHostMallocDefault);
+  hipError_t e = hipHostMalloc((void**)&c->host_out, (size_t)B * sizeof(StepOut), hipHostMallocCoherent);
   if (e != hipSuccess) return bail(EC_ERR_HIP, std::string("hipHostMalloc: ") + hipGetErrorString(e));
+  e = hipHostGetDevicePointer((void**)&c->host_out_dev, c->host_out, 0);
+  if (e != hipSuccess) return bail(EC_ERR_HIP, std::string("hipHostGetDevicePointer: ") + hipGetErrorString(e));
+  memset(c->host_out, 0, (size_t)B * sizeof(StepOut));
   size_t stage = (g.ptot > (size_t)2 * B * EC_MAX_N ? g.ptot : (size_t)2 * B * EC_MAX_N) * sizeof(int);
   e = hipHostMalloc((void**)&c->host_stage, stage, hipHostMallocDefault);
   if (e != hipSuccess) return bail(EC_ERR_HIP, std::string("hipHostMalloc: ") + hipGetErrorString(e));

@@ -52,7 +52,8 @@ struct StepOut {
 // 0; block b moves them by its SeqDesc (x_off) or by b times the per-sequence stride given in the
 // comment, and takes P, T, n_mb, mode_run, n_rows_run, forced_n from its SeqDesc.
 struct DecideArgs {
-  const SeqDesc* seqs;
+  const SeqDesc* seqs;     // NULL: a single sequence, described by seq0 (no table in memory)
+  SeqDesc seq0;
   // this step
   const float4* partials;  // [lm0 + row][nparts] (max, argmax as float bits, sum e, sum e*(z-max))
   int nparts;
@@ -72,7 +73,7 @@ struct DecideArgs {
   int* rows_partial;       // [T] ascending positions of M u R (x_off)
   int* mb_idx;             // [block] index of each block row inside rows_partial (stride block)
   float* row_stats;        // [block][4] token, confidence, entropy, max logit (stride 4*block)
-  StepOut* out;            // (stride 1)
+  StepOut* out;            // (stride 1) pinned host memory, written once by thread 0
   // configuration
   int P, N, T, block, k_recent, n_tok;
   float tau;
@@ -150,7 +151,8 @@ struct GemmEpi {
 // for the first GEMM, the row's sum of squares into sumsq[0..R) and zeros into the nbuf-1
 // further sum buffers (stride sumsq_stride) of the step.  Padding rows get zeros.
 struct StepLists {
-  const SeqDesc* seqs; int B;
+  const SeqDesc* seqs; int B;   // seqs == NULL: a single sequence, described by seq0
+  SeqDesc seq0;
   int R, n_lm;                  // rows of the step (with padding); masked block rows
   const int* x;                 // concatenated by x_off, like rows_partial
   const int* rows_partial;

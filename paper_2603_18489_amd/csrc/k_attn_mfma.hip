@@ -200,6 +200,22 @@ __global__ __launch_bounds__(512) void attn_mfma_split_kernel(
                             real_ ? T : 0, !real_ || ((c_ == nchunks - 1) && (T & 31)));    \
   }
   EC_AT_LOAD(kfa, vfa, 0)
+  // At most three chunks per wave (up to 768 keys per block): a third register set lets every
+  // load be issued before the first multiplication, one trip to memory instead of two in a row.
+  const int rounds = (c_hi - c_lo + NW - 1) / NW;  // block-uniform
+  if (rounds <= 3) {
+    bf16x8 kfc[2][HB], vfc[HT];
+    EC_AT_LOAD(kfb, vfb, 1)
+    EC_AT_LOAD(kfc, vfc, 2)
+    __builtin_amdgcn_sched_barrier(0);
+    // (n_my is wave-uniform and scalar: these are scalar branches around whole MFMA sequences)
+    if (n_my > 0) EC_AT_COMPUTE(kfa, vfa, 0)
+    __builtin_amdgcn_sched_barrier(0);
+    if (n_my > 1) EC_AT_COMPUTE(kfb, vfb, 1)
+    __builtin_amdgcn_sched_barrier(0);
+    if (n_my > 2) EC_AT_COMPUTE(kfc, vfc, 2)
+    __builtin_amdgcn_sched_barrier(0);
+  } else
   for (int i = 0; i < n_my; i += 2) {
     EC_AT_LOAD(kfb, vfb, i + 1)
     __builtin_amdgcn_sched_barrier(0);

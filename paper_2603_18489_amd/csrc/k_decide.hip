@@ -118,7 +118,7 @@ __global__ __launch_bounds__(kDecideThreads) void decide_kernel(DecideArgs a) {
   extern __shared__ int s_dyn[];
   {  // this block's sequence: move the pointers, take the per-sequence scalars
     const int b = blockIdx.x;
-    const SeqDesc sd = a.seqs[b];
+    const SeqDesc sd = a.seqs ? a.seqs[b] : a.seq0;
     if (sd.mode < 0) return;  // finished earlier: no rows in this step, nothing to decide
     a.partials += (size_t)sd.lm0 * a.nparts;
     a.n_mb = sd.n_mb; a.mode_run = sd.mode; a.n_rows_run = sd.n_rows; a.forced_n = sd.forced_n;

@@ -467,6 +467,14 @@ static void launch_skinny_t(const bf16_t* Ap, int MT_src, const void* Wp, int to
   size_t smem = (size_t)KS * NTW * MT * 64 * sizeof(float4) + MT * 16 * sizeof(float);
   if (EPI == EPI_LOGITS) smem += (size_t)NTW * MT * 16 * sizeof(float4);  // per-tile row tuples
   if (W8) smem += NTW * 16 * sizeof(float);                               // weight scales
+  if (smem > 48 * 1024) {
+    static bool once = false;
+    if (!once) {
+      hipFuncSetAttribute((const void*)gemm_bf16_skinny_kernel<EPI, MT, NTW, KS, U, W8>,
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+      once = true;
+    }
+  }
   gemm_bf16_skinny_kernel<EPI, MT, NTW, KS, U, W8><<<grid, KS * 64, smem, s>>>(
       (const u32x4*)Ap, (const u32x4*)Wp, total_nt, KB, MT_src, e);
 }

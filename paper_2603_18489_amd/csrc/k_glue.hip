@@ -43,7 +43,7 @@ __global__ __launch_bounds__(256) void step_prologue_bf16_kernel(
     int4 ri = make_int4(-1, -1, 0, 32);
     int4 ti = make_int4(0, 0, 32, 0);
     for (int b = 0; b < L.B; ++b) {
-      const SeqDesc sd = L.seqs[b];
+      const SeqDesc sd = L.seqs ? L.seqs[b] : L.seq0;
       if (sd.mode < 0 || r < sd.row0 || r >= sd.row0 + sd.seg_rows) continue;
       const int i = r - sd.row0;
       int pos = -1;
@@ -56,7 +56,7 @@ __global__ __launch_bounds__(256) void step_prologue_bf16_kernel(
     sh_xidx = ri.y;
     if (r < L.n_lm) {
       for (int b = 0; b < L.B; ++b) {
-        const SeqDesc sd = L.seqs[b];
+        const SeqDesc sd = L.seqs ? L.seqs[b] : L.seq0;
         if (sd.mode < 0 || r < sd.lm0 || r >= sd.lm0 + sd.n_mb) continue;
         const int i = b * L.block + (r - sd.lm0);
         L.lm_sel[r] = sd.row0 + (sd.mode == EC_FULL ? L.mb_pos[i] : L.mb_idx[i]);
