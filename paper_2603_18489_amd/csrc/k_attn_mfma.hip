@@ -124,16 +124,22 @@ __device__ __forceinline__ float2 ld_agent(const float* p) {
   return make_float2(c.f[0], c.f[1]);
 }
 
-template <int HD>
+//
+// HS > 1 also splits the head dimension of the OUTPUT over HS blocks: each of them computes the
+// whole score tile (it needs all of K) but multiplies only its HD/HS columns of V and stores only
+// those, so nothing has to be merged across blocks.  A compute unit pulls only so many bytes
+// per microsecond; with few blocks in the grid this spreads V over more of them.
+template <int HD, int HS>
 __global__ __launch_bounds__(512) void attn_mfma_split_kernel(
     const bf16_t* __restrict__ q, const au32x4* __restrict__ kp, const au32x4* __restrict__ vp,
     int R, const int4* __restrict__ rowinfo, const int4* __restrict__ pairs, int npairs,
     int4 one_seq, int Hq, int Hkv, float scale_log2e, bf16_t* __restrict__ out, AttnSplit sp) {
-  constexpr int HB = HD / 32, HT = HD / 16, NW = 8;
+  constexpr int HB = HD / 32, HT = HD / 16 / HS, NW = 8;  // HT: hd tiles of V / the output here
   extern __shared__ float4 lds[];
   // scalar wave index: no MFMA may sit under a condition the compiler could treat as divergent
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int kvh = blockIdx.x, G = Hq / Hkv, MT = (R + 15) >> 4;
+  const int by = blockIdx.y / HS, h0 = (blockIdx.y % HS) * HT;  // (visit, head of the group); first hd tile
   // The block's (row tile, sequence) pair: the few-row sequences are packed into the row list
   // without padding, so a tile can hold rows of two of them; it is then visited once for each,
   // and a visit serves only the rows of its own sequence.  pairs == NULL: a single sequence,
@@ -141,11 +147,11 @@ __global__ __launch_bounds__(512) void attn_mfma_split_kernel(
   int mt, gq;
   int4 ti;
   if (pairs) {
-    const int4 pr = pairs[blockIdx.y % npairs];
-    mt = pr.x; gq = blockIdx.y / npairs;
+    const int4 pr = pairs[by % npairs];
+    mt = pr.x; gq = by / npairs;
     ti = make_int4(pr.y, pr.z, pr.w, 0);
   } else {
-    mt = blockIdx.y % MT; gq = blockIdx.y / MT;
+    mt = by % MT; gq = by / MT;
     ti = one_seq;
     if (ti.w != 0) return;  // a many-row sequence: the other kernel's
   }
@@ -190,7 +196,7 @@ __global__ __launch_bounds__(512) void attn_mfma_split_kernel(
       _Pragma("unroll") for (int hb = 0; hb < HB; ++hb)                                     \
         KF[t2][hb] = av4_as_bf16x8(kbase[((size_t)(c_ * 2 + t2) * HB + hb) * 64]);          \
     _Pragma("unroll") for (int h = 0; h < HT; ++h)                                          \
-      VF[h] = av4_as_bf16x8(vbase[((size_t)h * KB32 + c_) * 64]);                           \
+      VF[h] = av4_as_bf16x8(vbase[((size_t)(h0 + h) * KB32 + c_) * 64]);                    \
   }
 #define EC_AT_COMPUTE(KF, VF, I)                                                            \
   {                                                                                         \
@@ -271,13 +277,15 @@ __global__ __launch_bounds__(512) void attn_mfma_split_kernel(
       // lane holds hd rows h*16 + grp*4 .. +3 of query qcol
       const float inv = 1.0f / l_all;
       uint2 pk = make_uint2(pack2_bf16(o.x * inv, o.y * inv), pack2_bf16(o.z * inv, o.w * inv));
-      if (qvalid) *(uint2*)(out + packed_act_index(qrow, qhead * HD + h * 16 + grp * 4, MT)) = pk;
+      if (qvalid) *(uint2*)(out + packed_act_index(qrow, qhead * HD + (h0 + h) * 16 + grp * 4, MT)) = pk;
     } else {
       st_agent(mine + (h * 64 + lane) * 4, o.x, o.y);
       st_agent(mine + (h * 64 + lane) * 4 + 2, o.z, o.w);
     }
   }
   if (nz == 1) return;
+  static_assert(HS == 1 || HD % (16 * HS) == 0, "whole hd tiles per block");
+  // (key slices over blocks are only launched with HS == 1: the piece layout below assumes it)
 
   // ---- cross-block: leave (m, l), draw a ticket, the last block of the pair finishes ---------
   // Ordering: every thread's pieces happen-before the block barrier (work-group scope); thread
@@ -452,7 +460,7 @@ static void launch_attn_mfma_hd(const bf16_t* q, const uint4* kp, const uint4* v
     constexpr size_t smem = 8 * SLOT * sizeof(float4);
     static bool attr_set = false;
     if (smem > 48 * 1024 && !attr_set) {
-      (void)hipFuncSetAttribute((const void*)attn_mfma_split_kernel<HD>,
+      (void)hipFuncSetAttribute((const void*)attn_mfma_split_kernel<HD, 1>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
       attr_set = true;
     }
@@ -474,9 +482,20 @@ static void launch_attn_mfma_hd(const bf16_t* q, const uint4* kp, const uint4* v
     AttnSplit sp;
     sp.part = part;
     sp.tickets = tickets;
-    attn_mfma_split_kernel<HD><<<dim3(Hkv, G * nvis, nz), 512, smem, s>>>(
-        q, (const au32x4*)kp, (const au32x4*)vp, R, rowinfo, pairs, npairs, one_seq, Hq, Hkv, sc,
-        out, sp);
+    // output columns over blocks while the grid stays within the chip's 256 compute units
+    int hs = 1;
+    if (nz == 1)
+      while (hs < 8 && hs * 2 <= HD / 16 && blocks1 * hs * 2 <= 256) hs *= 2;
+#define EC_SPLIT_LAUNCH(HS_)                                                                     \
+  attn_mfma_split_kernel<HD, HS_><<<dim3(Hkv, G * nvis * HS_, nz), 512,                          \
+                                    8 * ((HD / 16 / HS_) * 64 + 32) * sizeof(float4), s>>>(      \
+      q, (const au32x4*)kp, (const au32x4*)vp, R, rowinfo, pairs, npairs, one_seq, Hq, Hkv, sc,  \
+      out, sp)
+    if (hs == 8) { if constexpr (HD >= 128) EC_SPLIT_LAUNCH(8); }
+    else if (hs == 4) EC_SPLIT_LAUNCH(4);
+    else if (hs == 2) EC_SPLIT_LAUNCH(2);
+    else EC_SPLIT_LAUNCH(1);
+#undef EC_SPLIT_LAUNCH
   }
   if (has_large) {
     // two query tiles per wave halve the LDS reads per MFMA, but only pay once the grid still
