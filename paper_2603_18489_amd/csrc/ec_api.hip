@@ -237,6 +237,7 @@ struct ec_ctx {
   Buffers b;
   StepOut* host_out = nullptr;   // pinned [B]: the decision kernel writes its results here
   StepOut* host_out_dev = nullptr;  // the same memory as the device addresses it
+  int serial = 0;                   // number of the last decision launch (StepOut::serial)
   int* host_stage = nullptr;     // pinned: prompts / forced lists on their way to the device
   SeqDesc* host_seqs = nullptr;  // pinned [B]
   int4* host_pairs = nullptr;    // pinned [rmax/16 + B]
@@ -321,6 +322,28 @@ void fill_decide_args(ec_ctx* c, DecideArgs& a) {
   a.n_tok = c->d.tokens_per_step; a.tau = c->d.tau;
   a.conf_threshold = c->d.conf_threshold; a.gate_metric = c->d.gate_metric;
   a.schedule = c->d.schedule;
+  a.serial = c->serial = (c->serial == 0x7fffffff ? 1 : c->serial + 1);
+}
+
+// Waits for the decision kernel's results.  Every taking-part sequence's block stores the
+// launch's serial number behind its result (system-scope release), so the host can take the
+// result as soon as the numbers show up instead of waiting for the stream to drain and the
+// runtime to notice; later work is ordered behind the kernel by the stream anyway.  The poll is
+// bounded: the stream is queried now and then, and once it has drained (or failed) the ordinary
+// synchronisation decides.
+int wait_results(ec_ctx* c, const int* taking_part) {
+  const int B = c->B;
+  for (unsigned spin = 1;; ++spin) {
+    bool all = true;
+    for (int b = 0; b < B && all; ++b)
+      if (!taking_part || taking_part[b] >= 0)
+        all = __atomic_load_n(&c->host_out[b].serial, __ATOMIC_ACQUIRE) == c->serial;
+    if (all) return EC_OK;
+    if ((spin & 0xfff) == 0 && hipStreamQuery(c->stream) != hipErrorNotReady) break;
+    __builtin_ia32_pause();
+  }
+  EC_HIP(c, hipStreamSynchronize(c->stream));
+  return EC_OK;
 }
 
 // static part of a sequence's descriptor
@@ -608,9 +631,14 @@ int run_step(ec_ctx* c, const int32_t* modes, int modes_n, const int32_t* forced
   fill_decide_args(c, a);
   { Scope p(c, EC_K_DECIDE); launch_decide(a, B, c->stream); }
   EC_HIP(c, hipGetLastError());
-  // the decision kernel wrote the results straight into pinned host memory
-  EC_HIP(c, hipStreamSynchronize(c->stream));
-  if (c->prof_on) prof_collect(c);
+  // the decision kernel writes the results straight into pinned host memory
+  if (c->prof_on) {
+    EC_HIP(c, hipStreamSynchronize(c->stream));
+    prof_collect(c);
+  } else {
+    int rcw = wait_results(c, mode.data());
+    if (rcw != EC_OK) return rcw;
+  }
 
   // ---- mirror the new state ------------------------------------------------------------------------
   c->steps_run += 1;
@@ -621,6 +649,7 @@ int run_step(ec_ctx* c, const int32_t* modes, int modes_n, const int32_t* forced
   if (forced_n) {
     // the flags follow the committed tokens; the device computed them, mirror them from its state
     st.resize(B);
+    EC_HIP(c, hipStreamSynchronize(c->stream));
     EC_HIP(c, hipMemcpy(st.data(), c->b.st, (size_t)B * sizeof(DevState), hipMemcpyDeviceToHost));
   }
   int all_done = 1;

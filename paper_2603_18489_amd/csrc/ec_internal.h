@@ -45,7 +45,8 @@ struct StepOut {
   ec_step_result r;
   int next_n_mb;
   int next_n_rows_partial;
-  int pad[6];
+  int serial;   // the launch's DecideArgs::serial once everything above has been written
+  int pad[5];
 };
 
 // Arguments of the decision kernel: one block per sequence.  The pointers are those of sequence
@@ -80,6 +81,7 @@ struct DecideArgs {
   float conf_threshold;    // 0 = fixed n_tok per step
   int gate_metric;         // EC_GATE_*
   int schedule;            // EC_SCHED_*
+  int serial;              // written to StepOut::serial as the block's very last store (> 0)
 };
 
 // thread-local message behind ec_last_error(NULL)

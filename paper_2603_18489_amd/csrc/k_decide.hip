@@ -378,6 +378,11 @@ __global__ __launch_bounds__(kDecideThreads) void decide_kernel(DecideArgs a) {
       o.r.n_block_rows = a.n_mb;
       o.r.n_recent_next = n_recent;
     }
+    // The result sits in pinned host memory.  The other threads' entries were stored before the
+    // barriers above; this fence orders them and the fields above before the serial number, so
+    // a host that sees the number sees the whole result.
+    __threadfence_system();
+    __hip_atomic_store(&o.serial, a.serial, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
   }
 }
 
