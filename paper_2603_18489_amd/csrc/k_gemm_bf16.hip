@@ -483,11 +483,12 @@ static void launch_skinny_t(const bf16_t* Ap, int MT_src, const void* Wp, int to
 // delivers (weights once + the activation fragments once per block), so more weight tiles per
 // block (fewer re-reads of the activations) win as long as the grid still covers the 256 CUs.
 // blocks (= partial tuples per row) of the skinny LM-head GEMM over a vocabulary of V columns
-int lm_head_parts(int V) { return (V / 16 + 3) / 4; }
+constexpr int kLmTiles = 8;  // weight tiles (of 16 vocabulary columns) per LM-head block
+int lm_head_parts(int V) { return (V / 16 + kLmTiles - 1) / kLmTiles; }
 
 int skinny_tiles_per_block(int epi, int total_nt) {
   if (epi == EPI_RESID) return 1;
-  if (epi == EPI_LOGITS) return 4;
+  if (epi == EPI_LOGITS) return kLmTiles;
   if (total_nt >= 6 * 256) return 6;
   if (total_nt >= 3 * 256) return 3;
   return total_nt >= 2 * 256 ? 2 : 1;
@@ -499,7 +500,7 @@ template <int EPI, int MT>
 static void launch_skinny_mt_w8(const bf16_t* Ap, int MT_src, const void* Wq, int total_nt,
                                 int KB, const GemmEpi& e, hipStream_t s) {
   if constexpr (EPI == EPI_LOGITS) {
-    launch_skinny_t<EPI, MT, 4, 4, 2, true>(Ap, MT_src, Wq, total_nt, KB, e, s);
+    launch_skinny_t<EPI, MT, kLmTiles, 4, 1, true>(Ap, MT_src, Wq, total_nt, KB, e, s);
   } else if constexpr (EPI == EPI_RESID) {
     launch_skinny_t<EPI, MT, 1, 8, (MT > 3 ? 1 : 2), true>(Ap, MT_src, Wq, total_nt, KB, e, s);
   } else {
@@ -517,7 +518,7 @@ template <int EPI, int MT>
 static void launch_skinny_mt(const bf16_t* Ap, int MT_src, const bf16_t* Wp, int total_nt, int KB,
                              const GemmEpi& e, hipStream_t s) {
   if constexpr (EPI == EPI_LOGITS) {
-    launch_skinny_t<EPI, MT, 4, 4, 4>(Ap, MT_src, Wp, total_nt, KB, e, s);
+    launch_skinny_t<EPI, MT, kLmTiles, 4, (MT > 2 ? 1 : 2)>(Ap, MT_src, Wp, total_nt, KB, e, s);
   } else if constexpr (EPI == EPI_RESID) {
     launch_skinny_t<EPI, MT, 1, 8, 2>(Ap, MT_src, Wp, total_nt, KB, e, s);
   } else {
