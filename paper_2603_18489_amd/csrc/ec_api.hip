@@ -120,7 +120,7 @@ void carve(Carver& c, const ec_model_cfg& m, const ec_decode_cfg& d, const Geome
   b.forced_tok = c.take<int>((size_t)B * EC_MAX_N); b.prompt = c.take<int>(g.ptot);
   b.seqs = c.take<SeqDesc>(B); b.rowinfo = c.take<int4>(R); b.tileinfo = c.take<int4>(R / 16);
   b.lm_sel = c.take<int>(BL);
-  b.pairs = c.take<int4>(R / 16 + B);
+  b.pairs = c.take<int4>(R / 16 + 2 * B);   // [B sequence entries][visits]
   b.rope_cs = c.take<float2>((size_t)g.tmax * (m.head_dim / 2));
   b.kv_plane = g.kv_plane;
   b.kv = c.take<char>((size_t)m.n_layers * 2 * g.kv_plane * es);
@@ -400,6 +400,7 @@ struct StepPlan {
   bool has_small = false, has_large = false;
   int max_T_small = 1;
   int npairs = 0;                           // (row tile, sequence) visits of few-row sequences
+  int nsmall = 0, max_visits = 0;           // few-row sequences; most visits of one of them
   bool single = false;                      // one sequence takes part: one_seq is its tile entry
   int4 one_seq = make_int4(0, 0, 32, 0);
   int64_t rows = 0;                         // sum of the sequences' own row counts
@@ -483,9 +484,10 @@ int forward_bf16(ec_ctx* c, const StepPlan& sp) {
       launch_gemm_bf16(EPI_QKV, u, R, b.pl[l].wqkv, b.pl[l].qqkv, nqkv, d, e, s); }
     { Scope p(c, EC_K_ATTN);
       launch_attention_mfma(q, kc, vc, R, b.rowinfo, sp.single ? nullptr : b.tileinfo,
-                            sp.single ? nullptr : b.pairs, sp.npairs, sp.one_seq, sp.has_small,
-                            sp.has_large, sp.max_T_small, m.n_heads, m.n_kv_heads, hd, attn,
-                            b.ksplit_part, b.ksplit_floats, b.attn_tickets, s); }
+                            sp.single ? nullptr : b.pairs + c->B, sp.npairs,
+                            sp.single ? nullptr : b.pairs, sp.nsmall, sp.max_visits, sp.one_seq,
+                            sp.has_small, sp.has_large, sp.max_T_small, m.n_heads, m.n_kv_heads, hd,
+                            attn, b.ksplit_part, b.ksplit_floats, b.attn_tickets, s); }
     { Scope p(c, EC_K_OPROJ);
       GemmEpi e{}; e.M = M; e.MT = MT; e.h = b.h; e.d = d; e.gain_next = G(c->mlp_norm[l]);
       e.a_next = u; e.sumsq_out = sums(2 * l + 1); e.sum_stride = b.sumsq_stride;
@@ -583,9 +585,15 @@ int run_step(ec_ctx* c, const int32_t* modes, int modes_n, const int32_t* forced
       sd.mode = mode[b]; sd.n_rows = n_rows; sd.row0 = sp.R;
       sd.seg_rows = large ? seg_rows_of(n_rows) : n_rows;   // few-row sequences: back to back
       sd.n_mb = c->n_mb[b]; sd.forced_n = fn;
-      if (!large)
+      if (!large) {
+        // the table starts with one entry per few-row sequence (its first visit, how many),
+        // the visits follow from entry B on
+        const int first = sp.npairs;
         for (int mt = sd.row0 / 16; mt <= (sd.row0 + n_rows - 1) / 16; ++mt)
-          c->host_pairs[sp.npairs++] = make_int4(mt, sd.kv_off, sd.T, sd.tpad);
+          c->host_pairs[B + sp.npairs++] = make_int4(mt, sd.kv_off, sd.T, sd.tpad);
+        c->host_pairs[sp.nsmall++] = make_int4(first, sp.npairs - first, 0, 0);
+        if (sp.npairs - first > sp.max_visits) sp.max_visits = sp.npairs - first;
+      }
       sp.R += sd.seg_rows; sp.rows += n_rows;
       (large ? sp.has_large : sp.has_small) = true;
       if (!large && c->g.T[b] > sp.max_T_small) sp.max_T_small = c->g.T[b];
@@ -606,7 +614,7 @@ int run_step(ec_ctx* c, const int32_t* modes, int modes_n, const int32_t* forced
   sp.single = sp.n_full + sp.n_partial == 1;
   sp.R = (sp.R + 15) / 16 * 16;
   if (!sp.single && sp.npairs > 0)
-    EC_HIP(c, hipMemcpyAsync(c->b.pairs, c->host_pairs, (size_t)sp.npairs * sizeof(int4),
+    EC_HIP(c, hipMemcpyAsync(c->b.pairs, c->host_pairs, (size_t)(B + sp.npairs) * sizeof(int4),
                              hipMemcpyHostToDevice, c->stream));
   if (B > 1)
     EC_HIP(c, hipMemcpyAsync(c->b.seqs, c->host_seqs, (size_t)B * sizeof(SeqDesc),
@@ -808,7 +816,7 @@ static int init_impl(ec_ctx** out, const ec_model_cfg* model, const ec_weights* 
   if (e != hipSuccess) return bail(EC_ERR_HIP, std::string("hipHostMalloc: ") + hipGetErrorString(e));
   e = hipHostMalloc((void**)&c->host_seqs, (size_t)B * sizeof(SeqDesc), hipHostMallocDefault);
   if (e != hipSuccess) return bail(EC_ERR_HIP, std::string("hipHostMalloc: ") + hipGetErrorString(e));
-  e = hipHostMalloc((void**)&c->host_pairs, (g.rmax / 16 + B) * sizeof(int4), hipHostMallocDefault);
+  e = hipHostMalloc((void**)&c->host_pairs, (g.rmax / 16 + 2 * B) * sizeof(int4), hipHostMallocDefault);
   if (e != hipSuccess) return bail(EC_ERR_HIP, std::string("hipHostMalloc: ") + hipGetErrorString(e));
 
   // one-time device set-up: RoPE table, re-tiled bf16 matrices, finite padding keys

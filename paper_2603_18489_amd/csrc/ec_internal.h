@@ -210,7 +210,8 @@ void launch_repack_rows_f32(const float* src, int N, float* dst, int mode, int h
 // most positions of any few-row sequence taking part.
 void launch_attention_mfma(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int R,
                            const int4* rowinfo, const int4* tileinfo, const int4* pairs,
-                           int npairs, int4 one_seq, bool has_small, bool has_large, int max_T,
+                           int npairs, const int4* seqtab, int nsmall, int max_visits,
+                           int4 one_seq, bool has_small, bool has_large, int max_T,
                            int Hq, int Hkv, int hd, bf16_t* out, float* part, size_t part_floats,
                            int* tickets, hipStream_t s);
 

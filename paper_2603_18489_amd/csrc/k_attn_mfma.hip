@@ -338,11 +338,19 @@ template <int N> __device__ __forceinline__ void attn_wait_vmcnt() {
 // Chunks of the LDS ring (a deeper ring was measured: no gain, the loop is not waiting on loads).
 constexpr int kAttnStages = 3;
 
-template <int HD, int QT, int NW>
+//
+// FEW: the same ring for a batch of few-row sequences.  A block then owns one (sequence, query
+// head): wave w serves the sequence's w-th row-tile visit (the packed row list lets a tile hold
+// rows of two sequences; a visit serves only its own sequence's rows and stores nothing else),
+// waves without a visit only help with the loads.  The sequence's K/V are read once per head
+// instead of once per visit, which is what bounds a batch's partial step.
+template <int HD, int QT, int NW, bool FEW = false>
 __global__ __launch_bounds__(NW * 64) void attn_mfma_shared_kernel(
     const bf16_t* __restrict__ q, const au32x4* __restrict__ kp, const au32x4* __restrict__ vp,
     int R, const int4* __restrict__ rowinfo, const int4* __restrict__ tileinfo, int4 one_seq,
-    int Hq, int Hkv, float scale_log2e, bf16_t* __restrict__ out) {
+    int Hq, int Hkv, float scale_log2e, bf16_t* __restrict__ out,
+    const int4* __restrict__ pairs, const int4* __restrict__ seqtab, int nsmall) {
+  static_assert(!FEW || QT == 1, "one visit per wave");
   constexpr int HB = HD / 32, HT = HD / 16, NSTAGE = kAttnStages;
   constexpr int NFRAG = 2 * HB + HT, LF = NFRAG / NW;
   static_assert(NFRAG % NW == 0, "fragments per chunk must divide over the waves");
@@ -353,14 +361,27 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_shared_kernel(
   const int kvh = blockIdx.x, G = Hq / Hkv, MT = (R + 15) >> 4, MTp = (MT + 15) & ~15;
   // the block's NW*QT query tiles: one head of the group, consecutive row tiles that all lie in
   // one many-row sequence (such sequences come first and are padded to 16 row tiles) or in none
-  const int t_first = blockIdx.y * NW * QT;
-  const int gq = t_first / MTp, mt_first = t_first - gq * MTp;
-  if (mt_first >= MT) return;
-  const int4 ti = tileinfo ? tileinfo[mt_first] : one_seq;
-  if (ti.w == 0) return;  // few-row sequences belong to the other kernel
+  int gq, mt0;
+  int4 ti;
+  bool active = true;  // (wave-uniform) this wave has query rows to serve
+  if constexpr (FEW) {
+    gq = blockIdx.y / nsmall;
+    const int4 se = seqtab[blockIdx.y - gq * nsmall];  // first visit, number of visits (<= NW)
+    const int4 p0 = pairs[se.x];
+    ti = make_int4(p0.y, p0.z, p0.w, 1);
+    active = __builtin_amdgcn_readfirstlane(wave < se.y ? 1 : 0) != 0;
+    mt0 = __builtin_amdgcn_readfirstlane(pairs[se.x + (wave < se.y ? wave : 0)].x);
+  } else {
+    const int t_first = blockIdx.y * NW * QT;
+    gq = t_first / MTp;
+    const int mt_first = t_first - gq * MTp;
+    if (mt_first >= MT) return;
+    ti = tileinfo ? tileinfo[mt_first] : one_seq;
+    if (ti.w == 0) return;  // few-row sequences belong to the other kernels
+    mt0 = mt_first + wave * QT;
+  }
   const int T = ti.y, Tpad = ti.z;
   const int nchunks = (T + 31) >> 5, KB32 = Tpad >> 5;
-  const int mt0 = mt_first + wave * QT;
   const int qcol = lane & 15, grp = lane >> 4;
 
   // fragment f of a chunk: f < 2*HB is K tile f / HB, hd block f % HB; the rest are V^T hd tiles
@@ -388,7 +409,9 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_shared_kernel(
 #pragma unroll
   for (int t = 0; t < QT; ++t) {
     qrow[t] = (mt0 + t) * 16 + qcol;
-    qvalid[t] = qrow[t] < R && rowinfo[qrow[t] < R ? qrow[t] : 0].x >= 0;
+    const int4 qri = rowinfo[qrow[t] < R ? qrow[t] : 0];
+    qvalid[t] = qrow[t] < R && qri.x >= 0;
+    if constexpr (FEW) qvalid[t] = qvalid[t] && active && qri.z == ti.x;  // a row of this sequence
 #pragma unroll
     for (int hb = 0; hb < HB; ++hb) {
       uint4 v = make_uint4(0, 0, 0, 0);
@@ -424,10 +447,12 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_shared_kernel(
 
     const int key0 = c * 32 + grp * 8;
     const bool mask_tail = (c == nchunks - 1) && (T & 31);
+    if (active) {  // (a scalar branch around whole MFMA sequences)
 #pragma unroll
-    for (int t = 0; t < QT; ++t)
-      attn_chunk_tile<HB, HT>(kf, vf, qf[t], acc[t], m_run[t], l_run[t], scale_log2e, key0, T,
-                              mask_tail);
+      for (int t = 0; t < QT; ++t)
+        attn_chunk_tile<HB, HT>(kf, vf, qf[t], acc[t], m_run[t], l_run[t], scale_log2e, key0, T,
+                                mask_tail);
+    }
   }
   attn_wait_vmcnt<0>();  // drain the clamped tail loads before the LDS goes away
 
@@ -441,7 +466,8 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_shared_kernel(
       uint2 pk = make_uint2(pack2_bf16(a[0] * inv, a[1] * inv), pack2_bf16(a[2] * inv, a[3] * inv));
       if (!qvalid[t]) pk = make_uint2(0u, 0u);  // padding rows read as zeros downstream
       int k = qhead * HD + h * 16 + grp * 4;
-      *(uint2*)(out + packed_act_index(qrow[t], k, MT)) = pk;
+      // (FEW: the other rows of the tile belong to a neighbour sequence's visit)
+      if (!FEW || qvalid[t]) *(uint2*)(out + packed_act_index(qrow[t], k, MT)) = pk;
     }
   }
 }
@@ -449,12 +475,29 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_shared_kernel(
 template <int HD>
 static void launch_attn_mfma_hd(const bf16_t* q, const uint4* kp, const uint4* vp, int R,
                                 const int4* rowinfo, const int4* tileinfo, const int4* pairs,
-                                int npairs, int4 one_seq, bool has_small, bool has_large,
+                                int npairs, const int4* seqtab, int nsmall, int max_visits,
+                                int4 one_seq, bool has_small, bool has_large,
                                 int max_T, int Hq, int Hkv, bf16_t* out, float* part,
                                 size_t part_floats, int* tickets, hipStream_t s) {
   const int G = Hq / Hkv, MT = (R + 15) / 16;
   const float sc = 1.4426950408889634f / sqrtf((float)HD);
-  if (has_small) {
+  constexpr int kRingFrag = 2 * (HD / 32) + HD / 16;
+  constexpr size_t kRingBytes = (size_t)kAttnStages * kRingFrag * 1024;
+  // A batch of few-row sequences whose rows spread over several row tiles each: one block per
+  // (sequence, head) that reads the sequence's K/V once, provided that fills the chip.
+  const bool few_shared = has_small && pairs && seqtab && nsmall > 0 && max_visits <= 8 &&
+                          npairs >= 2 * nsmall && (long)nsmall * Hq >= 256;
+  if (few_shared) {
+    static bool few_attr_set = false;
+    if (kRingBytes > 48 * 1024 && !few_attr_set) {
+      (void)hipFuncSetAttribute((const void*)attn_mfma_shared_kernel<HD, 1, 8, true>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kRingBytes);
+      few_attr_set = true;
+    }
+    attn_mfma_shared_kernel<HD, 1, 8, true><<<dim3(Hkv, G * nsmall), 512, kRingBytes, s>>>(
+        q, (const au32x4*)kp, (const au32x4*)vp, R, rowinfo, tileinfo, one_seq, Hq, Hkv, sc, out,
+        pairs, seqtab, nsmall);
+  } else if (has_small) {
     // sequences with few rows: one block per query tile, the keys split over its waves
     constexpr int SLOT = (HD / 16) * 64 + 32;
     constexpr size_t smem = 8 * SLOT * sizeof(float4);
@@ -515,29 +558,30 @@ static void launch_attn_mfma_hd(const bf16_t* q, const uint4* kp, const uint4* v
       dim3 grid(Hkv, tiles / (2 * NW));
       attn_mfma_shared_kernel<HD, 2, NW><<<grid, NW * 64, ring_bytes, s>>>(
           q, (const au32x4*)kp, (const au32x4*)vp, R, rowinfo, tileinfo, one_seq, Hq, Hkv, sc,
-          out);
+          out, nullptr, nullptr, 0);
     } else {
       dim3 grid(Hkv, tiles / NW);
       attn_mfma_shared_kernel<HD, 1, NW><<<grid, NW * 64, ring_bytes, s>>>(
           q, (const au32x4*)kp, (const au32x4*)vp, R, rowinfo, tileinfo, one_seq, Hq, Hkv, sc,
-          out);
+          out, nullptr, nullptr, 0);
     }
   }
 }
 
 void launch_attention_mfma(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int R,
                            const int4* rowinfo, const int4* tileinfo, const int4* pairs,
-                           int npairs, int4 one_seq, bool has_small, bool has_large, int max_T,
+                           int npairs, const int4* seqtab, int nsmall, int max_visits,
+                           int4 one_seq, bool has_small, bool has_large, int max_T,
                            int Hq, int Hkv, int hd, bf16_t* out, float* part, size_t part_floats,
                            int* tickets, hipStream_t s) {
   if (R <= 0) return;
   if (hd == 64)
     launch_attn_mfma_hd<64>(q, (const uint4*)kc, (const uint4*)vc, R, rowinfo, tileinfo, pairs,
-                            npairs, one_seq,
+                            npairs, seqtab, nsmall, max_visits, one_seq,
                             has_small, has_large, max_T, Hq, Hkv, out, part, part_floats, tickets, s);
   else
     launch_attn_mfma_hd<128>(q, (const uint4*)kc, (const uint4*)vc, R, rowinfo, tileinfo, pairs,
-                             npairs, one_seq,
+                             npairs, seqtab, nsmall, max_visits, one_seq,
                              has_small, has_large, max_T, Hq, Hkv, out, part, part_floats, tickets,
                              s);
 }

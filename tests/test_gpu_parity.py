@@ -184,6 +184,21 @@ def test_largest_batch():
     assert s["tokens_exact"] > 0 and s["rows_decided"] > 0 and s["modes_exact"] > 0
 
 
+def test_many_few_row_sequences_one_attention_block_per_sequence_and_head():
+    """32 ragged sequences x 8 heads whose partial steps recompute up to 36 rows each: the row
+    list packs them back to back (a 16-row tile holds rows of two or three sequences), and the
+    batch is large enough that the attention serves all row tiles of a (sequence, head) from one
+    block that reads the sequence's K/V once.  Every sequence against its own oracle run."""
+    cfg = small_cfg("bf16", 8, 4, 64, scale=13.0)
+    w = ec_inputs.make_weights(cfg, 59, gain_jitter=0.1)
+    B = 32
+    dec = ec_inputs.DecodeCfg(gen_len=40, block=32, k_recent=4, tokens_per_step=2, tau=1e9, batch=B)
+    prompts = [ec_inputs.make_prompt(cfg.vocab, 5 + (11 * b) % 57, 500 + b) for b in range(B)]
+    s = run_teacher_forced_batch(cfg, w, dec, prompts, TOL["bf16"], max_steps=7, check_cache_every=3)
+    print(s)
+    assert s["modes"][eco.PARTIAL] == 6 * B and s["tokens_exact"] > 0
+
+
 def test_batched_generate_runs_every_sequence_to_the_end():
     """ec_generate on a batch: free-running, sequences in different modes side by side; every
     generation slot ends up decoded, the counters add up, and a reset reproduces the run."""
