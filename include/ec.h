@@ -66,7 +66,11 @@ enum {
   EC_ERR_WORKSPACE = -3, /* workspace missing, misaligned or smaller than ec_workspace_bytes()  */
   EC_ERR_STATE = -4,     /* PARTIAL before any FULL step; step after the generation is done     */
   EC_ERR_HIP = -5,       /* a HIP runtime call failed                                           */
-  EC_ERR_HOST_MEMORY = -6 /* the host ran out of memory inside the call; the context is unusable */
+  EC_ERR_HOST_MEMORY = -6, /* the host ran out of memory inside the call; the context is unusable */
+  EC_ERR_NONFINITE = -7  /* a block row's logits had no finite maximum (NaN weights, overflow):
+                            the step ran to its end and stayed inside its buffers - such a row
+                            reports token 0, confidence 0 and infinite entropy - but what it
+                            computed is meaningless; ec_reset() before going on               */
 };
 
 /* Model shape.  "Bidirectional Llama-style": pre-norm blocks, RMSNorm, rotate-half RoPE on
@@ -225,8 +229,11 @@ int ec_reset(ec_ctx *ctx, const int32_t *prompt_ids /*HOST*/);
  * out: HOST, batch ec_step_result, written on success only; a sequence that had finished earlier
  * reports done = 1 and zeros.
  * Errors: EC_ERR_ARG (NULL, bad mode), EC_ERR_STATE (every sequence finished; EC_PARTIAL for a
- * sequence that has not run a FULL step yet) - the state is untouched then - and EC_ERR_HIP.
- * Synchronises the stream once, for the read-back. */
+ * sequence that has not run a FULL step yet) - the state is untouched then - EC_ERR_HIP, and
+ * EC_ERR_NONFINITE: some block row's logits had no finite maximum.  That step has run and the
+ * state has advanced (no access left its buffers: the row took token 0), out is written, but
+ * nothing computed from then on means anything; ec_reset() the context.
+ * Waits once, for the results (which the decision kernel leaves in pinned host memory). */
 int ec_step(ec_ctx *ctx, int mode, ec_step_result *out);
 
 /* Teacher forcing: runs the forward pass and the vocabulary reduction in `mode`, reports the
@@ -272,7 +279,9 @@ int ec_debug_read_seq(ec_ctx *ctx, int seq, int what, int layer, void *host_dst,
  * of a float32 matrix, stats[row] = (argmax token id as a float, lowest id on ties; confidence =
  * maximum softmax probability; entropy -sum p ln p in nats; maximum logit).  One pass over the
  * logits; partial (max, argmax, sum e, sum e*(z-max)) tuples per 2048 columns are merged in a
- * fixed order, so the result is bit-reproducible.  A logit of -inf has probability 0.
+ * fixed order, so the result is bit-reproducible.  A logit of -inf has probability 0.  A row
+ * that holds a NaN reports NaN statistics, and a token id outside [0, vocab) if it has no
+ * finite maximum at all: check before using it as an index.
  *  logits     DEVICE float32 [rows, vocab], row stride ld elements (ld >= vocab); read only
  *  rows       0 .. EC_MAX_BLOCK; vocab 2 .. 163840
  *  stats      DEVICE float32 [rows, 4], 16-byte aligned; written

@@ -21,6 +21,7 @@ EC_GATE_MAX_ENTROPY, EC_GATE_ENTROPY_SUM, EC_GATE_MAX_CONFIDENCE = 0, 1, 2
 EC_SCHED_BLOCKS, EC_SCHED_SLIDING = 0, 1
 EC_OK, EC_ERR_ARG, EC_ERR_CONFIG, EC_ERR_WORKSPACE, EC_ERR_STATE, EC_ERR_HIP = 0, -1, -2, -3, -4, -5
 EC_ERR_HOST_MEMORY = -6
+EC_ERR_NONFINITE = -7
 (EC_K_EMBED, EC_K_NORM, EC_K_QKV, EC_K_ROPE_KV, EC_K_ATTN, EC_K_OPROJ, EC_K_GATEUP, EC_K_SWIGLU,
  EC_K_DOWN, EC_K_LMHEAD, EC_K_VOCAB_REDUCE, EC_K_DECIDE, EC_K_COUNT) = range(13)
 KERNEL_CLASS_NAMES = ["embed", "norm", "qkv", "rope_kv", "attn", "oproj", "gateup", "swiglu",

@@ -322,6 +322,7 @@ void fill_decide_args(ec_ctx* c, DecideArgs& a) {
   a.n_tok = c->d.tokens_per_step; a.tau = c->d.tau;
   a.conf_threshold = c->d.conf_threshold; a.gate_metric = c->d.gate_metric;
   a.schedule = c->d.schedule;
+  a.vocab = c->m.vocab;
   a.serial = c->serial = (c->serial == 0x7fffffff ? 1 : c->serial + 1);
 }
 
@@ -420,7 +421,7 @@ int forward_f32(ec_ctx* c, int mode, int M, int n_mb) {
   float* act = (float*)b.act; float* u_lm = (float*)b.u_lm;
   auto W = [](const void* p) { return (const float*)p; };
 
-  { Scope p(c, EC_K_EMBED); launch_embed_f32(W(c->w.tok_emb), b.x, rows, M, d, b.h, s); }
+  { Scope p(c, EC_K_EMBED); launch_embed_f32(W(c->w.tok_emb), b.x, rows, M, d, m.vocab, b.h, s); }
   for (int l = 0; l < m.n_layers; ++l) {
     float* kc = (float*)kv_ptr(c, l, 0); float* vc = (float*)kv_ptr(c, l, 1);
     { Scope p(c, EC_K_NORM);
@@ -471,6 +472,7 @@ int forward_bf16(ec_ctx* c, const StepPlan& sp) {
     StepLists sl{};
     sl.seqs = c->B == 1 ? nullptr : b.seqs; sl.seq0 = c->host_seqs[0]; sl.B = c->B; sl.R = R; sl.n_lm = sp.n_lm; sl.x = b.x;
     sl.rows_partial = b.rows_partial; sl.mb_pos = b.mb_pos; sl.mb_idx = b.mb_idx;
+    sl.vocab = m.vocab;
     sl.block = c->d.block; sl.rowinfo = b.rowinfo; sl.tileinfo = b.tileinfo; sl.lm_sel = b.lm_sel;
     launch_step_prologue_bf16(sl, G(c->w.tok_emb), d, G(c->attn_norm[0]), b.h, u, b.sumsq,
                               (2 * L + 1) * kSumSlots, b.sumsq_stride, s); }
@@ -690,6 +692,11 @@ int run_step(ec_ctx* c, const int32_t* modes, int modes_n, const int32_t* forced
     all_done &= c->done[b];
   }
   c->all_done = all_done;
+  for (int b = 0; b < B; ++b)
+    if (mode[b] >= 0 && c->host_out[b].nonfinite)
+      return fail(c, EC_ERR_NONFINITE,
+                  "a block row's logits had no finite maximum (sequence " + std::to_string(b) +
+                      "): the step's results are meaningless, reset before going on");
   return EC_OK;
 }
 
@@ -1040,6 +1047,7 @@ const char* ec_strerror(int code) {
     case EC_ERR_STATE: return "call not valid in the current state";
     case EC_ERR_HIP: return "HIP runtime error";
     case EC_ERR_HOST_MEMORY: return "out of host memory";
+    case EC_ERR_NONFINITE: return "logits without a finite maximum";
     default: return "unknown error code";
   }
 }

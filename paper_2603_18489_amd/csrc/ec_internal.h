@@ -46,7 +46,8 @@ struct StepOut {
   int next_n_mb;
   int next_n_rows_partial;
   int serial;   // the launch's DecideArgs::serial once everything above has been written
-  int pad[5];
+  int nonfinite;  // 1: some block row had no finite maximum logit (its token was forced to 0)
+  int pad[4];
 };
 
 // Arguments of the decision kernel: one block per sequence.  The pointers are those of sequence
@@ -82,6 +83,7 @@ struct DecideArgs {
   int gate_metric;         // EC_GATE_*
   int schedule;            // EC_SCHED_*
   int serial;              // written to StepOut::serial as the block's very last store (> 0)
+  int vocab;               // a row's argmax must lie in [0, vocab)
 };
 
 // thread-local message behind ec_last_error(NULL)
@@ -89,8 +91,8 @@ void set_global_error(const char* msg);
 
 // ---- launchers (each enqueues on `s`; shapes are validated by the caller) --------------------
 // float32 path
-void launch_embed_f32(const float* emb, const int* x, const int* rows, int M, int d, float* h,
-                      hipStream_t s);
+void launch_embed_f32(const float* emb, const int* x, const int* rows, int M, int d, int vocab,
+                      float* h, hipStream_t s);
 // out row r = rmsnorm(h row sel[r] (or r)) * gain
 void launch_rmsnorm_f32(const float* h, const int* sel, int M, int d, const float* gain, float eps,
                         float* out, hipStream_t s);
@@ -155,6 +157,7 @@ struct GemmEpi {
 struct StepLists {
   const SeqDesc* seqs; int B;   // seqs == NULL: a single sequence, described by seq0
   SeqDesc seq0;
+  int vocab;                    // token ids outside [0, vocab) are read as token 0
   int R, n_lm;                  // rows of the step (with padding); masked block rows
   const int* x;                 // concatenated by x_off, like rows_partial
   const int* rows_partial;

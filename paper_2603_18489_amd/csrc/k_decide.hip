@@ -130,6 +130,7 @@ __global__ __launch_bounds__(kDecideThreads) void decide_kernel(DecideArgs a) {
   }
   __shared__ int s_tok[EC_MAX_BLOCK], s_pos[EC_MAX_BLOCK];
   __shared__ float s_conf[EC_MAX_BLOCK], s_H[EC_MAX_BLOCK];
+  __shared__ int s_badrow[EC_MAX_BLOCK];  // 1: the row's logits had no finite maximum / sums
   __shared__ int s_sel[EC_MAX_N];    // block rows of the step's own choice, most confident first
   __shared__ int s_frow[EC_MAX_N];   // block rows of the caller's positions (-1: not in the block)
   __shared__ int scratch[kDecideWaves];
@@ -201,10 +202,18 @@ __global__ __launch_bounds__(kDecideThreads) void decide_kernel(DecideArgs a) {
       if (live && l32 == 0) {
         float conf, H;
         vt_finish(v, conf, H);
-        s_tok[row] = v.idx;
+        // A row of NaNs has no maximum: its index is still the sentinel, its sums are NaN.  The
+        // token becomes an index into the embedding table at the next step, so it must be a
+        // token; such a row counts as least confident and of infinite entropy, and is reported.
+        int tok = v.idx, bad = 0;
+        if ((unsigned)tok >= (unsigned)a.vocab) { tok = 0; bad = 1; }
+        if (!(v.s > 0.f) || !(conf >= 0.f) || !(v.t == v.t) || !(H >= 0.f)) bad = 1;
+        if (bad) { conf = 0.f; H = INFINITY; }  // (the clamp in vt_finish turns a NaN entropy into 0)
+        s_badrow[row] = bad;
+        s_tok[row] = tok;
         s_conf[row] = conf;
         s_H[row] = H;
-        *(float4*)(a.row_stats + row * 4) = make_float4((float)v.idx, conf, H, v.m);
+        *(float4*)(a.row_stats + row * 4) = make_float4((float)tok, conf, H, v.m);
       }
     }
     __syncthreads();
@@ -381,6 +390,10 @@ __global__ __launch_bounds__(kDecideThreads) void decide_kernel(DecideArgs a) {
     // The result sits in pinned host memory.  The other threads' entries were stored before the
     // barriers above; this fence orders them and the fields above before the serial number, so
     // a host that sees the number sees the whole result.
+    int bad = 0;
+    if (!a.init_only)
+      for (int r = 0; r < a.n_mb; ++r) bad |= s_badrow[r];
+    o.nonfinite = bad;
     __threadfence_system();
     __hip_atomic_store(&o.serial, a.serial, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
   }

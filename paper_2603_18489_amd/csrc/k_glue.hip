@@ -14,18 +14,20 @@ namespace ec {
 __global__ __launch_bounds__(256) void embed_f32_kernel(const float* __restrict__ emb,
                                                         const int* __restrict__ x,
                                                         const int* __restrict__ rows, int d,
-                                                        float* __restrict__ h) {
+                                                        int vocab, float* __restrict__ h) {
   int r = blockIdx.x;
   int pos = rows ? rows[r] : r;
-  const float* src = emb + (size_t)x[pos] * d;
+  int tok = x[pos];
+  if ((unsigned)tok >= (unsigned)vocab) tok = 0;  // (never index the table with a non-token)
+  const float* src = emb + (size_t)tok * d;
   float* dst = h + (size_t)r * d;
   for (int c = threadIdx.x; c < d; c += 256) dst[c] = src[c];
 }
 
-void launch_embed_f32(const float* emb, const int* x, const int* rows, int M, int d, float* h,
-                      hipStream_t s) {
+void launch_embed_f32(const float* emb, const int* x, const int* rows, int M, int d, int vocab,
+                      float* h, hipStream_t s) {
   if (M <= 0) return;
-  embed_f32_kernel<<<M, 256, 0, s>>>(emb, x, rows, d, h);
+  embed_f32_kernel<<<M, 256, 0, s>>>(emb, x, rows, d, vocab, h);
 }
 
 // bf16: the step's first kernel, one block per row of the step's row list.  It derives the
@@ -65,7 +67,9 @@ __global__ __launch_bounds__(256) void step_prologue_bf16_kernel(
   }
   __syncthreads();
   const int xidx = sh_xidx;
-  const bf16_t* src = emb + (size_t)(xidx >= 0 ? L.x[xidx] : 0) * d;
+  int tok = xidx >= 0 ? L.x[xidx] : 0;
+  if ((unsigned)tok >= (unsigned)L.vocab) tok = 0;  // (never index the table with a non-token)
+  const bf16_t* src = emb + (size_t)tok * d;
   float* dst = h + (size_t)r * d;
   float ss = 0.f;
   for (int c8 = threadIdx.x * 8; c8 < d; c8 += 256 * 8) {

@@ -204,3 +204,4 @@ def test_row_entropy_argument_errors_without_gpu(lib):
     assert call(z, 4, 4096, 4096, st, vp(0x300010), need, None) == ec.EC_ERR_WORKSPACE
     assert call(z, 32, 126464, 126464, st, ws, need - 256, None) == ec.EC_ERR_WORKSPACE
     assert len(lib.ec_strerror(ec.EC_ERR_HOST_MEMORY)) > 0
+    assert len(lib.ec_strerror(ec.EC_ERR_NONFINITE)) > 0

@@ -445,3 +445,38 @@ def test_e4m3_weight_batch():
     s = run_teacher_forced_batch(cfg, w, dec, prompts, TOL["fp8w"], max_steps=12)
     print(s)
     assert s["modes"][eco.PARTIAL] >= 1 and s["tokens_exact"] > 0
+
+
+@pytest.mark.parametrize("dtype,batch", [("bf16", 1), ("f32", 1), ("bf16", 3)])
+def test_rows_of_nan_logits_are_reported_and_nothing_leaves_its_buffers(dtype, batch):
+    """A model whose final norm gain is NaN: every logit is NaN, so no row has a maximum.  The
+    step must say so (EC_ERR_NONFINITE), the rows take token 0 (a row's token indexes the
+    embedding table at the next step), further steps and a generation run to their end the same
+    way, and a healthy context next to it is unaffected."""
+    cfg = small_cfg(dtype, 4, 2, 64)
+    good = ec_inputs.make_weights(cfg, 61, gain_jitter=0.1)
+    bad = dict(good)
+    bad["final_norm"] = good["final_norm"].copy()
+    if dtype == "f32":
+        bad["final_norm"][:] = np.nan
+    else:
+        bad["final_norm"][:] = 0x7FC0          # a bfloat16 NaN
+    dec = ec_inputs.DecodeCfg(gen_len=24, block=8, k_recent=2, tokens_per_step=2, tau=2.5, batch=batch)
+    prompts = [ec_inputs.make_prompt(cfg.vocab, 9 + 5 * b, 70 + b) for b in range(batch)]
+    g = ec.EntropyCache(cfg, ec.weights_to_device(cfg, bad), dec, prompts if batch > 1 else prompts[0])
+    for mode in (ec.EC_AUTO, ec.EC_AUTO, ec.EC_PARTIAL, ec.EC_FULL):
+        with pytest.raises(ec.EcError) as e:
+            g.step(mode)
+        assert e.value.code == ec.EC_ERR_NONFINITE
+        x = g.debug_read(ec.EC_DBG_X)
+        assert x.min() >= 0 and x.max() < cfg.vocab
+    stats = g.debug_read(ec.EC_DBG_ROW_STATS, count=1)
+    assert stats[0, 0] == 0 and stats[0, 1] == 0 and np.isinf(stats[0, 2])
+    with pytest.raises(ec.EcError) as e:
+        g.generate()
+    assert e.value.code == ec.EC_ERR_NONFINITE
+    g.close()
+    # the same shapes with finite weights still match the oracle
+    s = (run_teacher_forced(cfg, good, dec, prompts[0], TOL[dtype], max_steps=4) if batch == 1 else
+         run_teacher_forced_batch(cfg, good, dec, prompts, TOL[dtype], max_steps=4))
+    assert s["steps"] == 4
