@@ -221,6 +221,35 @@ def test_batched_generate_runs_every_sequence_to_the_end():
         g.close()
 
 
+def test_recompute_ratio_counter():
+    """RR = rows recomputed / (steps x T), the fraction of KV states recomputed per step: 1 when
+    the threshold lies below every entropy (all steps FULL); with a threshold nothing exceeds it
+    is one FULL step plus |M u R| <= block + k rows per step, and equals the oracle's count."""
+    cfg = small_cfg("f32", 4, 2, 64)
+    w = ec_inputs.make_weights(cfg, 67, gain_jitter=0.1)
+    prompt = ec_inputs.make_prompt(cfg.vocab, 40, 13)
+    dw = ec.weights_to_device(cfg, w)
+    T, N, block, k = 40 + 32, 32, 8, 2
+    for tau in (-1.0, 1e9):
+        dec = ec_inputs.DecodeCfg(gen_len=N, block=block, k_recent=k, tokens_per_step=1, tau=tau)
+        g = ec.EntropyCache(cfg, dw, dec, prompt)
+        try:
+            _, stats = g.generate()
+        finally:
+            g.close()
+        assert stats["steps"] == N
+        rr = stats["rows_recomputed"] / (stats["steps"] * T)
+        if tau < 0:
+            assert stats["full_steps"] == N and rr == 1.0
+        else:
+            assert stats["full_steps"] == 1 and stats["partial_steps"] == N - 1
+            rows_oracle = sum(len(r["S"]) for r in eco.eco_generate(
+                eco.eco_init(eco.OracleModel(cfg, w), dec, prompt)))
+            assert stats["rows_recomputed"] == rows_oracle
+            assert T < stats["rows_recomputed"] <= T + (N - 1) * (block + k)
+            assert rr < 0.25
+
+
 @pytest.mark.parametrize("dtype,P,N,block,k,n,tau", [
     ("f32", 0, 20, 8, 2, 1, 2.5),          # no prompt at all
     ("bf16", 3, 40, 128, 100, 32, 1e9),    # largest block and tokens per step, k beyond the generation
