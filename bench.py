@@ -74,6 +74,7 @@ def run_generation(g, prompt, mode_fn=None, max_steps=None, first_untimed=0):
     g.reset(prompt)
     modes = []
     toks = 0
+    rows = 0
     t0 = None
     while True:
         if len(modes) == first_untimed:
@@ -82,11 +83,13 @@ def run_generation(g, prompt, mode_fn=None, max_steps=None, first_untimed=0):
         mode = ec.EC_AUTO if mode_fn is None else mode_fn(len(modes))
         r = g.step(mode)
         modes.append(r["mode_run"])
+        rows += r["n_query_rows"]
         if len(modes) > first_untimed:
             toks += r["n_unmasked"]
         if r["done"] or (max_steps is not None and len(modes) >= max_steps):
             break
     torch.cuda.synchronize()
+    run_generation.last_rows = rows          # rows recomputed over all steps of this run
     return modes, toks, time.perf_counter() - (t0 if t0 is not None else time.perf_counter())
 
 
@@ -298,7 +301,9 @@ def main():
     gen_steps, gen_full = len(gen_modes), gen_modes.count(ec.EC_FULL)
     whole = {"steps": gen_steps, "full_steps": gen_full, "full_fraction": gen_full / gen_steps,
              "ms_per_step": gen_secs / gen_steps * 1e3, "tok_s": gen_toks / gen_secs,
-             "tokens": gen_toks}
+             "tokens": gen_toks,
+             # fraction of KV states recomputed per step (the paper's recompute ratio)
+             "recompute_ratio": run_generation.last_rows / (gen_steps * (len(prompt) + dec.gen_len))}
 
     # ---- timed region: exactly K consecutive free-running steps ---------------------------------
     K = args.steps
