@@ -69,7 +69,7 @@ class Counters:
                       "lnconf_vs_bound": 0.0, "reduce_H": 0.0, "reduce_conf": 0.0}
 
     def up(self, key, v):
-        self.worst[key] = max(self.worst[key], float(v))
+        self.worst[key] = max(self.worst.get(key, 0.0), float(v))
 
     def summary(self):
         return {"tokens_exact": self.tokens_exact, "choices_exact": self.choices_exact,

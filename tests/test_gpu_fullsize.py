@@ -125,9 +125,21 @@ def check_trace_step(cfg, dec, gold, st, arr, key, q, g, cnt, seq, where):
     for li, l in enumerate(gold["layers"]):
         for name, which in (("K", ec.EC_DBG_KCACHE), ("V", ec.EC_DBG_VCACHE)):
             c = gpu_cache(g, which, l, seq=seq)[pos][:, gold["heads"], :]
-            e = float(np.abs(c - arr[key + name][li]).max() / st[name + "_absmax"][li])
+            ref_kv = arr[key + name][li]
+            e = float(np.abs(c - ref_kv).max() / st[name + "_absmax"][li])
             cnt.up(name, e)
             assert e <= TOL, f"{where} layer {l}: {name} rel err {e:.3e}"
+            # and every sampled (position, head) vector against its own largest magnitude: an
+            # error confined to a few rows or heads cannot hide behind the layer's maximum
+            ev = float((np.abs(c - ref_kv).max(axis=-1) / np.abs(ref_kv).max(axis=-1)).max())
+            cnt.up(name + "_vec", ev)
+            assert ev <= VEC_TOL, f"{where} layer {l}: {name} vector rel err {ev:.3e}"
+
+
+# A sampled (position, head) vector's own largest magnitude can lie several times below its
+# layer's, so the same absolute error reads larger against it: 4 x the tensor bar (observed:
+# up to 0.041 at 32 layers, 0.01 - 0.02 on the 2-layer batch trace).
+VEC_TOL = 4 * TOL
 
 
 def load_trace(name):
