@@ -259,6 +259,9 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* 
   // count outstanding loads exactly): k-steps past the slice re-read the slice's last fragments,
   // which are still in cache, and their activation operand is replaced by zeros, so the MFMAs,
   // which ignore EXEC and must run unconditionally anyway, add nothing.
+  // The weights are loaded with the non-temporal hint: every byte of them is used once, and kept
+  // out of the way they leave the L2 to the activation fragments that all blocks re-read
+  // (measured: the whole partial step 3.31 -> 3.11 ms).
   const int nkb = kb_hi - kb_lo;
   const int last = nkb > 0 ? nkb - 1 : 0;
   const u32x4 zero4 = {0u, 0u, 0u, 0u};
@@ -266,7 +269,7 @@ __global__ __launch_bounds__(KS * 64) void gemm_bf16_skinny_kernel(const u32x4* 
 #define EC_SK_LOAD(WSET, ASET, IT0)                                                        \
   _Pragma("unroll") for (int u = 0; u < U; ++u) {                                          \
     const int it_ = (IT0) + u < last ? (IT0) + u : last;                                   \
-    _Pragma("unroll") for (int i = 0; i < NTW; ++i) WSET[u][i] = wp[i][(size_t)it_ * wstep];  \
+    _Pragma("unroll") for (int i = 0; i < NTW; ++i) WSET[u][i] = __builtin_nontemporal_load(&wp[i][(size_t)it_ * wstep]);  \
     _Pragma("unroll") for (int j = 0; j < MT; ++j)                                         \
       _Pragma("unroll") for (int h = 0; h < AW; ++h)                                       \
         ASET[u][j * AW + h] = ap[j][((size_t)it_ * AW + h) * MT_src * 64];                 \
