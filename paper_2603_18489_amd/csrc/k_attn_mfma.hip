@@ -398,7 +398,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_shared_kernel(
       __builtin_amdgcn_global_load_lds(
           (const void __attribute__((address_space(1)))*)src,
           (void __attribute__((address_space(3)))*)(ring + ((size_t)stage * NFRAG + f) * 64), 16,
-          0, 0);
+          0, FEW ? 2 : 0);  // (few-row batches read every K/V byte once: non-temporal)
     }
   };
 
